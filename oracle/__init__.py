@@ -1,0 +1,157 @@
+"""CPU oracle for batched IVF-Flat search.  TEST INFRASTRUCTURE ONLY.
+
+Thin ctypes wrapper around ``ivf_oracle.c`` (plain C, double accumulation,
+query-major; see the header of that file for the conventions and the passages
+of the paper it follows).  Only ``tests/``, ``__graft_entry__.smoke()`` and the
+``cpu_baseline`` leg of ``bench.py`` may import this package.  It imports
+nothing from the HIP package and the HIP package imports nothing from here.
+
+Arrays are numpy.  Stored vectors are passed as ``float32``, ``float16`` or, for
+bfloat16, as the ``uint16`` bit patterns together with ``dtype="bf16"``.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "ivf_oracle.c")
+_LIB = os.path.join(_HERE, "libivf_oracle.so")
+
+IP, L2 = 0, 1
+_DTYPES = {"f32": 0, "f16": 1, "bf16": 2}
+
+_lib = None
+
+
+def build(force=False):
+    """Compile the oracle with gcc (-O2, OpenMP, no fast-math so that the
+    summation order is the one written in the source)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+               "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        c = ctypes
+        p = c.c_void_p
+        lib.oracle_num_threads.restype = c.c_int
+        lib.oracle_coarse.argtypes = [p, c.c_int64, p, c.c_int64, c.c_int, c.c_int, c.c_int, p, p]
+        lib.oracle_scan.argtypes = [p, c.c_int64, c.c_int, p, c.c_int64, p, c.c_int, p, p,
+                                    c.c_int, c.c_int, c.c_int, p, p]
+        lib.oracle_ivf_search.argtypes = [p, c.c_int64, c.c_int, p, p, c.c_int64, p, c.c_int, p,
+                                          c.c_int, c.c_int, c.c_int, p, p, p]
+        lib.oracle_bruteforce.argtypes = [p, c.c_int64, c.c_int, p, c.c_int, p, c.c_int64,
+                                          c.c_int, c.c_int, p, p]
+        lib.oracle_pair_scores.argtypes = [p, c.c_int, p, c.c_int, c.c_int, p, p, c.c_int64, p]
+        _lib = lib
+    return _lib
+
+
+def num_threads():
+    return int(_load().oracle_num_threads())
+
+
+def _ptr(a):
+    return ctypes.c_void_p(a.ctypes.data)
+
+
+def _as(a, dt):
+    a = np.ascontiguousarray(a)
+    if a.dtype != dt:
+        raise TypeError(f"expected {dt}, got {a.dtype}")
+    return a
+
+
+def _vectors(vectors, dtype):
+    code = _DTYPES[dtype]
+    want = {0: np.float32, 1: np.float16, 2: np.uint16}[code]
+    return _as(vectors, want), code
+
+
+def _check(rc, name):
+    if rc != 0:
+        raise RuntimeError(f"{name} failed with code {rc}")
+
+
+def coarse(queries, centroids, nprobe, metric):
+    """Returns (probe_ids [nq,nprobe] int32 best-first, scores [nq,nprobe] float64)."""
+    q = _as(queries, np.float32)
+    c = _as(centroids, np.float32)
+    nq, d = q.shape
+    nlist = c.shape[0]
+    assert c.shape[1] == d
+    probe = np.empty((nq, nprobe), np.int32)
+    sc = np.empty((nq, nprobe), np.float64)
+    _check(_load().oracle_coarse(_ptr(q), nq, _ptr(c), nlist, d, metric, nprobe, _ptr(probe),
+                                 _ptr(sc)), "oracle_coarse")
+    return probe, sc
+
+
+def scan(queries, offsets, vectors, dtype, ids, probe, k, metric):
+    """Fine step with given probe lists.  Returns (ids [nq,k] int64, scores [nq,k] float64)."""
+    q = _as(queries, np.float32)
+    off = _as(offsets, np.int64)
+    v, code = _vectors(vectors, dtype)
+    lab = _as(ids, np.int64)
+    pr = _as(probe, np.int32)
+    nq, d = q.shape
+    assert pr.shape[0] == nq and v.shape[1] == d and lab.shape[0] == v.shape[0]
+    assert off[0] == 0 and off[-1] == v.shape[0]
+    out_i = np.empty((nq, k), np.int64)
+    out_s = np.empty((nq, k), np.float64)
+    _check(_load().oracle_scan(_ptr(q), nq, d, _ptr(off), off.shape[0] - 1, _ptr(v), code,
+                               _ptr(lab), _ptr(pr), pr.shape[1], k, metric, _ptr(out_i),
+                               _ptr(out_s)), "oracle_scan")
+    return out_i, out_s
+
+
+def ivf_search(queries, centroids, offsets, vectors, dtype, ids, nprobe, k, metric):
+    """Whole search.  Returns (probe_ids, ids, scores)."""
+    q = _as(queries, np.float32)
+    c = _as(centroids, np.float32)
+    off = _as(offsets, np.int64)
+    v, code = _vectors(vectors, dtype)
+    lab = _as(ids, np.int64)
+    nq, d = q.shape
+    nlist = c.shape[0]
+    assert off.shape[0] == nlist + 1 and off[0] == 0 and off[-1] == v.shape[0]
+    probe = np.empty((nq, nprobe), np.int32)
+    out_i = np.empty((nq, k), np.int64)
+    out_s = np.empty((nq, k), np.float64)
+    _check(_load().oracle_ivf_search(_ptr(q), nq, d, _ptr(c), _ptr(off), nlist, _ptr(v), code,
+                                     _ptr(lab), nprobe, k, metric, _ptr(probe), _ptr(out_i),
+                                     _ptr(out_s)), "oracle_ivf_search")
+    return probe, out_i, out_s
+
+
+def bruteforce(queries, vectors, dtype, ids, k, metric):
+    """Exact search over all rows.  Returns (ids [nq,k], scores [nq,k] float64)."""
+    q = _as(queries, np.float32)
+    v, code = _vectors(vectors, dtype)
+    lab = _as(ids, np.int64)
+    nq, d = q.shape
+    out_i = np.empty((nq, k), np.int64)
+    out_s = np.empty((nq, k), np.float64)
+    _check(_load().oracle_bruteforce(_ptr(q), nq, d, _ptr(v), code, _ptr(lab), v.shape[0], k,
+                                     metric, _ptr(out_i), _ptr(out_s)), "oracle_bruteforce")
+    return out_i, out_s
+
+
+def pair_scores(queries, vectors, dtype, metric, qidx, ridx):
+    """Scores of chosen (query, row) pairs, float64."""
+    q = _as(queries, np.float32)
+    v, code = _vectors(vectors, dtype)
+    qi = _as(np.asarray(qidx, np.int64), np.int64)
+    ri = _as(np.asarray(ridx, np.int64), np.int64)
+    out = np.empty(qi.shape[0], np.float64)
+    _check(_load().oracle_pair_scores(_ptr(q), q.shape[1], _ptr(v), code, metric, _ptr(qi),
+                                      _ptr(ri), qi.shape[0], _ptr(out)), "oracle_pair_scores")
+    return out
