@@ -1,0 +1,137 @@
+"""Benchmark of the batched IVF search hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C3] [--no-cpu-baseline]
+
+One step = one hr_ivf_search call (coarse scoring, top-nprobe, grouping by list, cluster-major
+scan, per-query merge) over one batch of synthetic queries, index and queries resident in HBM.
+Prints one JSON line: queries/s, plus the roofline of the list-scan kernel (algorithmic bytes
+of the probed lists / its average duration, measured with HIP events around its launches) and
+the CPU oracle timed on a bounded sample of the same batch.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+MFMA_PEAK_TFLOPS = {"f16": 2500.0, "bf16": 2500.0, "f32": 2500.0}   # f32 rows run as binary16 pairs
+ESIZE = {"f32": 4, "f16": 2, "bf16": 2}
+
+
+def cpu_baseline(cfg, idx, q, target_s=15.0):
+    """The oracle as it stands, on the host cores, on a sample sized for about target_s seconds."""
+    import numpy as np
+    import oracle
+    import synth
+    cent = synth.to_numpy(idx.centroids)
+    off = synth.to_numpy(idx.list_offsets)
+    vec = synth.to_numpy(idx.list_vectors)
+    ids = synth.to_numpy(idx.list_ids)
+    qh = synth.to_numpy(q)
+    m = oracle.IP if cfg.metric == "ip" else oracle.L2
+    threads = oracle.num_threads()
+    rng = np.random.default_rng(7)
+    order = rng.permutation(qh.shape[0])
+    n0 = min(len(order), max(threads, 8))
+    t0 = time.time()
+    oracle.ivf_search(np.ascontiguousarray(qh[order[:n0]]), cent, off, vec, cfg.dtype, ids, cfg.nprobe, cfg.k, m)
+    t_pilot = time.time() - t0
+    n1 = int(min(len(order) - n0, max(0, (target_s - t_pilot) / max(t_pilot / n0, 1e-9))))
+    n1 -= n1 % threads if n1 > threads else 0
+    total_t, total_n = t_pilot, n0
+    if n1 > 0:
+        t0 = time.time()
+        oracle.ivf_search(np.ascontiguousarray(qh[order[n0:n0 + n1]]), cent, off, vec, cfg.dtype, ids,
+                          cfg.nprobe, cfg.k, m)
+        total_t += time.time() - t0
+        total_n += n1
+    return {"value": total_n / total_t, "unit": "queries/s", "cores": threads, "kind": "oracle",
+            "sample": f"{total_n} randomly chosen queries of the batch (full index, nprobe={cfg.nprobe}, "
+                      f"k={cfg.k}), {total_t:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="C3")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
+
+    import torch
+    import paper_2507_09138_amd as hr
+    import synth
+
+    cfg = synth.CONFIGS[args.workload]
+    torch.cuda.set_device(0)
+    idx = synth.make_index(cfg, "cuda")
+    rounds = synth.make_queries(cfg, idx)
+    ix = hr.IvfIndex(idx.centroids, idx.list_offsets, idx.list_vectors, idx.list_ids)
+    nq = cfg.nq
+    metric = hr.HR_METRIC_IP if cfg.metric == "ip" else hr.HR_METRIC_L2
+    ids = torch.empty(nq, cfg.k, dtype=torch.int64, device="cuda")
+    scores = torch.empty(nq, cfg.k, dtype=torch.float32, device="cuda")
+    ws = ix.workspace(nq, cfg.nprobe, cfg.k)
+
+    def step(i):
+        q = rounds[i % len(rounds)]
+        hr.hr_ivf_search(ix.handle, q, nq, cfg.nprobe, cfg.k, metric, ids, scores, ws, ws.numel())
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    hr.hr_ivf_profile_begin(ix.handle, args.steps)
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    n_timed, scan_ms = hr.hr_ivf_profile_end(ix.handle)
+    ms_per_step = dt / args.steps * 1e3
+    st = ix.stats(nq, cfg.nprobe, cfg.k)
+
+    # work of the last step, from its probe lists (host arithmetic on the coarse output)
+    probe, _ = ix.coarse(rounds[(args.steps - 1) % len(rounds)], cfg.nprobe, cfg.metric)
+    w = torch.bincount(probe.flatten().long(), minlength=cfg.nlist).cpu()
+    lens = idx.list_offsets[1:] - idx.list_offsets[:-1]
+    pair_rows = int((w * lens).sum())
+    rows_streamed = int(lens[w > 0].sum())
+    assert rows_streamed == st["rows_streamed"], (rows_streamed, st)
+    scan_bytes = rows_streamed * cfg.d * ESIZE[cfg.dtype]
+    scan_flops = 2.0 * cfg.d * pair_rows
+    achieved = scan_bytes / (scan_ms * 1e-3) / 1e9 if scan_ms > 0 else 0.0
+
+    out = {
+        "metric": "queries/sec batched IVF top-k search", "value": nq / (ms_per_step * 1e-3),
+        "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": {"f16": "f16", "bf16": "bf16", "f32": "f16x2"}[cfg.dtype] + " operands, f32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: N={cfg.N}, d={cfg.d}, nlist={cfg.nlist}, nq={nq}, "
+                               f"nprobe={cfg.nprobe}, k={cfg.k}, {cfg.dtype} storage, {cfg.metric}",
+                   "rounds": cfg.rounds, "scan_items": st["items"], "seg_rows": st["seg_rows"],
+                   "pairs": st["pairs"]},
+        "roofline": {"bound": "hbm", "kernel": "k_scan (list scan)", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": None, "scan_ms_avg": scan_ms, "launches_timed": n_timed,
+                     "algorithmic_bytes_per_launch": scan_bytes,
+                     "mfma_tflops": scan_flops / (scan_ms * 1e-3) / 1e12 if scan_ms > 0 else 0.0,
+                     "mfma_frac": (scan_flops / (scan_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS[cfg.dtype])
+                     if scan_ms > 0 else 0.0},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, idx, rounds[0])
+    ix.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

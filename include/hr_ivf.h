@@ -1,0 +1,153 @@
+/*
+ * hr_ivf.h — C ABI of the MI355X (gfx950) batched IVF-Flat top-k search.
+ *
+ * The operation is the retrieval stage of the paper (Section 2.2): similarity
+ * (inner product on caller-normalised vectors, or squared L2 distance) between
+ * each query and the stored vectors, restricted to the nprobe clusters whose
+ * centroids are closest to the query, top-k nearest returned.  A call handles a
+ * whole batch of queries; queries that probe the same inverted list share one
+ * pass over it (the cross-request, variable-length cluster search of Section 5,
+ * with the per-request merge of Section 4.4).
+ *
+ * Pointers marked DEV are device (HBM) addresses on the current HIP device;
+ * HOST are ordinary host addresses.  No call takes ownership of caller memory.
+ * Every function returns HR_OK (0) or a negative error code; nothing is thrown
+ * and nothing aborts.  On any error other than HR_ERR_HIP nothing was enqueued
+ * and outputs are untouched.  hr_last_error() gives a message for the last
+ * failing call on the calling thread.
+ *
+ * Result convention: row q of the outputs is sorted best-first (inner product
+ * descending, L2 ascending; equal scores by ascending id).  If fewer than k
+ * candidates exist, ids are padded with -1 and scores with -inf (IP) / +inf (L2).
+ * Same inputs give bit-identical outputs on every run.
+ */
+#ifndef HR_IVF_H
+#define HR_IVF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct hr_ivf_index hr_ivf_index; /* opaque */
+
+enum { HR_METRIC_IP = 0, HR_METRIC_L2 = 1 };      /* L2 = squared distance, smaller is better */
+enum { HR_F32 = 0, HR_F16 = 1, HR_BF16 = 2 };     /* storage type of list_vectors only */
+enum {
+    HR_OK = 0,
+    HR_ERR_ARG = -1,          /* null pointer, size or enum out of range, offsets not monotone */
+    HR_ERR_HANDLE = -2,       /* index handle null, freed or corrupt */
+    HR_ERR_WORKSPACE = -3,    /* workspace null, misaligned or smaller than hr_ivf_workspace_bytes */
+    HR_ERR_HIP = -4,          /* a HIP runtime call failed (message in hr_last_error) */
+    HR_ERR_UNSUPPORTED = -5   /* valid request outside what the kernels are built for */
+};
+
+#define HR_K_MAX 128          /* largest k */
+#define HR_NPROBE_MAX 128     /* largest nprobe */
+#define HR_WORKSPACE_ALIGN 256
+
+/*
+ * hr_ivf_load — wrap an IVF-Flat index that already lives in HBM (Section 2.2: vectors
+ * partitioned into clusters, each represented by a centroid).
+ *   centroids     DEV  [nlist, d] float32, row-major.
+ *   list_offsets  HOST [nlist+1] int64; list l holds rows list_offsets[l] .. list_offsets[l+1]-1;
+ *                 list_offsets[0] = 0, list_offsets[nlist] = N, non-decreasing (empty lists allowed).
+ *                 Copied during the call.
+ *   list_vectors  DEV  [N, d] row-major in `dtype` (HR_F32 / HR_F16 / HR_BF16), list-major.
+ *   list_ids      DEV  [N] int64, the label reported for each row (any values; ties between equal
+ *                 scores are broken by ascending label).
+ *   d             supported: 64, 128, 256, 512, 768, 1024 (else HR_ERR_UNSUPPORTED).
+ *   N < 2^31.  Values must be finite and, for HR_F32 storage and for centroids/queries, of
+ *   magnitude below 65504 (they pass through binary16 pairs inside the kernels).
+ *   stream        hipStream_t (as void*) on which the derived tables are computed.
+ * centroids, list_vectors and list_ids are BORROWED: they must stay valid and unchanged until
+ * hr_ivf_free.  The library allocates (hipMalloc) only small derived tables: device copies of
+ * the offsets and 4 bytes per row / per centroid of squared norms.  The call synchronises
+ * `stream` before returning.
+ */
+int hr_ivf_load(const float* centroids, const int64_t* list_offsets, const void* list_vectors,
+                const int64_t* list_ids, int64_t nlist, int64_t N, int32_t d, int32_t dtype,
+                void* stream, hr_ivf_index** out);
+
+/* Releases the derived tables.  The handle is invalid afterwards (HR_ERR_HANDLE if reused). */
+int hr_ivf_free(hr_ivf_index* index);
+
+/*
+ * Bytes of DEV scratch that hr_ivf_search / hr_ivf_coarse / hr_ivf_scan need for this batch
+ * shape; 0 on invalid arguments.  Depends only on (index, nq, nprobe, k), never on the data.
+ */
+size_t hr_ivf_workspace_bytes(const hr_ivf_index* index, int64_t nq, int32_t nprobe, int32_t k);
+
+/*
+ * hr_ivf_search — the whole hot path for one batch: coarse scoring of queries against the
+ * centroids, top-nprobe selection, grouping of (query, list) probes by list, cluster-major
+ * scan with per-query top-k merge (Sections 2.2, 5 and 4.4 of the paper).
+ *   queries     DEV  [nq, d] float32 row-major.   nq >= 0 (0 is a no-op).
+ *   nprobe      1 .. min(nlist, HR_NPROBE_MAX);   k  1 .. HR_K_MAX.
+ *   metric      HR_METRIC_IP or HR_METRIC_L2; the coarse step uses the same metric.
+ *   out_ids     DEV  [nq, k] int64;   out_scores  DEV [nq, k] float32.
+ *   workspace   DEV, HR_WORKSPACE_ALIGN-aligned, >= hr_ivf_workspace_bytes(...) bytes; contents
+ *               are scratch.  Two calls that overlap in time must not share a workspace.
+ *   stream      hipStream_t (as void*).  The call only enqueues kernels on it: no allocation,
+ *               no host synchronisation; outputs are valid once the stream reaches that point.
+ */
+int hr_ivf_search(const hr_ivf_index* index, const float* queries, int64_t nq, int32_t nprobe,
+                  int32_t k, int32_t metric, int64_t* out_ids, float* out_scores,
+                  void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * hr_ivf_coarse — first half only (Section 2.2: "the nprobe closest clusters are selected").
+ *   out_probe_ids     DEV [nq, nprobe] int32, best-first (ties: lower list number first).
+ *   out_probe_scores  DEV [nq, nprobe] float32 or NULL.
+ */
+int hr_ivf_coarse(const hr_ivf_index* index, const float* queries, int64_t nq, int32_t nprobe,
+                  int32_t metric, int32_t* out_probe_ids, float* out_probe_scores,
+                  void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * hr_ivf_scan — second half only, with the probe lists given by the caller: the step-wise,
+ * variable-length cluster search of Section 5 (a scheduler hands each query the clusters it
+ * wants searched in this step).
+ *   probe_ids  DEV [nq, nprobe] int32.  An entry < 0 or >= nlist means "no list here", which
+ *              gives queries probe lists of different lengths.  A list must not appear twice
+ *              in one query's row (its vectors would be reported twice).
+ */
+int hr_ivf_scan(const hr_ivf_index* index, const float* queries, int64_t nq,
+                const int32_t* probe_ids, int32_t nprobe, int32_t k, int32_t metric,
+                int64_t* out_ids, float* out_scores, void* workspace, size_t workspace_bytes,
+                void* stream);
+
+/*
+ * hr_ivf_stats — host-side facts about the last hr_ivf_search / hr_ivf_scan enqueued with this
+ * workspace, read back AFTER the caller has synchronised the stream (this call does a small
+ * blocking device-to-host copy).  out[0] = work items of the list scan, out[1] = rows per
+ * segment chosen for this batch, out[2] = sum over probed lists of their row counts (rows
+ * streamed once each), out[3] = number of (query, list) pairs.  For benchmarks and tests.
+ */
+int hr_ivf_stats(const hr_ivf_index* index, const void* workspace, size_t workspace_bytes,
+                 int64_t nq, int32_t nprobe, int32_t k, int64_t out[4]);
+
+/*
+ * Kernel timing for benchmarks.  hr_ivf_profile_begin creates max_calls pairs of HIP events
+ * (no device memory); from then on every hr_ivf_search / hr_ivf_scan records one pair on its
+ * stream immediately before and after the list-scan kernel (the dominant kernel), until
+ * max_calls pairs are used.  hr_ivf_profile_end waits for the recorded events, returns the
+ * number of timed launches in *n and their average duration in milliseconds in *scan_ms_avg
+ * (0 if none), destroys the events and switches timing off.  Not thread-safe with concurrent
+ * searches on the same index.
+ */
+int hr_ivf_profile_begin(hr_ivf_index* index, int32_t max_calls);
+int hr_ivf_profile_end(hr_ivf_index* index, int32_t* n, double* scan_ms_avg);
+
+/* Message for the last error on this thread (static storage, never NULL). */
+const char* hr_last_error(void);
+
+/* Library version string, e.g. "hr_ivf 0.1 gfx950". */
+const char* hr_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HR_IVF_H */

@@ -1,0 +1,205 @@
+"""ctypes binding with the same names as the C entry points of hr_ivf.h.
+
+The low-level functions take raw addresses / torch tensors and return the C return code's
+meaning as an exception (HrError) when it is not HR_OK.  ``IvfIndex`` is a small convenience
+wrapper that keeps the borrowed tensors alive and owns a workspace tensor.
+
+The library must have been built (``python -m paper_2507_09138_amd.build``); there is no
+fallback: if ``libhr_ivf.so`` is missing, importing this module raises.
+"""
+import ctypes
+import os
+
+import torch
+
+HR_METRIC_IP, HR_METRIC_L2 = 0, 1
+HR_F32, HR_F16, HR_BF16 = 0, 1, 2
+HR_K_MAX, HR_NPROBE_MAX = 128, 128
+_ERR = {-1: "HR_ERR_ARG", -2: "HR_ERR_HANDLE", -3: "HR_ERR_WORKSPACE", -4: "HR_ERR_HIP",
+        -5: "HR_ERR_UNSUPPORTED"}
+_DTYPE = {torch.float32: HR_F32, torch.float16: HR_F16, torch.bfloat16: HR_BF16}
+_METRIC = {"ip": HR_METRIC_IP, "l2": HR_METRIC_L2, 0: 0, 1: 1}
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+lib_path = os.path.join(_HERE, "libhr_ivf.so")
+
+
+class HrError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"{_ERR.get(code, code)}: {msg}")
+        self.code = code
+
+
+def _load_lib():
+    if not os.path.exists(lib_path):
+        raise ImportError(f"{lib_path} not built; run `python -m paper_2507_09138_amd.build`")
+    L = ctypes.CDLL(lib_path)
+    c, p = ctypes, ctypes.c_void_p
+    L.hr_ivf_load.argtypes = [p, p, p, p, c.c_int64, c.c_int64, c.c_int32, c.c_int32, p, c.POINTER(p)]
+    L.hr_ivf_free.argtypes = [p]
+    L.hr_ivf_workspace_bytes.argtypes = [p, c.c_int64, c.c_int32, c.c_int32]
+    L.hr_ivf_workspace_bytes.restype = c.c_size_t
+    L.hr_ivf_search.argtypes = [p, p, c.c_int64, c.c_int32, c.c_int32, c.c_int32, p, p, p, c.c_size_t, p]
+    L.hr_ivf_coarse.argtypes = [p, p, c.c_int64, c.c_int32, c.c_int32, p, p, p, c.c_size_t, p]
+    L.hr_ivf_scan.argtypes = [p, p, c.c_int64, p, c.c_int32, c.c_int32, c.c_int32, p, p, p, c.c_size_t, p]
+    L.hr_ivf_stats.argtypes = [p, p, c.c_size_t, c.c_int64, c.c_int32, c.c_int32, c.POINTER(c.c_int64)]
+    L.hr_ivf_profile_begin.argtypes = [p, c.c_int32]
+    L.hr_ivf_profile_end.argtypes = [p, c.POINTER(c.c_int32), c.POINTER(c.c_double)]
+    L.hr_last_error.restype = c.c_char_p
+    L.hr_version.restype = c.c_char_p
+    return L
+
+
+lib = _load_lib()
+
+
+def hr_last_error():
+    return lib.hr_last_error().decode()
+
+
+def hr_version():
+    return lib.hr_version().decode()
+
+
+def _check(rc):
+    if rc != 0:
+        raise HrError(rc, hr_last_error())
+
+
+def _addr(t):
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return ctypes.c_void_p(t)
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    if isinstance(stream, int):
+        return ctypes.c_void_p(stream)
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def hr_ivf_load(centroids, list_offsets, list_vectors, list_ids, nlist, N, d, dtype, stream=None):
+    """list_offsets: host int64 tensor; the others device tensors (or raw addresses)."""
+    h = ctypes.c_void_p()
+    _check(lib.hr_ivf_load(_addr(centroids), _addr(list_offsets), _addr(list_vectors),
+                           _addr(list_ids), nlist, N, d, dtype, _stream(stream), ctypes.byref(h)))
+    return h
+
+
+def hr_ivf_free(handle):
+    _check(lib.hr_ivf_free(handle))
+
+
+def hr_ivf_workspace_bytes(handle, nq, nprobe, k):
+    return int(lib.hr_ivf_workspace_bytes(handle, nq, nprobe, k))
+
+
+def hr_ivf_search(handle, queries, nq, nprobe, k, metric, out_ids, out_scores, workspace,
+                  workspace_bytes, stream=None):
+    _check(lib.hr_ivf_search(handle, _addr(queries), nq, nprobe, k, metric, _addr(out_ids),
+                             _addr(out_scores), _addr(workspace), workspace_bytes, _stream(stream)))
+
+
+def hr_ivf_coarse(handle, queries, nq, nprobe, metric, out_probe_ids, out_probe_scores, workspace,
+                  workspace_bytes, stream=None):
+    _check(lib.hr_ivf_coarse(handle, _addr(queries), nq, nprobe, metric, _addr(out_probe_ids),
+                             _addr(out_probe_scores), _addr(workspace), workspace_bytes,
+                             _stream(stream)))
+
+
+def hr_ivf_scan(handle, queries, nq, probe_ids, nprobe, k, metric, out_ids, out_scores, workspace,
+                workspace_bytes, stream=None):
+    _check(lib.hr_ivf_scan(handle, _addr(queries), nq, _addr(probe_ids), nprobe, k, metric,
+                           _addr(out_ids), _addr(out_scores), _addr(workspace), workspace_bytes,
+                           _stream(stream)))
+
+
+def hr_ivf_stats(handle, workspace, workspace_bytes, nq, nprobe, k):
+    out = (ctypes.c_int64 * 4)()
+    _check(lib.hr_ivf_stats(handle, _addr(workspace), workspace_bytes, nq, nprobe, k, out))
+    return {"items": out[0], "seg_rows": out[1], "rows_streamed": out[2], "pairs": out[3]}
+
+
+def hr_ivf_profile_begin(handle, max_calls):
+    _check(lib.hr_ivf_profile_begin(handle, max_calls))
+
+
+def hr_ivf_profile_end(handle):
+    n = ctypes.c_int32()
+    ms = ctypes.c_double()
+    _check(lib.hr_ivf_profile_end(handle, ctypes.byref(n), ctypes.byref(ms)))
+    return n.value, ms.value
+
+
+class IvfIndex:
+    """Keeps the borrowed tensors alive, owns the handle and a growable workspace tensor."""
+
+    def __init__(self, centroids, list_offsets, list_vectors, list_ids):
+        assert centroids.is_cuda and list_vectors.is_cuda and list_ids.is_cuda
+        assert centroids.dtype == torch.float32 and list_ids.dtype == torch.int64
+        self.centroids = centroids.contiguous()
+        self.list_offsets = list_offsets.to("cpu", torch.int64).contiguous()
+        self.list_vectors = list_vectors.contiguous()
+        self.list_ids = list_ids.contiguous()
+        self.nlist, self.d = self.centroids.shape
+        self.N = self.list_vectors.shape[0]
+        self.dtype = _DTYPE[self.list_vectors.dtype]
+        self.handle = hr_ivf_load(self.centroids, self.list_offsets, self.list_vectors,
+                                  self.list_ids, self.nlist, self.N, self.d, self.dtype)
+        self._ws = None
+
+    def close(self):
+        if self.handle is not None:
+            torch.cuda.synchronize()
+            hr_ivf_free(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def workspace(self, nq, nprobe, k):
+        need = hr_ivf_workspace_bytes(self.handle, nq, nprobe, k)
+        if need == 0 and nq > 0:
+            raise HrError(-1, hr_last_error())
+        if self._ws is None or self._ws.numel() < need:
+            self._ws = torch.empty(max(need, 256), dtype=torch.uint8, device=self.centroids.device)
+        return self._ws
+
+    def search(self, queries, nprobe, k, metric="ip"):
+        q = queries.contiguous()
+        nq = q.shape[0]
+        ids = torch.empty(nq, k, dtype=torch.int64, device=q.device)
+        scores = torch.empty(nq, k, dtype=torch.float32, device=q.device)
+        ws = self.workspace(nq, nprobe, k)
+        hr_ivf_search(self.handle, q, nq, nprobe, k, _METRIC[metric], ids, scores, ws, ws.numel())
+        return ids, scores
+
+    def coarse(self, queries, nprobe, metric="ip"):
+        q = queries.contiguous()
+        nq = q.shape[0]
+        probe = torch.empty(nq, nprobe, dtype=torch.int32, device=q.device)
+        scores = torch.empty(nq, nprobe, dtype=torch.float32, device=q.device)
+        ws = self.workspace(nq, nprobe, 1)
+        hr_ivf_coarse(self.handle, q, nq, nprobe, _METRIC[metric], probe, scores, ws, ws.numel())
+        return probe, scores
+
+    def scan(self, queries, probe_ids, k, metric="ip"):
+        q = queries.contiguous()
+        pr = probe_ids.to(torch.int32).contiguous()
+        nq, nprobe = pr.shape
+        ids = torch.empty(nq, k, dtype=torch.int64, device=q.device)
+        scores = torch.empty(nq, k, dtype=torch.float32, device=q.device)
+        ws = self.workspace(nq, nprobe, k)
+        hr_ivf_scan(self.handle, q, nq, pr, nprobe, k, _METRIC[metric], ids, scores, ws, ws.numel())
+        return ids, scores
+
+    def stats(self, nq, nprobe, k):
+        ws = self.workspace(nq, nprobe, k)
+        return hr_ivf_stats(self.handle, ws, ws.numel(), nq, nprobe, k)

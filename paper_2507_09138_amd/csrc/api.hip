@@ -1,0 +1,481 @@
+// Host side of the C ABI declared in hr_ivf.h: argument checks, workspace layout, launch
+// sequence.  Nothing here synchronises the caller's stream except hr_ivf_load and hr_ivf_stats.
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "common.h"
+
+namespace hr {
+hipError_t launch_scan_f32(int d, const ScanArgs& a, int grid, size_t lds, hipStream_t s);
+hipError_t launch_scan_f16(int d, const ScanArgs& a, int grid, size_t lds, hipStream_t s);
+hipError_t launch_scan_bf16(int d, const ScanArgs& a, int grid, size_t lds, hipStream_t s);
+
+hipError_t launch_scan(int dtype, int d, const ScanArgs& a, int grid, size_t lds, hipStream_t s)
+{
+    switch (dtype) {
+    case HR_F32: return launch_scan_f32(d, a, grid, lds, s);
+    case HR_F16: return launch_scan_f16(d, a, grid, lds, s);
+    case HR_BF16: return launch_scan_bf16(d, a, grid, lds, s);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+size_t scan_lds_bytes(int dtype, int d, int k)
+{
+    const int planes = dtype == HR_F32 ? 2 : 1;
+    const size_t buf = (size_t)kBlockRows * (d * 2 + kRowPad) * planes;
+    const size_t cap = sel_cap(k);
+    const size_t cw = cols_per_item(dtype);
+    return 2 * buf + cw * cap * sizeof(Cand) + 4 * cap * sizeof(int64_t) + cw * sizeof(int) + 16;
+}
+}  // namespace hr
+
+using namespace hr;
+
+static thread_local char g_err[512] = "";
+
+static int fail(int code, const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+#define HR_HIP(call)                                                                      \
+    do {                                                                                  \
+        hipError_t e_ = (call);                                                           \
+        if (e_ != hipSuccess) return fail(HR_ERR_HIP, "%s: %s", #call, hipGetErrorString(e_)); \
+    } while (0)
+
+static constexpr uint64_t kMagic = 0x4852495646313031ULL;   // "HRIVF101"
+
+struct hr_ivf_index {
+    uint64_t magic;
+    const float* centroids;
+    const void* vectors;
+    const int64_t* ids;
+    int64_t nlist, N;
+    int d, dtype;
+    int* d_list_off;       // [nlist+1] int32
+    float* d_row_norm;     // [N]
+    float* d_cent_norm;    // [nlist]
+    int num_cus;
+    int lds_limit;
+    // optional kernel timing (hr_ivf_profile_begin/end)
+    hipEvent_t* prof_ev;   // 2 * prof_cap events
+    int prof_cap, prof_n;
+};
+
+static bool dim_supported(int d)
+{
+    return d == 64 || d == 128 || d == 256 || d == 512 || d == 768 || d == 1024;
+}
+
+static size_t align_up(size_t v) { return (v + HR_WORKSPACE_ALIGN - 1) & ~(size_t)(HR_WORKSPACE_ALIGN - 1); }
+
+// Layout of the caller's workspace for one batch shape.  Offsets in bytes.
+struct Plan {
+    // coarse step: centroid table scanned with all queries as one dense bucket
+    int cw_c, nqt_c, seg_c, nseg_c, items_c;
+    // list scan
+    int cw_s, item_cap;
+    size_t o_zero, n_zero;          // ints cleared per call: list_w[nlist], dyn[DYN_COUNT], counters[8]
+    size_t o_thr;                   // 2*nq ints set to "-inf"
+    size_t o_qop_c, o_qnorm_c, o_qop_s, o_qnorm_s;
+    size_t o_probe;
+    size_t o_pair_entry, o_bucket_off, o_bucket_q, o_item_base, o_item_tab;
+    size_t o_slot_cnt, o_slot_ent;
+    size_t total;
+};
+
+static Plan make_plan(const hr_ivf_index* ix, int64_t nq, int nprobe, int k)
+{
+    Plan p{};
+    const int64_t nlist = ix->nlist;
+    const int kk = k > nprobe ? k : nprobe;      // slots are shared by the two scans
+    p.cw_c = cols_per_item(HR_F32);
+    p.nqt_c = (int)((nq + p.cw_c - 1) / p.cw_c);
+    int64_t seg = (nlist * (int64_t)p.nqt_c + 2047) / 2048;
+    seg = (seg + 15) & ~15LL;
+    if (seg < 32) seg = 32;
+    if (seg > 1024) seg = 1024;
+    p.seg_c = (int)seg;
+    p.nseg_c = (int)((nlist + seg - 1) / seg);
+    p.items_c = p.nseg_c * p.nqt_c;
+    p.cw_s = cols_per_item(ix->dtype);
+    const int64_t pairs = nq * nprobe;
+    p.item_cap = (int)(kItemTarget + pairs / p.cw_s + (pairs < nlist ? pairs : nlist) + 8);
+
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
+    p.n_zero = (size_t)nlist + DYN_COUNT + 8;
+    p.o_zero = take(p.n_zero * 4);
+    p.o_thr = take((size_t)nq * 2 * 4);
+    p.o_qop_c = take((size_t)nq * 2 * ix->d * 2);
+    p.o_qnorm_c = take((size_t)nq * 4);
+    p.o_qop_s = ix->dtype == HR_F32 ? p.o_qop_c
+                                    : take((size_t)nq * (ix->dtype == HR_BF16 ? 2 : 1) * ix->d * 2);
+    p.o_qnorm_s = take((size_t)nq * 4);
+    p.o_probe = take((size_t)pairs * 4);
+    p.o_pair_entry = take((size_t)pairs * 4);
+    p.o_bucket_off = take((size_t)(nlist + 1) * 4);
+    p.o_bucket_q = take((size_t)pairs * 4);
+    p.o_item_base = take((size_t)(nlist + 1) * 4);
+    p.o_item_tab = take((size_t)p.item_cap * sizeof(int4));
+    size_t slots_c = (size_t)p.items_c * p.cw_c, slots_s = (size_t)p.item_cap * p.cw_s;
+    size_t slots = slots_c > slots_s ? slots_c : slots_s;
+    p.o_slot_cnt = take(slots * 4);
+    p.o_slot_ent = take(slots * (size_t)kk * sizeof(Cand));
+    p.total = o;
+    return p;
+}
+
+static int check_index(const hr_ivf_index* ix)
+{
+    if (!ix || ix->magic != kMagic) return fail(HR_ERR_HANDLE, "index handle is null, freed or corrupt");
+    return HR_OK;
+}
+
+static int check_batch(const hr_ivf_index* ix, int64_t nq, int nprobe, int k, int metric, bool need_k)
+{
+    if (nq < 0 || nq > (1 << 24)) return fail(HR_ERR_ARG, "nq=%lld out of range", (long long)nq);
+    if (nprobe < 1 || nprobe > ix->nlist || nprobe > HR_NPROBE_MAX)
+        return fail(HR_ERR_ARG, "nprobe=%d must be in 1..min(nlist=%lld, %d)", nprobe, (long long)ix->nlist, HR_NPROBE_MAX);
+    if (need_k && (k < 1 || k > HR_K_MAX)) return fail(HR_ERR_ARG, "k=%d must be in 1..%d", k, HR_K_MAX);
+    if (metric != HR_METRIC_IP && metric != HR_METRIC_L2) return fail(HR_ERR_ARG, "unknown metric %d", metric);
+    if (nq * (int64_t)nprobe >= (1LL << 30)) return fail(HR_ERR_UNSUPPORTED, "nq*nprobe too large");
+    return HR_OK;
+}
+
+static int check_ws(const Plan& p, const void* ws, size_t bytes)
+{
+    if (!ws) return fail(HR_ERR_WORKSPACE, "workspace is null");
+    if (((uintptr_t)ws) % HR_WORKSPACE_ALIGN) return fail(HR_ERR_WORKSPACE, "workspace not %d-byte aligned", HR_WORKSPACE_ALIGN);
+    if (bytes < p.total) return fail(HR_ERR_WORKSPACE, "workspace has %zu bytes, need %zu", bytes, p.total);
+    return HR_OK;
+}
+
+extern "C" {
+
+const char* hr_last_error(void) { return g_err; }
+const char* hr_version(void) { return "hr_ivf 0.1 gfx950"; }
+
+int hr_ivf_load(const float* centroids, const int64_t* list_offsets, const void* list_vectors,
+                const int64_t* list_ids, int64_t nlist, int64_t N, int32_t d, int32_t dtype,
+                void* stream, hr_ivf_index** out)
+{
+    if (!out) return fail(HR_ERR_ARG, "out is null");
+    *out = nullptr;
+    if (!centroids || !list_offsets) return fail(HR_ERR_ARG, "centroids / list_offsets is null");
+    if (nlist < 1 || nlist >= (1LL << 24)) return fail(HR_ERR_ARG, "nlist=%lld out of range", (long long)nlist);
+    if (N < 0 || N >= (1LL << 31)) return fail(HR_ERR_ARG, "N=%lld out of range (< 2^31)", (long long)N);
+    if (N > 0 && (!list_vectors || !list_ids)) return fail(HR_ERR_ARG, "list_vectors / list_ids is null");
+    if (dtype != HR_F32 && dtype != HR_F16 && dtype != HR_BF16) return fail(HR_ERR_ARG, "unknown dtype %d", dtype);
+    if (d < 1) return fail(HR_ERR_ARG, "d=%d", d);
+    if (!dim_supported(d)) return fail(HR_ERR_UNSUPPORTED, "d=%d not one of 64,128,256,512,768,1024", d);
+    if (list_offsets[0] != 0 || list_offsets[nlist] != N) return fail(HR_ERR_ARG, "list_offsets must start at 0 and end at N");
+    for (int64_t l = 0; l < nlist; l++)
+        if (list_offsets[l + 1] < list_offsets[l]) return fail(HR_ERR_ARG, "list_offsets decreases at list %lld", (long long)l);
+
+    hipStream_t s = (hipStream_t)stream;
+    int dev = 0;
+    HR_HIP(hipGetDevice(&dev));
+    hr_ivf_index* ix = new (std::nothrow) hr_ivf_index();
+    if (!ix) return fail(HR_ERR_HIP, "out of host memory");
+    ix->centroids = centroids; ix->vectors = list_vectors; ix->ids = list_ids;
+    ix->nlist = nlist; ix->N = N; ix->d = d; ix->dtype = dtype;
+    int* h_off = new (std::nothrow) int[nlist + 1];
+    if (!h_off) { delete ix; return fail(HR_ERR_HIP, "out of host memory"); }
+    for (int64_t l = 0; l <= nlist; l++) h_off[l] = (int)list_offsets[l];
+    hipError_t e = hipDeviceGetAttribute(&ix->num_cus, hipDeviceAttributeMultiprocessorCount, dev);
+    ix->lds_limit = 160 * 1024;     // LDS per workgroup on gfx950
+    if (e == hipSuccess) {
+        hipDeviceProp_t prop;
+        e = hipGetDeviceProperties(&prop, dev);
+        if (e == hipSuccess && strncmp(prop.gcnArchName, "gfx950", 6) != 0) {
+            delete[] h_off;
+            delete ix;
+            return fail(HR_ERR_UNSUPPORTED, "device is %s; this library is built for gfx950 only", prop.gcnArchName);
+        }
+    }
+    if (e == hipSuccess) e = hipMalloc(&ix->d_list_off, (size_t)(nlist + 1) * 4);
+    if (e == hipSuccess) e = hipMalloc(&ix->d_row_norm, (size_t)(N > 0 ? N : 1) * 4);
+    if (e == hipSuccess) e = hipMalloc(&ix->d_cent_norm, (size_t)nlist * 4);
+    if (e == hipSuccess) e = hipMemcpyAsync(ix->d_list_off, h_off, (size_t)(nlist + 1) * 4, hipMemcpyHostToDevice, s);
+    if (e == hipSuccess) e = launch_row_norms(list_vectors, dtype, N, d, ix->d_row_norm, s);
+    if (e == hipSuccess) e = launch_row_norms(centroids, HR_F32, nlist, d, ix->d_cent_norm, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    delete[] h_off;
+    if (e != hipSuccess) {
+        if (ix->d_list_off) (void)hipFree(ix->d_list_off);
+        if (ix->d_row_norm) (void)hipFree(ix->d_row_norm);
+        if (ix->d_cent_norm) (void)hipFree(ix->d_cent_norm);
+        delete ix;
+        return fail(HR_ERR_HIP, "hr_ivf_load: %s", hipGetErrorString(e));
+    }
+    ix->magic = kMagic;
+    *out = ix;
+    return HR_OK;
+}
+
+static void drop_events(hr_ivf_index* ix)
+{
+    if (!ix->prof_ev) return;
+    for (int i = 0; i < 2 * ix->prof_cap; i++)
+        if (ix->prof_ev[i]) (void)hipEventDestroy(ix->prof_ev[i]);
+    delete[] ix->prof_ev;
+    ix->prof_ev = nullptr;
+    ix->prof_cap = ix->prof_n = 0;
+}
+
+int hr_ivf_profile_begin(hr_ivf_index* ix, int32_t max_calls)
+{
+    if (int rc = check_index(ix)) return rc;
+    if (max_calls < 1 || max_calls > 65536) return fail(HR_ERR_ARG, "max_calls=%d", max_calls);
+    drop_events(ix);
+    ix->prof_ev = new (std::nothrow) hipEvent_t[2 * (size_t)max_calls]();
+    if (!ix->prof_ev) return fail(HR_ERR_HIP, "out of host memory");
+    ix->prof_cap = max_calls;
+    for (int i = 0; i < 2 * max_calls; i++) {
+        hipError_t e = hipEventCreate(&ix->prof_ev[i]);
+        if (e != hipSuccess) { drop_events(ix); return fail(HR_ERR_HIP, "hipEventCreate: %s", hipGetErrorString(e)); }
+    }
+    return HR_OK;
+}
+
+int hr_ivf_profile_end(hr_ivf_index* ix, int32_t* n, double* scan_ms_avg)
+{
+    if (int rc = check_index(ix)) return rc;
+    if (!n || !scan_ms_avg) return fail(HR_ERR_ARG, "n / scan_ms_avg is null");
+    double sum = 0.0;
+    int cnt = 0;
+    for (int i = 0; i < ix->prof_n; i++) {
+        float ms = 0.f;
+        hipError_t e = hipEventSynchronize(ix->prof_ev[2 * i + 1]);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, ix->prof_ev[2 * i], ix->prof_ev[2 * i + 1]);
+        if (e != hipSuccess) { drop_events(ix); return fail(HR_ERR_HIP, "event timing: %s", hipGetErrorString(e)); }
+        sum += ms;
+        cnt++;
+    }
+    *n = cnt;
+    *scan_ms_avg = cnt ? sum / cnt : 0.0;
+    drop_events(ix);
+    return HR_OK;
+}
+
+int hr_ivf_free(hr_ivf_index* ix)
+{
+    if (int rc = check_index(ix)) return rc;
+    drop_events(ix);
+    ix->magic = 0;
+    (void)hipFree(ix->d_list_off);
+    (void)hipFree(ix->d_row_norm);
+    (void)hipFree(ix->d_cent_norm);
+    delete ix;
+    return HR_OK;
+}
+
+size_t hr_ivf_workspace_bytes(const hr_ivf_index* ix, int64_t nq, int32_t nprobe, int32_t k)
+{
+    if (check_index(ix)) return 0;
+    if (check_batch(ix, nq, nprobe, k, HR_METRIC_IP, true)) return 0;
+    return make_plan(ix, nq, nprobe, k).total;
+}
+
+}  // extern "C"
+
+// ---------------------------------------------------------------------------------------
+static int scan_grid(const hr_ivf_index* ix, size_t lds)
+{
+    int occ = (int)((size_t)ix->lds_limit / lds);
+    if (occ < 1) occ = 1;
+    if (occ > 3) occ = 3;
+    return ix->num_cus * occ;
+}
+
+static int enqueue_clear(const Plan& p, char* ws, int64_t nq, hipStream_t s)
+{
+    HR_HIP(launch_fill_i32((int*)(ws + p.o_zero), (int64_t)p.n_zero, 0, s));
+    HR_HIP(launch_fill_i32((int*)(ws + p.o_thr), nq * 2, kEncNegInf, s));
+    return HR_OK;
+}
+
+// coarse scoring + top-nprobe: the scan kernel over the centroid table, then the merge
+static int enqueue_coarse(const hr_ivf_index* ix, const Plan& p, char* ws, int64_t nq, int nprobe,
+                          int metric, int32_t* out_probe, float* out_scores, hipStream_t s)
+{
+    const size_t lds = scan_lds_bytes(HR_F32, ix->d, nprobe);
+    if (lds > (size_t)ix->lds_limit)
+        return fail(HR_ERR_UNSUPPORTED, "coarse step needs %zu bytes of LDS (d=%d, nprobe=%d), device has %d", lds, ix->d, nprobe, ix->lds_limit);
+    int* zero = (int*)(ws + p.o_zero);
+    ScanArgs a{};
+    a.rows = ix->centroids;
+    a.row_norm = ix->d_cent_norm;
+    a.row_ids = nullptr;
+    a.qop = ws + p.o_qop_c;
+    a.thr = (int*)(ws + p.o_thr);
+    a.slot_cnt = (int*)(ws + p.o_slot_cnt);
+    a.slot_ent = (Cand*)(ws + p.o_slot_ent);
+    a.work_counter = zero + ix->nlist + DYN_COUNT;
+    a.dense = 1;
+    a.dense_items = p.items_c;
+    a.dense_nqt = p.nqt_c;
+    a.dense_seg_rows = p.seg_c;
+    a.dense_nrows = (int)ix->nlist;
+    a.nq = (int)nq; a.k = nprobe; a.cap = sel_cap(nprobe); a.l2 = metric == HR_METRIC_L2;
+    int grid = scan_grid(ix, lds);
+    if (grid > p.items_c) grid = p.items_c;
+    HR_HIP(launch_scan(HR_F32, ix->d, a, grid, lds, s));
+    MergeArgs m{};
+    m.slot_cnt = a.slot_cnt; m.slot_ent = a.slot_ent;
+    m.row_ids = nullptr;
+    m.qnorm = (const float*)(ws + p.o_qnorm_c);
+    m.dense = 1; m.dense_nqt = p.nqt_c; m.dense_nseg = p.nseg_c;
+    m.nq = (int)nq; m.nprobe = nprobe; m.nlist = (int)ix->nlist; m.k = nprobe; m.cw = p.cw_c;
+    m.l2 = a.l2;
+    m.out_ids32 = out_probe; m.out_scores = out_scores;
+    HR_HIP(launch_merge(m, s));
+    return HR_OK;
+}
+
+// grouping by list + cluster-major scan + per-query merge
+static int enqueue_scan(const hr_ivf_index* ix, const Plan& p, char* ws, int64_t nq, const int32_t* probe,
+                        int nprobe, int k, int metric, int64_t* out_ids, float* out_scores, hipStream_t s)
+{
+    const size_t lds = scan_lds_bytes(ix->dtype, ix->d, k);
+    if (lds > (size_t)ix->lds_limit)
+        return fail(HR_ERR_UNSUPPORTED, "scan needs %zu bytes of LDS (d=%d, k=%d), device has %d", lds, ix->d, k, ix->lds_limit);
+    int* zero = (int*)(ws + p.o_zero);
+    BucketArgs b{};
+    b.probe = probe; b.nq = (int)nq; b.nprobe = nprobe; b.nlist = (int)ix->nlist; b.cw = p.cw_s;
+    b.list_off = ix->d_list_off;
+    b.list_w = zero;
+    b.pair_entry = (int*)(ws + p.o_pair_entry);
+    b.bucket_off = (int*)(ws + p.o_bucket_off);
+    b.bucket_q = (int*)(ws + p.o_bucket_q);
+    b.item_base = (int*)(ws + p.o_item_base);
+    b.item_tab = (int4*)(ws + p.o_item_tab);
+    b.dyn = zero + ix->nlist;
+    b.item_cap = p.item_cap;
+    HR_HIP(launch_bucketing(b, s));
+
+    ScanArgs a{};
+    a.rows = ix->vectors;
+    a.row_norm = ix->d_row_norm;
+    a.row_ids = ix->ids;
+    a.qop = ws + p.o_qop_s;
+    a.thr = (int*)(ws + p.o_thr) + nq;
+    a.slot_cnt = (int*)(ws + p.o_slot_cnt);
+    a.slot_ent = (Cand*)(ws + p.o_slot_ent);
+    a.work_counter = zero + ix->nlist + DYN_COUNT + 1;
+    a.list_off = ix->d_list_off;
+    a.bucket_off = b.bucket_off;
+    a.bucket_q = b.bucket_q;
+    a.item_tab = b.item_tab;
+    a.dyn = b.dyn;
+    a.dense = 0;
+    a.nq = (int)nq; a.k = k; a.cap = sel_cap(k); a.l2 = metric == HR_METRIC_L2;
+    hr_ivf_index* mix = const_cast<hr_ivf_index*>(ix);
+    const bool timed = mix->prof_ev && mix->prof_n < mix->prof_cap;
+    if (timed) HR_HIP(hipEventRecord(mix->prof_ev[2 * mix->prof_n], s));
+    HR_HIP(launch_scan(ix->dtype, ix->d, a, scan_grid(ix, lds), lds, s));
+    if (timed) {
+        HR_HIP(hipEventRecord(mix->prof_ev[2 * mix->prof_n + 1], s));
+        mix->prof_n++;
+    }
+
+    MergeArgs m{};
+    m.slot_cnt = a.slot_cnt; m.slot_ent = a.slot_ent;
+    m.row_ids = ix->ids;
+    m.qnorm = (const float*)(ws + p.o_qnorm_s);
+    m.probe = probe; m.pair_entry = b.pair_entry;
+    m.list_off = ix->d_list_off; m.bucket_off = b.bucket_off; m.item_base = b.item_base; m.dyn = b.dyn;
+    m.dense = 0;
+    m.nq = (int)nq; m.nprobe = nprobe; m.nlist = (int)ix->nlist; m.k = k; m.cw = p.cw_s; m.l2 = a.l2;
+    m.out_ids = out_ids; m.out_scores = out_scores;
+    HR_HIP(launch_merge(m, s));
+    return HR_OK;
+}
+
+extern "C" {
+
+int hr_ivf_search(const hr_ivf_index* ix, const float* queries, int64_t nq, int32_t nprobe, int32_t k,
+                  int32_t metric, int64_t* out_ids, float* out_scores, void* workspace,
+                  size_t workspace_bytes, void* stream)
+{
+    if (int rc = check_index(ix)) return rc;
+    if (int rc = check_batch(ix, nq, nprobe, k, metric, true)) return rc;
+    if (nq == 0) return HR_OK;
+    if (!queries || !out_ids || !out_scores) return fail(HR_ERR_ARG, "queries / out_ids / out_scores is null");
+    const Plan p = make_plan(ix, nq, nprobe, k);
+    if (int rc = check_ws(p, workspace, workspace_bytes)) return rc;
+    char* ws = (char*)workspace;
+    hipStream_t s = (hipStream_t)stream;
+    if (int rc = enqueue_clear(p, ws, nq, s)) return rc;
+    HR_HIP(launch_prep_queries(queries, nq, ix->d, ix->dtype, ws + p.o_qop_c, (float*)(ws + p.o_qnorm_c),
+                               ix->dtype == HR_F32 ? nullptr : ws + p.o_qop_s, (float*)(ws + p.o_qnorm_s), s));
+    int32_t* probe = (int32_t*)(ws + p.o_probe);
+    if (int rc = enqueue_coarse(ix, p, ws, nq, nprobe, metric, probe, nullptr, s)) return rc;
+    return enqueue_scan(ix, p, ws, nq, probe, nprobe, k, metric, out_ids, out_scores, s);
+}
+
+int hr_ivf_coarse(const hr_ivf_index* ix, const float* queries, int64_t nq, int32_t nprobe, int32_t metric,
+                  int32_t* out_probe_ids, float* out_probe_scores, void* workspace, size_t workspace_bytes,
+                  void* stream)
+{
+    if (int rc = check_index(ix)) return rc;
+    if (int rc = check_batch(ix, nq, nprobe, 1, metric, false)) return rc;
+    if (nq == 0) return HR_OK;
+    if (!queries || !out_probe_ids) return fail(HR_ERR_ARG, "queries / out_probe_ids is null");
+    const Plan p = make_plan(ix, nq, nprobe, 1);
+    if (int rc = check_ws(p, workspace, workspace_bytes)) return rc;
+    char* ws = (char*)workspace;
+    hipStream_t s = (hipStream_t)stream;
+    if (int rc = enqueue_clear(p, ws, nq, s)) return rc;
+    HR_HIP(launch_prep_queries(queries, nq, ix->d, HR_F32, ws + p.o_qop_c, (float*)(ws + p.o_qnorm_c),
+                               nullptr, nullptr, s));
+    return enqueue_coarse(ix, p, ws, nq, nprobe, metric, out_probe_ids, out_probe_scores, s);
+}
+
+int hr_ivf_scan(const hr_ivf_index* ix, const float* queries, int64_t nq, const int32_t* probe_ids,
+                int32_t nprobe, int32_t k, int32_t metric, int64_t* out_ids, float* out_scores,
+                void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (int rc = check_index(ix)) return rc;
+    if (nprobe < 1 || nprobe > HR_NPROBE_MAX) return fail(HR_ERR_ARG, "nprobe=%d must be in 1..%d", nprobe, HR_NPROBE_MAX);
+    int np_plan = nprobe > ix->nlist ? (int)ix->nlist : nprobe;
+    if (int rc = check_batch(ix, nq, np_plan, k, metric, true)) return rc;
+    if (nq == 0) return HR_OK;
+    if (!queries || !probe_ids || !out_ids || !out_scores) return fail(HR_ERR_ARG, "queries / probe_ids / outputs null");
+    const Plan p = make_plan(ix, nq, nprobe, k);
+    if (int rc = check_ws(p, workspace, workspace_bytes)) return rc;
+    char* ws = (char*)workspace;
+    hipStream_t s = (hipStream_t)stream;
+    if (int rc = enqueue_clear(p, ws, nq, s)) return rc;
+    const bool f32 = ix->dtype == HR_F32;
+    HR_HIP(launch_prep_queries(queries, nq, ix->d, ix->dtype, f32 ? ws + p.o_qop_c : nullptr, nullptr,
+                               f32 ? nullptr : ws + p.o_qop_s, (float*)(ws + p.o_qnorm_s), s));
+    return enqueue_scan(ix, p, ws, nq, probe_ids, nprobe, k, metric, out_ids, out_scores, s);
+}
+
+int hr_ivf_stats(const hr_ivf_index* ix, const void* workspace, size_t workspace_bytes, int64_t nq,
+                 int32_t nprobe, int32_t k, int64_t out[4])
+{
+    if (int rc = check_index(ix)) return rc;
+    if (!out) return fail(HR_ERR_ARG, "out is null");
+    if (int rc = check_batch(ix, nq, nprobe > ix->nlist ? (int)ix->nlist : nprobe, k, HR_METRIC_IP, true)) return rc;
+    const Plan p = make_plan(ix, nq, nprobe, k);
+    if (int rc = check_ws(p, workspace, workspace_bytes)) return rc;
+    int dyn[DYN_COUNT];
+    HR_HIP(hipMemcpy(dyn, (const char*)workspace + p.o_zero + (size_t)ix->nlist * 4, sizeof dyn, hipMemcpyDeviceToHost));
+    out[0] = dyn[DYN_ITEMS];
+    out[1] = dyn[DYN_SEG_ROWS];
+    out[2] = ((int64_t)(uint32_t)dyn[DYN_ROWS_HI] << 32) | (uint32_t)dyn[DYN_ROWS_LO];
+    out[3] = dyn[DYN_PAIRS];
+    return HR_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,418 @@
+// Small kernels around the list scan: query operand preparation, row norms, grouping of
+// (query, list) probes by list, and the per-query merge of the scan's partial results.
+#include "scan_kernel.h"
+
+namespace hr {
+
+// ------------------------------------------------------------------------------------------
+__global__ void k_fill_i32(int* p, int64_t n, int v)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+hipError_t launch_fill_i32(int* p, int64_t n, int v, hipStream_t s)
+{
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_fill_i32, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, p, n, v);
+    return hipGetLastError();
+}
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+__device__ __forceinline__ uint16_t bf16_rne(float f)
+{
+    uint32_t u = __builtin_bit_cast(uint32_t, f);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ float bf16_to_f32(uint16_t b)
+{
+    return __builtin_bit_cast(float, ((uint32_t)b) << 16);
+}
+
+// Squared norm of every stored row, float32 accumulation of the exact stored values; used by
+// the squared-L2 metric in its expanded form |q|^2 + |x|^2 - 2 q.x.  One wave per row.
+__global__ __launch_bounds__(256) void k_row_norms(const void* rows, int dtype, int64_t nrows, int d, float* out)
+{
+    int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= nrows) return;
+    int lane = threadIdx.x & 63;
+    float acc = 0.f;
+    if (dtype == HR_F32) {
+        const float* p = (const float*)rows + row * d;
+        for (int i = lane; i < d; i += 64) acc += p[i] * p[i];
+    } else if (dtype == HR_F16) {
+        const _Float16* p = (const _Float16*)rows + row * d;
+        for (int i = lane; i < d; i += 64) { float x = (float)p[i]; acc += x * x; }
+    } else {
+        const uint16_t* p = (const uint16_t*)rows + row * d;
+        for (int i = lane; i < d; i += 64) { float x = bf16_to_f32(p[i]); acc += x * x; }
+    }
+    acc = wave_sum(acc);
+    if (lane == 0) out[row] = acc;
+}
+
+hipError_t launch_row_norms(const void* rows, int dtype, int64_t nrows, int d, float* out, hipStream_t s)
+{
+    if (nrows <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_row_norms, dim3((unsigned)((nrows + 3) / 4)), dim3(256), 0, s, rows, dtype, nrows, d, out);
+    return hipGetLastError();
+}
+
+// Query operands.  Coarse step and float32 storage: binary16 hi row and 2^11-scaled binary16
+// lo row per query.  binary16 storage: the query rounded to binary16.  bfloat16 storage:
+// bfloat16 hi and lo rows.  The squared norms are those of the operand actually multiplied,
+// so that the expanded L2 form cancels consistently.  One wave per query.
+__global__ __launch_bounds__(256) void k_prep_queries(const float* q, int64_t nq, int d, int dtype,
+                                                      _Float16* qc, float* qnorm_c, void* qs, float* qnorm_s)
+{
+    int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= nq) return;
+    int lane = threadIdx.x & 63;
+    const float* p = q + row * d;
+    float n32 = 0.f, ns = 0.f;
+    for (int i = lane; i < d; i += 64) {
+        float x = p[i];
+        n32 += x * x;
+        if (qc) {
+            _Float16 h = (_Float16)x;
+            qc[(row * 2) * d + i] = h;
+            qc[(row * 2 + 1) * d + i] = (_Float16)((x - (float)h) * 2048.0f);
+        }
+        if (qs) {
+            if (dtype == HR_F16) {
+                _Float16 h = (_Float16)x;
+                ((_Float16*)qs)[row * d + i] = h;
+                ns += (float)h * (float)h;
+            } else if (dtype == HR_BF16) {
+                uint16_t hi = bf16_rne(x);
+                uint16_t lo = bf16_rne(x - bf16_to_f32(hi));
+                ((uint16_t*)qs)[(row * 2) * d + i] = hi;
+                ((uint16_t*)qs)[(row * 2 + 1) * d + i] = lo;
+                float e = bf16_to_f32(hi) + bf16_to_f32(lo);
+                ns += e * e;
+            }
+        }
+    }
+    n32 = wave_sum(n32);
+    ns = wave_sum(ns);
+    if (lane == 0) {
+        if (qnorm_c) qnorm_c[row] = n32;
+        if (qnorm_s) qnorm_s[row] = (dtype == HR_F32) ? n32 : ns;
+    }
+}
+
+hipError_t launch_prep_queries(const float* q, int64_t nq, int d, int dtype, void* qop_coarse,
+                               float* qnorm_coarse, void* qop_scan, float* qnorm_scan, hipStream_t s)
+{
+    if (nq <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_prep_queries, dim3((unsigned)((nq + 3) / 4)), dim3(256), 0, s, q, nq, d, dtype,
+                       (_Float16*)qop_coarse, qnorm_coarse, qop_scan, qnorm_scan);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// Grouping of the nq*nprobe (query, list) pairs by list (the cross-request grouping behind
+// the variable-length cluster search interface, Section 5 of the paper).
+
+// pair -> its position inside the list's bucket (order of arrival; results do not depend on it)
+__global__ void k_bucket_count(BucketArgs a)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (int64_t)a.nq * a.nprobe) return;
+    int l = a.probe[i];
+    a.pair_entry[i] = (l >= 0 && l < a.nlist) ? atomicAdd(&a.list_w[l], 1) : -1;
+}
+
+// One workgroup: bucket offsets, rows per segment for this batch, first work item of every list.
+__global__ __launch_bounds__(1024) void k_bucket_scan(BucketArgs a)
+{
+    __shared__ long long part[1024];
+    __shared__ long long s_total;
+    __shared__ int s_seg;
+    const int t = threadIdx.x;
+    const int per = (a.nlist + 1023) / 1024;
+    const int l0 = min(a.nlist, t * per), l1 = min(a.nlist, l0 + per);
+
+    // pass 1: bucket offsets, cost = sum rows * query tiles, rows streamed, pairs
+    long long w_sum = 0, cost = 0, rows = 0;
+    for (int l = l0; l < l1; l++) {
+        int w = a.list_w[l];
+        long long len = a.list_off[l + 1] - a.list_off[l];
+        w_sum += w;
+        cost += len * ((w + a.cw - 1) / a.cw);
+        if (w > 0) rows += len;
+    }
+    part[t] = w_sum;
+    __syncthreads();
+    if (t == 0) {
+        long long run = 0;
+        for (int i = 0; i < 1024; i++) { long long v = part[i]; part[i] = run; run += v; }
+        s_total = run;
+    }
+    __syncthreads();
+    {
+        long long run = part[t];
+        for (int l = l0; l < l1; l++) { a.bucket_off[l] = (int)run; run += a.list_w[l]; }
+        if (t == 0) { a.bucket_off[a.nlist] = (int)s_total; a.dyn[DYN_PAIRS] = (int)s_total; }
+    }
+    __syncthreads();
+    part[t] = cost;
+    __syncthreads();
+    if (t == 0) {
+        long long c = 0;
+        for (int i = 0; i < 1024; i++) c += part[i];
+        long long seg = (c + kItemTarget - 1) / kItemTarget;
+        seg = (seg + 15) & ~15LL;
+        if (seg < kMinSegRows) seg = kMinSegRows;
+        if (seg > (1LL << 30)) seg = 1LL << 30;
+        s_seg = (int)seg;
+        a.dyn[DYN_SEG_ROWS] = (int)seg;
+    }
+    __syncthreads();
+    part[t] = rows;
+    __syncthreads();
+    if (t == 0) {
+        long long r = 0;
+        for (int i = 0; i < 1024; i++) r += part[i];
+        a.dyn[DYN_ROWS_LO] = (int)(r & 0xffffffffLL);
+        a.dyn[DYN_ROWS_HI] = (int)(r >> 32);
+    }
+    __syncthreads();
+
+    // pass 2: work items per list = segments * query tiles
+    const int seg = s_seg;
+    long long items = 0;
+    for (int l = l0; l < l1; l++) {
+        int w = a.list_w[l];
+        int len = a.list_off[l + 1] - a.list_off[l];
+        if (w > 0 && len > 0) items += (long long)((len + seg - 1) / seg) * ((w + a.cw - 1) / a.cw);
+    }
+    part[t] = items;
+    __syncthreads();
+    if (t == 0) {
+        long long run = 0;
+        for (int i = 0; i < 1024; i++) { long long v = part[i]; part[i] = run; run += v; }
+        s_total = run;
+    }
+    __syncthreads();
+    {
+        long long run = part[t];
+        for (int l = l0; l < l1; l++) {
+            a.item_base[l] = (int)run;
+            int w = a.list_w[l];
+            int len = a.list_off[l + 1] - a.list_off[l];
+            if (w > 0 && len > 0) run += (long long)((len + seg - 1) / seg) * ((w + a.cw - 1) / a.cw);
+        }
+        if (t == 0) {
+            a.item_base[a.nlist] = (int)s_total;
+            // never more than the table holds (cannot happen: the host sizes it from the same bound)
+            a.dyn[DYN_ITEMS] = (int)min(s_total, (long long)a.item_cap);
+        }
+    }
+}
+
+__global__ void k_bucket_scatter(BucketArgs a)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (int64_t)a.nq * a.nprobe) return;
+    int e = a.pair_entry[i];
+    if (e < 0) return;
+    int l = a.probe[i];
+    a.bucket_q[a.bucket_off[l] + e] = (int)(i / a.nprobe);
+}
+
+// One wave per list writes the list's work items: segment-major, query tile minor, so the
+// tiles that re-read a segment run next to each other in time.
+__global__ __launch_bounds__(256) void k_item_expand(BucketArgs a)
+{
+    int l = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (l >= a.nlist) return;
+    int lane = threadIdx.x & 63;
+    int w = a.list_w[l];
+    int len = a.list_off[l + 1] - a.list_off[l];
+    if (w <= 0 || len <= 0) return;
+    int seg = a.dyn[DYN_SEG_ROWS];
+    int nqt = (w + a.cw - 1) / a.cw;
+    long long n = (long long)((len + seg - 1) / seg) * nqt;
+    long long base = a.item_base[l];
+    for (long long i = lane; i < n; i += 64) {
+        long long idx = base + i;
+        if (idx < a.item_cap) a.item_tab[idx] = make_int4(l, (int)(i / nqt), (int)(i % nqt), 0);
+    }
+}
+
+hipError_t launch_bucketing(const BucketArgs& a, hipStream_t s)
+{
+    int64_t pairs = (int64_t)a.nq * a.nprobe;
+    unsigned gp = (unsigned)((pairs + 255) / 256);
+    hipLaunchKernelGGL(k_bucket_count, dim3(gp), dim3(256), 0, s, a);
+    hipLaunchKernelGGL(k_bucket_scan, dim3(1), dim3(1024), 0, s, a);
+    hipLaunchKernelGGL(k_bucket_scatter, dim3(gp), dim3(256), 0, s, a);
+    hipLaunchKernelGGL(k_item_expand, dim3((unsigned)((a.nlist + 3) / 4)), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// Per-query merge of the scan's partial results (the "effective reduction" of Section 5 and
+// the per-request merge of Section 4.4): one wave per query walks the slots that hold its
+// candidates, keeps the k best in an LDS buffer pruned as in the scan, then orders the
+// survivors by (key, label) and writes the output row.
+constexpr int kMergeCap = 256;     // candidates buffered per query (k <= 128, up to 64 appended per step)
+
+__global__ __launch_bounds__(256) void k_merge(MergeArgs a)
+{
+    __shared__ Cand s_buf[4][kMergeCap];
+    __shared__ int64_t s_tie[4][kMergeCap];
+    __shared__ int s_pref[4][HR_NPROBE_MAX + 1];
+    __shared__ int s_cnt[4];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int64_t q = (int64_t)blockIdx.x * 4 + wave;
+    if (q >= a.nq) return;                       // whole wave leaves; no block barrier below
+    Cand* buf = s_buf[wave];
+    int64_t* tie = s_tie[wave];
+    int* pref = s_pref[wave];
+    const int k = a.k;
+    const int seg_rows = a.dense ? 1 : a.dyn[DYN_SEG_ROWS];
+
+    // ---- how many segments (= slots) does each probed list contribute
+    int total;
+    if (a.dense) {
+        total = a.dense_nseg;
+    } else {
+        int run = 0;
+        for (int p0 = 0; p0 < a.nprobe; p0 += 64) {
+            int p = p0 + lane;
+            int ns = 0;
+            if (p < a.nprobe) {
+                int l = a.probe[q * a.nprobe + p];
+                if (l >= 0 && l < a.nlist && a.pair_entry[q * a.nprobe + p] >= 0) {
+                    int len = a.list_off[l + 1] - a.list_off[l];
+                    ns = (len + seg_rows - 1) / seg_rows;
+                }
+            }
+            int inc = ns;                         // inclusive scan over the wave
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                int v = __shfl_up(inc, o);
+                if (lane >= o) inc += v;
+            }
+            if (p < a.nprobe) pref[p + 1] = run + inc;
+            run += __shfl(inc, 63);
+        }
+        if (lane == 0) pref[0] = 0;
+        total = run;
+    }
+    if (lane == 0) s_cnt[wave] = 0;
+    wave_sync();
+
+    float thr = -__builtin_inff();
+    for (int f0 = 0; f0 < total; f0 += 64) {
+        const int f = f0 + lane;
+        int c = 0;
+        size_t slot = 0;
+        if (f < total) {
+            if (a.dense) {
+                slot = ((size_t)f * a.dense_nqt + (size_t)(q / a.cw)) * a.cw + (size_t)(q % a.cw);
+            } else {
+                int lo = 0, hi = a.nprobe;        // largest p with pref[p] <= f
+                while (hi - lo > 1) {
+                    int mid = (lo + hi) >> 1;
+                    if (pref[mid] <= f) lo = mid; else hi = mid;
+                }
+                int p = lo;
+                int s = f - pref[p];
+                int l = a.probe[q * a.nprobe + p];
+                int e = a.pair_entry[q * a.nprobe + p];
+                int w = a.bucket_off[l + 1] - a.bucket_off[l];
+                int nqt = (w + a.cw - 1) / a.cw;
+                size_t item = (size_t)a.item_base[l] + (size_t)s * nqt + (size_t)(e / a.cw);
+                slot = item * a.cw + (size_t)(e % a.cw);
+            }
+            c = a.slot_cnt[slot];
+        }
+        int maxc = c;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) maxc = max(maxc, __shfl_xor(maxc, o));
+        for (int j = 0; j < maxc; j++) {
+            if (j < c) {
+                Cand cd = a.slot_ent[slot * k + j];
+                if (__builtin_bit_cast(float, cd.key) >= thr) {
+                    int pos = atomicAdd(&s_cnt[wave], 1);
+                    buf[pos] = cd;
+                }
+            }
+            wave_sync();
+            int n = s_cnt[wave];
+            if (n > kMergeCap - 64) {
+                float kth = wave_prune<4>(buf, n, k, a.row_ids, tie);
+                thr = fmaxf(thr, kth);
+                if (lane == 0) s_cnt[wave] = k;
+                wave_sync();
+            }
+        }
+    }
+    wave_sync();
+    int n = s_cnt[wave];
+    if (n > k) {
+        wave_prune<4>(buf, n, k, a.row_ids, tie);
+        n = k;
+    }
+    wave_sync();
+
+    // ---- final order by (key descending, label ascending); n <= k <= 128: two entries per lane
+    Cand e[2];
+    int64_t id[2];
+#pragma unroll
+    for (int m = 0; m < 2; m++) {
+        int idx = lane + 64 * m;
+        e[m] = (idx < n) ? buf[idx] : Cand{0u, 0u};
+        id[m] = (idx < n) ? (a.row_ids ? a.row_ids[e[m].row] : (int64_t)e[m].row) : INT64_MAX;
+        if (idx < n) tie[idx] = id[m];
+    }
+    wave_sync();
+    int pos[2] = {0, 0};
+    for (int i = 0; i < n; i++) {
+        float so = __builtin_bit_cast(float, buf[i].key);
+        int64_t oid = tie[i];
+#pragma unroll
+        for (int m = 0; m < 2; m++) {
+            float sm = __builtin_bit_cast(float, e[m].key);
+            pos[m] += (so > sm || (so == sm && oid < id[m])) ? 1 : 0;
+        }
+    }
+    const float qn = (a.l2 && a.qnorm) ? a.qnorm[q] : 0.f;
+#pragma unroll
+    for (int m = 0; m < 2; m++) {
+        int idx = lane + 64 * m;
+        if (idx < n) {
+            float key = __builtin_bit_cast(float, e[m].key);
+            float score = a.l2 ? fmaxf(qn - key, 0.f) : key;
+            size_t o = (size_t)q * k + pos[m];
+            if (a.out_ids) a.out_ids[o] = id[m];
+            if (a.out_ids32) a.out_ids32[o] = (int32_t)id[m];
+            if (a.out_scores) a.out_scores[o] = score;
+        }
+    }
+    for (int idx = n + lane; idx < k; idx += 64) {     // fewer than k candidates: pad
+        size_t o = (size_t)q * k + idx;
+        if (a.out_ids) a.out_ids[o] = -1;
+        if (a.out_ids32) a.out_ids32[o] = -1;
+        if (a.out_scores) a.out_scores[o] = a.l2 ? __builtin_inff() : -__builtin_inff();
+    }
+}
+
+hipError_t launch_merge(const MergeArgs& a, hipStream_t s)
+{
+    if (a.nq <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_merge, dim3((unsigned)((a.nq + 3) / 4)), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+}  // namespace hr

@@ -1,0 +1,116 @@
+// Shared declarations of the gfx950 IVF search library (internal; the public ABI is hr_ivf.h).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "hr_ivf.h"
+
+namespace hr {
+
+constexpr int kWave = 64;
+constexpr int kScanThreads = 256;          // 4 waves per workgroup
+constexpr int kBlockRows = 16;             // rows per MFMA block (M of 16x16x32)
+constexpr int kRowPad = 16;                // bytes of LDS padding per staged row (bank spread)
+constexpr int kAppendMax = 16;             // most candidates one column can gain per block
+constexpr int kMinSegRows = 128;           // smallest rows-per-work-item
+constexpr int kItemTarget = 32768;         // aimed number of scan work items per batch
+
+// columns (queries) per work item: 16 per wave when the query operand is one binary16
+// row, 8 per wave when it is a (hi, lo) pair occupying two MFMA columns.
+__host__ __device__ constexpr int cols_per_item(int dtype) { return dtype == HR_F16 ? 64 : 32; }
+
+// selection buffer capacity per column for a given k
+__host__ __device__ constexpr int sel_cap(int k)
+{
+    int a = 2 * k + 12, b = k + 60;
+    int c = a < b ? a : b;
+    if (c < k + kAppendMax + 4) c = k + kAppendMax + 4;
+    return (c + 3) & ~3;
+}
+
+// order-preserving map float -> int32 (for atomicMax on scores)
+__host__ __device__ inline int enc_order(float f)
+{
+    int b = __builtin_bit_cast(int, f);
+    return b ^ ((b >> 31) & 0x7fffffff);
+}
+__host__ __device__ inline float dec_order(int i)
+{
+    int b = i ^ ((i >> 31) & 0x7fffffff);
+    return __builtin_bit_cast(float, b);
+}
+constexpr int kEncNegInf = (int)0x807fffff;   // enc_order(-inf): 0xff800000 ^ 0x7fffffff
+
+// One candidate: key (float bits, larger is better) and row number.
+struct Cand { uint32_t key; uint32_t row; };
+
+// Arguments of the scan kernel (both uses: centroid table with all queries as one dense
+// bucket, and the inverted lists with the per-list buckets).
+struct ScanArgs {
+    const void* rows;           // [nrows, d] storage
+    const float* row_norm;      // [nrows] squared norms (used when l2 != 0)
+    const int64_t* row_ids;     // [nrows] labels, or nullptr: label = row number
+    const void* qop;            // query operand rows (layout depends on dtype)
+    int* thr;                   // [nq] running per-query lower bound of the k-th key (ordered int)
+    int* slot_cnt;              // [items * CW]
+    Cand* slot_ent;             // [items * CW * k]
+    int* work_counter;          // zeroed before launch
+    // bucket mode
+    const int* list_off;        // [nlist+1] row offsets
+    const int* bucket_off;      // [nlist+1]
+    const int* bucket_q;        // [pairs] query index per bucket entry
+    const int4* item_tab;       // [items] (list, segment, query tile, 0)
+    const int* dyn;             // device scalars: [0] = items, [1] = rows per segment
+    // dense mode (dense != 0): one list = all rows, bucket = all queries
+    int dense, dense_items, dense_nqt, dense_seg_rows, dense_nrows;
+    int nq, k, cap, l2;
+};
+
+// Device scalars written by the bucketing kernels (ints in workspace)
+enum { DYN_ITEMS = 0, DYN_SEG_ROWS = 1, DYN_ROWS_LO = 2, DYN_ROWS_HI = 3, DYN_PAIRS = 4, DYN_COUNT = 8 };
+
+struct MergeArgs {
+    const int* slot_cnt;
+    const Cand* slot_ent;
+    const int64_t* row_ids;     // nullptr: label = row number
+    const float* qnorm;         // [nq] squared norm of the query operand (L2 only)
+    // bucket mode
+    const int* probe;           // [nq, nprobe]
+    const int* pair_entry;      // [nq, nprobe] position of the pair inside its list's bucket
+    const int* list_off;        // [nlist+1]
+    const int* bucket_off;      // [nlist+1]
+    const int* item_base;       // [nlist+1]
+    const int* dyn;
+    // dense mode
+    int dense, dense_nqt, dense_nseg;
+    int nq, nprobe, nlist, k, cw, l2;
+    int64_t* out_ids;           // [nq, k] or nullptr
+    int32_t* out_ids32;         // [nq, k] (coarse) or nullptr
+    float* out_scores;          // [nq, k] or nullptr
+};
+
+// launchers implemented in the .hip files
+hipError_t launch_scan(int dtype, int d, const ScanArgs& a, int grid, size_t lds_bytes, hipStream_t s);
+size_t scan_lds_bytes(int dtype, int d, int k);
+hipError_t launch_merge(const MergeArgs& a, hipStream_t s);
+hipError_t launch_row_norms(const void* rows, int dtype, int64_t nrows, int d, float* out, hipStream_t s);
+hipError_t launch_prep_queries(const float* q, int64_t nq, int d, int dtype, void* qop_coarse,
+                               float* qnorm_coarse, void* qop_scan, float* qnorm_scan, hipStream_t s);
+hipError_t launch_fill_i32(int* p, int64_t n, int v, hipStream_t s);
+
+struct BucketArgs {
+    const int* probe;           // [nq*nprobe]
+    int nq, nprobe, nlist, cw;
+    const int* list_off;        // [nlist+1]
+    int* list_w;                // [nlist]   (zeroed by the first kernel's launch sequence)
+    int* pair_entry;            // [nq*nprobe]
+    int* bucket_off;            // [nlist+1]
+    int* bucket_q;              // [nq*nprobe]
+    int* item_base;             // [nlist+1]
+    int4* item_tab;             // [item_cap]
+    int* dyn;                   // device scalars
+    int item_cap;
+};
+hipError_t launch_bucketing(const BucketArgs& a, hipStream_t s);
+
+}  // namespace hr

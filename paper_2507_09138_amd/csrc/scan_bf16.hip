@@ -1,0 +1,9 @@
+// List-scan kernel instantiations for HR_BF16 storage (all supported dimensions).
+#include "scan_kernel.h"
+
+namespace hr {
+hipError_t launch_scan_bf16(int d, const ScanArgs& a, int grid, size_t lds, hipStream_t s)
+{
+    return launch_scan_dtype<HR_BF16>(d, a, grid, lds, s);
+}
+}  // namespace hr

@@ -1,0 +1,72 @@
+"""The C-ABI library loads, exports every symbol the header declares, and validates arguments
+on the host (no GPU needed for any of this)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def hr():
+    import paper_2507_09138_amd as hr
+    if not os.path.exists(hr.lib_path):
+        from paper_2507_09138_amd import build
+        build.build()
+    return hr
+
+
+def test_every_declared_symbol_is_exported(hr):
+    text = open(os.path.join(ROOT, "include", "hr_ivf.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = set(re.findall(r"\b(hr_[a-z0-9_]+)\s*\(", text))
+    assert {"hr_ivf_load", "hr_ivf_search", "hr_ivf_coarse", "hr_ivf_scan", "hr_ivf_free",
+            "hr_ivf_workspace_bytes", "hr_last_error"} <= names
+    for n in names:
+        assert hasattr(hr.lib, n), n
+    assert hr.hr_version().startswith("hr_ivf")
+
+
+def test_header_constants_match_binding(hr):
+    text = open(os.path.join(ROOT, "include", "hr_ivf.h")).read()
+    assert int(re.search(r"#define HR_K_MAX (\d+)", text).group(1)) == hr.HR_K_MAX
+    assert int(re.search(r"#define HR_NPROBE_MAX (\d+)", text).group(1)) == hr.HR_NPROBE_MAX
+
+
+def test_load_argument_validation_on_host(hr):
+    h = ctypes.c_void_p()
+    P = ctypes.c_void_p
+    off = np.array([0, 3, 5], np.int64)
+    bad = np.array([0, 6, 5], np.int64)
+    fake = P(4096)                                  # never dereferenced: validation fails first
+
+    def load(cent=fake, offs=off, vec=fake, ids=fake, nlist=2, N=5, d=768, dtype=0):
+        return hr.lib.hr_ivf_load(cent, P(offs.ctypes.data) if offs is not None else None, vec, ids,
+                                  nlist, N, d, dtype, None, ctypes.byref(h))
+
+    assert load(cent=None) == -1
+    assert load(offs=None) == -1
+    assert load(vec=None) == -1
+    assert load(nlist=0) == -1
+    assert load(N=-1) == -1
+    assert load(N=1 << 31) == -1
+    assert load(dtype=3) == -1
+    assert load(d=0) == -1
+    assert load(d=100) == -5 and "d=100" in hr.hr_last_error()
+    assert load(offs=bad) == -1 and "decreases" in hr.hr_last_error()
+    assert load(N=4) == -1
+    assert h.value is None
+    assert hr.lib.hr_ivf_load(fake, P(off.ctypes.data), fake, fake, 2, 5, 768, 0, None, None) == -1
+
+
+def test_null_handle_is_rejected(hr):
+    assert hr.lib.hr_ivf_free(None) == -2
+    assert hr.lib.hr_ivf_workspace_bytes(None, 10, 4, 4) == 0
+    assert hr.lib.hr_ivf_search(None, None, 1, 1, 1, 0, None, None, None, 0, None) == -2
+    assert hr.lib.hr_ivf_coarse(None, None, 1, 1, 0, None, None, None, 0, None) == -2
+    assert hr.lib.hr_ivf_scan(None, None, 1, None, 1, 1, 0, None, None, None, 0, None) == -2
+    bogus = (ctypes.c_uint64 * 64)()                 # memory that is not an index
+    assert hr.lib.hr_ivf_free(ctypes.cast(bogus, ctypes.c_void_p)) == -2

@@ -1,0 +1,291 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs (copied, not regenerated).  Tolerances: 1e-4 relative for float32 storage,
+2e-3 for 16-bit storage (see compare.py for what "relative" is taken against); ids and probe
+lists identical except at near-ties inside that tolerance."""
+import os
+import time
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+from compare import TAU, check_probes, check_topk
+
+pytestmark = pytest.mark.gpu
+METRIC = {"ip": oracle.IP, "l2": oracle.L2}
+
+
+def _hr():
+    import paper_2507_09138_amd as hr
+    return hr
+
+
+class Host:
+    """Host copies of an index for the oracle."""
+
+    def __init__(self, index):
+        self.cfg = index.cfg
+        self.cent = synth.to_numpy(index.centroids)
+        self.off = synth.to_numpy(index.list_offsets)
+        self.vec = synth.to_numpy(index.list_vectors)
+        self.ids = synth.to_numpy(index.list_ids)
+        self.row_of = {}
+        self._inv = None
+
+    def rows_of(self, ids):
+        if self._inv is None:
+            order = np.argsort(self.ids, kind="stable")
+            self._sorted_ids = self.ids[order]
+            self._inv = order
+        pos = np.searchsorted(self._sorted_ids, ids)
+        assert np.array_equal(self._sorted_ids[pos], ids)
+        return self._inv[pos]
+
+    def xnorm(self):
+        n = min(4096, self.vec.shape[0])
+        sel = np.linspace(0, self.vec.shape[0] - 1, n).astype(np.int64)
+        q1 = np.ones((1, 1), np.float32)
+        del q1
+        v = self.vec[sel]
+        if self.cfg.dtype == "bf16":
+            v = (v.astype(np.uint32) << 16).view(np.float32)
+        return float(np.sqrt((v.astype(np.float64) ** 2).sum(1)).mean())
+
+
+def _scale(q, xn, metric):
+    qn = np.sqrt((q.astype(np.float64) ** 2).sum(1))
+    return qn * xn if metric == "ip" else qn ** 2 + xn ** 2
+
+
+def compare_all(index, queries, nprobe, k, metric, sample=None, label=""):
+    """coarse vs oracle; scan (with the GPU's probe lists) vs oracle; search == coarse + scan."""
+    hr = _hr()
+    cfg = index.cfg
+    tau = TAU[cfg.dtype]
+    host = Host(index)
+    ix = hr.IvfIndex(index.centroids, index.list_offsets, index.list_vectors, index.list_ids)
+    q_dev = queries
+    t0 = time.time()
+    probe_g, pscore_g = ix.coarse(q_dev, nprobe, metric)
+    ids_s, sc_s = ix.scan(q_dev, probe_g, k, metric)
+    ids_f, sc_f = ix.search(q_dev, nprobe, k, metric)
+    torch.cuda.synchronize()
+    t_gpu = time.time() - t0
+    st = ix.stats(q_dev.shape[0], nprobe, k)
+    probe_g, pscore_g = probe_g.cpu().numpy(), pscore_g.cpu().numpy()
+    ids_s, sc_s = ids_s.cpu().numpy(), sc_s.cpu().numpy()
+    ids_f, sc_f = ids_f.cpu().numpy(), sc_f.cpu().numpy()
+    # the one-call path and the two staged calls are the same kernels: identical bits
+    assert np.array_equal(ids_f, ids_s) and np.array_equal(sc_f, sc_s), "search != coarse+scan"
+    q = synth.to_numpy(q_dev)
+    sel = np.arange(q.shape[0]) if sample is None else np.asarray(sample)
+    qs = np.ascontiguousarray(q[sel])
+    m = METRIC[metric]
+    cn = float(np.sqrt((host.cent.astype(np.float64) ** 2).sum(1)).mean())
+    t0 = time.time()
+    probe_o, pscore_o = oracle.coarse(qs, host.cent, nprobe, m)
+    st_p = check_probes(probe_g[sel], pscore_g[sel], probe_o, pscore_o,
+                        lambda i, c: oracle.pair_scores(qs, host.cent, "f32", m, np.full(len(c), i), c),
+                        metric, TAU["f32"], _scale(qs, cn, metric))
+    ids_o, sc_o = oracle.scan(qs, host.off, host.vec, cfg.dtype, host.ids,
+                              np.ascontiguousarray(probe_g[sel]), k, m)
+    st_k = check_topk(ids_s[sel], sc_s[sel], ids_o, sc_o,
+                      lambda i, ids: oracle.pair_scores(qs, host.vec, cfg.dtype, m, np.full(len(ids), i),
+                                                        host.rows_of(ids)),
+                      metric, tau, _scale(qs, host.xnorm(), metric))
+    # end to end against the unstaged oracle: how often is everything identical
+    _, ids_e, _ = oracle.ivf_search(qs, host.cent, host.off, host.vec, cfg.dtype, host.ids, nprobe, k, m)
+    e2e = float((ids_e == ids_f[sel]).all(1).mean())
+    t_or = time.time() - t0
+    print(f"[parity {label or cfg.name}] nq={len(sel)} probes: {st_p} topk: {st_k} end-to-end exact rows: {e2e:.4f} "
+          f"stats: {st} gpu {t_gpu:.2f}s oracle {t_or:.1f}s", flush=True)
+    ix.close()
+    return st_p, st_k, e2e
+
+
+def _random_index(n, d, nlist, dtype, seed, dup=1, empty=True, device="cuda"):
+    """Unclustered random data: candidates everywhere, many insertions, ragged lists."""
+    g = torch.Generator(device="cpu").manual_seed(seed)
+    base = torch.randn(n // dup, d, generator=g)
+    x = base.repeat(dup, 1)[torch.randperm(n // dup * dup, generator=g)]
+    n = x.shape[0]
+    cent = torch.randn(nlist, d, generator=g)
+    cuts = torch.sort(torch.randint(0, n + 1, (nlist - 1,), generator=g)).values
+    off = torch.cat([torch.zeros(1, dtype=torch.int64), cuts, torch.tensor([n])])
+    if empty and nlist > 2:
+        off[2] = off[1]                      # list 1 is empty
+    ids = torch.randperm(n, generator=g) * 3 + 7
+    cfg = synth.Config("rand", n, d, nlist, "uniform", 0, False, dtype, "ip", 0, "uniform", 0, 0, 0)
+    return synth.Index(cfg, cent.to(device), off, x.to(synth.TORCH_DTYPE[dtype]).to(device), ids.to(device),
+                       torch.arange(nlist))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("metric", ["ip", "l2"])
+def test_random_small(dtype, metric):
+    print(f"case random_small {dtype} {metric}", flush=True)
+    idx = _random_index(6000, 128, 37, dtype, seed=11)
+    g = torch.Generator(device="cpu").manual_seed(5)
+    q = torch.randn(150, 128, generator=g).cuda()
+    compare_all(idx, q, nprobe=9, k=10, metric=metric)
+
+
+@pytest.mark.parametrize("d", [64, 256, 512, 1024])
+def test_dimensions(d):
+    print(f"case dimensions d={d}", flush=True)
+    idx = _random_index(3000, d, 19, "f16", seed=d)
+    g = torch.Generator(device="cpu").manual_seed(6)
+    q = torch.randn(70, d, generator=g).cuda()
+    compare_all(idx, q, nprobe=5, k=7, metric="ip")
+    idx = _random_index(3000, d, 19, "f32", seed=d + 1)
+    compare_all(idx, q, nprobe=5, k=7, metric="l2")
+
+
+@pytest.mark.parametrize("nprobe,k", [(1, 1), (37, 128), (37, 3), (2, 100)])
+def test_extreme_k_and_nprobe(nprobe, k):
+    print(f"case extreme nprobe={nprobe} k={k}", flush=True)
+    idx = _random_index(5000, 64, 37, "f16", seed=23)
+    g = torch.Generator(device="cpu").manual_seed(7)
+    q = torch.randn(65, 64, generator=g).cuda()
+    compare_all(idx, q, nprobe=nprobe, k=k, metric="ip")       # k > candidates for some: padding
+    idx = _random_index(5000, 64, 37, "bf16", seed=24)
+    compare_all(idx, q, nprobe=nprobe, k=k, metric="l2")
+
+
+def test_nprobe_max_many_lists():
+    print("case nprobe=128 over 300 lists", flush=True)
+    idx = _random_index(20000, 64, 300, "f16", seed=29)
+    g = torch.Generator(device="cpu").manual_seed(8)
+    q = torch.randn(33, 64, generator=g).cuda()
+    compare_all(idx, q, nprobe=128, k=20, metric="ip")
+
+
+def test_duplicates_lowest_id_wins_exactly():
+    """Every vector is stored four times: equal scores; the ids must be the oracle's exactly."""
+    print("case duplicates", flush=True)
+    hr = _hr()
+    idx = _random_index(4000, 64, 5, "f32", seed=31, dup=4, empty=False)
+    g = torch.Generator(device="cpu").manual_seed(9)
+    q = torch.randn(120, 64, generator=g).cuda()
+    host = Host(idx)
+    ix = hr.IvfIndex(idx.centroids, idx.list_offsets, idx.list_vectors, idx.list_ids)
+    for metric in ("ip", "l2"):
+        for k in (2, 6, 11):
+            ids, sc = ix.search(q, 5, k, metric)
+            _, ids_o, sc_o = oracle.ivf_search(synth.to_numpy(q), host.cent, host.off, host.vec, "f32", host.ids,
+                                               5, k, METRIC[metric])
+            assert np.array_equal(ids.cpu().numpy(), ids_o), f"{metric} k={k}"
+            np.testing.assert_allclose(sc.cpu().numpy(), sc_o, rtol=1e-4, atol=1e-4)
+    ix.close()
+
+
+def test_variable_length_probe_lists_and_empty_batch():
+    print("case variable-length probes", flush=True)
+    hr = _hr()
+    idx = _random_index(5000, 64, 23, "f16", seed=37)
+    host = Host(idx)
+    g = torch.Generator(device="cpu").manual_seed(10)
+    q = torch.randn(90, 64, generator=g).cuda()
+    ix = hr.IvfIndex(idx.centroids, idx.list_offsets, idx.list_vectors, idx.list_ids)
+    probe = torch.stack([torch.randperm(23, generator=g)[:8] for _ in range(90)]).to(torch.int32)
+    drop = torch.rand(90, 8, generator=g) < 0.4
+    probe[drop] = -1
+    probe[3] = -1                                 # a query with nothing to search
+    probe[4, 0] = 1000                            # out of range = skipped
+    ids, sc = ix.scan(q, probe.cuda(), 10, "ip")
+    ids_o, sc_o = oracle.scan(synth.to_numpy(q), host.off, host.vec, "f16", host.ids, probe.numpy(), 10, oracle.IP)
+    qn = synth.to_numpy(q)
+    check_topk(ids.cpu().numpy(), sc.cpu().numpy(), ids_o, sc_o,
+               lambda i, v: oracle.pair_scores(qn, host.vec, "f16", oracle.IP, np.full(len(v), i), host.rows_of(v)),
+               "ip", TAU["f16"], _scale(qn, host.xnorm(), "ip"))
+    assert (ids[3] == -1).all() and torch.isinf(sc[3]).all()
+    # nq = 0 is a no-op
+    e_ids, e_sc = ix.search(q[:0], 4, 5, "ip")
+    assert e_ids.shape == (0, 5)
+    ix.close()
+
+
+def test_errors_and_determinism():
+    print("case errors + determinism", flush=True)
+    hr = _hr()
+    idx = _random_index(3000, 64, 11, "f16", seed=41)
+    g = torch.Generator(device="cpu").manual_seed(12)
+    q = torch.randn(40, 64, generator=g).cuda()
+    ix = hr.IvfIndex(idx.centroids, idx.list_offsets, idx.list_vectors, idx.list_ids)
+    ids = torch.full((40, 5), 12345, dtype=torch.int64, device="cuda")
+    sc = torch.zeros(40, 5, device="cuda")
+    ws = ix.workspace(40, 4, 5)
+    for args, code in [((12, 5), -1), ((0, 5), -1), ((4, 0), -1), ((4, hr.HR_K_MAX + 1), -1)]:
+        with pytest.raises(hr.HrError) as e:
+            hr.hr_ivf_search(ix.handle, q, 40, args[0], args[1], 0, ids, sc, ws, ws.numel())
+        assert e.value.code == code
+    with pytest.raises(hr.HrError) as e:
+        hr.hr_ivf_search(ix.handle, q, 40, 4, 5, 0, ids, sc, ws, 1024)
+    assert e.value.code == -3
+    with pytest.raises(hr.HrError) as e:
+        hr.hr_ivf_search(ix.handle, q, 40, 4, 5, 7, ids, sc, ws, ws.numel())
+    assert e.value.code == -1
+    torch.cuda.synchronize()
+    assert (ids == 12345).all()                   # nothing was enqueued
+    a = ix.search(q, 4, 5, "l2")
+    b = ix.search(q, 4, 5, "l2")
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+    h = ix.handle
+    ix.close()
+    with pytest.raises(hr.HrError) as e:
+        hr.hr_ivf_free(h)
+    assert e.value.code == -2
+
+
+# ---------------------------------------------------------------- the five workload shapes
+def _run_config(name, sample=None, **scale):
+    cfg = synth.CONFIGS[name]
+    if scale:
+        cfg = synth.scaled(cfg, **scale)
+    print(f"case config {name} {scale or 'full size'}", flush=True)
+    idx = synth.make_index(cfg, "cuda")
+    rounds = synth.make_queries(cfg, idx)
+    out = []
+    for r, q in enumerate(rounds):
+        sel = None
+        if sample is not None:
+            gs = np.random.default_rng(99 + r)
+            sel = np.sort(gs.choice(q.shape[0], size=min(sample, q.shape[0]), replace=False))
+        out.append(compare_all(idx, q, cfg.nprobe, cfg.k, cfg.metric, sample=sel,
+                               label=f"{name} round {r}" if len(rounds) > 1 else name))
+    return out
+
+
+def test_config1_tiny_fp32_full():
+    (st_p, st_k, e2e), = _run_config("C1")
+    assert st_p["exact_set_rate"] >= 0.98 and st_k["exact_id_rows"] >= 0.98
+
+
+def test_config2_medium_fp32_full_size_sampled():
+    (st_p, st_k, e2e), = _run_config("C2", sample=192)
+    assert st_p["exact_set_rate"] >= 0.98 and st_k["exact_id_rows"] >= 0.98
+
+
+def test_config3_skewed_fp16_scaled():
+    _run_config("C3", N=262144, nlist=256, nq=1024, nprobe=32)
+
+
+def test_config3_skewed_fp16_full_size_sampled():
+    (st_p, st_k, e2e), = _run_config("C3", sample=96)
+    assert st_p["exact_set_rate"] >= 0.95
+
+
+def test_config4_iterative_fp16_scaled_rounds():
+    out = _run_config("C4", N=262144, nlist=256, nq=128, nprobe=16)
+    assert len(out) == 8
+
+
+def test_config5_large_bf16_l2_scaled():
+    _run_config("C5", N=524288, nlist=512, nq=512, nprobe=64)
+
+
+@pytest.mark.skipif(os.environ.get("HR_SKIP_C5_FULL") == "1", reason="HR_SKIP_C5_FULL=1")
+def test_config5_large_bf16_l2_full_size_sampled():
+    _run_config("C5", sample=48)
