@@ -4,7 +4,8 @@ Bar: probe lists and top-k ids identical except at score ties or near-ties insid
 the tolerance; scores within TAU relative (1e-4 for float32 storage, 2e-3 for
 16-bit storage).  "Relative" is taken against max(|oracle score|, FLOOR * scale)
 where scale is the magnitude of the operands (|q||x| for inner product,
-|q|^2 + |x|^2 for squared L2): a score that is itself the result of cancellation
+|q|^2 + |x|^2 for squared L2) and FLOOR = 0.02 at d = 768 (floor_for(d) otherwise; callers
+pass floor * magnitude as `scale`): a score that is itself the result of cancellation
 (a distance near zero, an inner product of near-orthogonal vectors) cannot be
 relative-accurate to itself in any float32 arithmetic.
 """
@@ -14,8 +15,15 @@ TAU = {"f32": 1e-4, "f16": 2e-3, "bf16": 2e-3}
 FLOOR = 0.02
 
 
+def floor_for(d):
+    """Rounding one operand to a t-bit significand perturbs a d-term dot product by about
+    2^-t |q||x| / sqrt(d) (independent components), whatever the size of the result; the floor
+    below which errors are judged absolutely scales the same way: 0.02 at d = 768."""
+    return 0.02 * (768.0 / d) ** 0.5
+
+
 def _tol(s_ref, scale, tau):
-    return tau * np.maximum(np.abs(s_ref), FLOOR * scale)
+    return tau * np.maximum(np.abs(s_ref), scale)
 
 
 def _is_ip(metric):
@@ -90,7 +98,7 @@ def check_topk(got_ids, got_scores, ref_ids, ref_scores, score_of, metric, tau, 
         tol = _tol(r_s, sc, tau)
         err = np.abs(g_s - r_s)
         assert np.all(err <= tol), f"query {q}: rank-wise score error {err.max()} > tol"
-        max_rel = max(max_rel, float((err / np.maximum(np.abs(r_s), FLOOR * sc)).max()))
+        max_rel = max(max_rel, float((err / np.maximum(np.abs(r_s), sc)).max()))
         # best-first up to rounding
         assert np.all(_worse_by(g_s[:-1], g_s[1:], metric) <= 0), f"query {q}: not sorted"
         if np.array_equal(g_i, r_i):

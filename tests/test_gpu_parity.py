@@ -11,7 +11,7 @@ import torch
 
 import oracle
 import synth
-from compare import TAU, check_probes, check_topk
+from compare import TAU, check_probes, check_topk, floor_for
 
 pytestmark = pytest.mark.gpu
 METRIC = {"ip": oracle.IP, "l2": oracle.L2}
@@ -46,8 +46,6 @@ class Host:
     def xnorm(self):
         n = min(4096, self.vec.shape[0])
         sel = np.linspace(0, self.vec.shape[0] - 1, n).astype(np.int64)
-        q1 = np.ones((1, 1), np.float32)
-        del q1
         v = self.vec[sel]
         if self.cfg.dtype == "bf16":
             v = (v.astype(np.uint32) << 16).view(np.float32)
@@ -55,8 +53,9 @@ class Host:
 
 
 def _scale(q, xn, metric):
+    """floor * operand magnitude per query: below it score errors are judged absolutely"""
     qn = np.sqrt((q.astype(np.float64) ** 2).sum(1))
-    return qn * xn if metric == "ip" else qn ** 2 + xn ** 2
+    return floor_for(q.shape[1]) * (qn * xn if metric == "ip" else qn ** 2 + xn ** 2)
 
 
 def compare_all(index, queries, nprobe, k, metric, sample=None, label=""):
