@@ -20,7 +20,7 @@ HEADERS = [os.path.join(CSRC, "common.h"), os.path.join(CSRC, "scan_kernel.h"),
            os.path.join(ROOT, "include", "hr_ivf.h")]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-I", os.path.join(ROOT, "include"), "-I", CSRC]
+         "-I", os.path.join(ROOT, "include"), "-I", CSRC] + os.environ.get("HR_EXTRA_HIPCC_FLAGS", "").split()
 
 
 def _stale(target, deps):

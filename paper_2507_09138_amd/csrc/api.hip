@@ -7,29 +7,56 @@
 #include "common.h"
 
 namespace hr {
-hipError_t launch_scan_f32(int d, const ScanArgs& a, int grid, size_t lds, hipStream_t s);
-hipError_t launch_scan_f16(int d, const ScanArgs& a, int grid, size_t lds, hipStream_t s);
-hipError_t launch_scan_bf16(int d, const ScanArgs& a, int grid, size_t lds, hipStream_t s);
+hipError_t launch_scan_f32(int d, const ScanArgs& a, int ncs, int grid, size_t lds, hipStream_t s);
+hipError_t launch_scan_f16(int d, const ScanArgs& a, int ncs, int grid, size_t lds, hipStream_t s);
+hipError_t launch_scan_bf16(int d, const ScanArgs& a, int ncs, int grid, size_t lds, hipStream_t s);
 
-hipError_t launch_scan(int dtype, int d, const ScanArgs& a, int grid, size_t lds, hipStream_t s)
+hipError_t launch_seed_f32(int d, const SeedArgs& a, hipStream_t s);
+hipError_t launch_seed_f16(int d, const SeedArgs& a, hipStream_t s);
+hipError_t launch_seed_bf16(int d, const SeedArgs& a, hipStream_t s);
+
+hipError_t launch_seed(int dtype, int d, const SeedArgs& a, hipStream_t s)
 {
     switch (dtype) {
-    case HR_F32: return launch_scan_f32(d, a, grid, lds, s);
-    case HR_F16: return launch_scan_f16(d, a, grid, lds, s);
-    case HR_BF16: return launch_scan_bf16(d, a, grid, lds, s);
+    case HR_F32: return launch_seed_f32(d, a, s);
+    case HR_F16: return launch_seed_f16(d, a, s);
+    case HR_BF16: return launch_seed_bf16(d, a, s);
     default: return hipErrorInvalidValue;
     }
 }
 
-size_t scan_lds_bytes(int dtype, int d, int k)
+hipError_t launch_scan(int dtype, int d, const ScanArgs& a, int ncs, int grid, size_t lds, hipStream_t s)
+{
+    switch (dtype) {
+    case HR_F32: return launch_scan_f32(d, a, ncs, grid, lds, s);
+    case HR_F16: return launch_scan_f16(d, a, ncs, grid, lds, s);
+    case HR_BF16: return launch_scan_bf16(d, a, ncs, grid, lds, s);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+// LDS bytes of one workgroup with ncs column sets per wave (must match the carve-up at the top
+// of k_scan)
+size_t scan_lds_bytes(int dtype, int d, int k, int ncs)
 {
     const int planes = dtype == HR_F32 ? 2 : 1;
     const size_t buf = (size_t)kBlockRows * (d * 2 + kRowPad) * planes;
     const size_t cap = sel_cap(k);
-    const size_t cw = cols_per_item(dtype);
-    return 2 * buf + cw * cap * sizeof(Cand) + 4 * cap * sizeof(int64_t) + cw * sizeof(int) + 16;
+    const size_t cw = (size_t)cols_per_wave(dtype) * ncs * 4;
+    return 2 * buf + cw * cap * sizeof(Cand) + cw * sizeof(int) + 16;
 }
 }  // namespace hr
+
+static constexpr int kLdsLimit = 160 * 1024;      // LDS per workgroup on gfx950
+
+// column sets per wave for a scan: 2 (twice the query columns per pass over the rows) when the
+// selection buffers still fit in LDS, else 1; 0 = does not fit at all
+static int pick_ncs(int dtype, int d, int k)
+{
+    if (hr::scan_lds_bytes(dtype, d, k, 2) <= (size_t)kLdsLimit) return 2;
+    if (hr::scan_lds_bytes(dtype, d, k, 1) <= (size_t)kLdsLimit) return 1;
+    return 0;
+}
 
 using namespace hr;
 
@@ -79,14 +106,14 @@ static size_t align_up(size_t v) { return (v + HR_WORKSPACE_ALIGN - 1) & ~(size_
 // Layout of the caller's workspace for one batch shape.  Offsets in bytes.
 struct Plan {
     // coarse step: centroid table scanned with all queries as one dense bucket
-    int cw_c, nqt_c, seg_c, nseg_c, items_c;
+    int nw_c /* column sets per wave */, cw_c, nqt_c, seg_c, nseg_c, items_c;
     // list scan
-    int cw_s, item_cap;
+    int nw_s, cw_s, item_cap;
     size_t o_zero, n_zero;          // ints cleared per call: list_w[nlist], dyn[DYN_COUNT], counters[8]
     size_t o_thr;                   // 2*nq ints set to "-inf"
     size_t o_qop_c, o_qnorm_c, o_qop_s, o_qnorm_s;
     size_t o_probe;
-    size_t o_pair_entry, o_bucket_off, o_bucket_q, o_item_base, o_item_tab;
+    size_t o_pair_entry, o_bucket_off, o_bucket_q, o_item_base, o_item_tab, o_xq;
     size_t o_slot_cnt, o_slot_ent;
     size_t total;
 };
@@ -96,7 +123,9 @@ static Plan make_plan(const hr_ivf_index* ix, int64_t nq, int nprobe, int k)
     Plan p{};
     const int64_t nlist = ix->nlist;
     const int kk = k > nprobe ? k : nprobe;      // slots are shared by the two scans
-    p.cw_c = cols_per_item(HR_F32);
+    p.nw_c = pick_ncs(HR_F32, ix->d, nprobe);
+    p.nw_s = pick_ncs(ix->dtype, ix->d, k);
+    p.cw_c = cols_per_wave(HR_F32) * 4 * (p.nw_c ? p.nw_c : 1);
     p.nqt_c = (int)((nq + p.cw_c - 1) / p.cw_c);
     int64_t seg = (nlist * (int64_t)p.nqt_c + 2047) / 2048;
     seg = (seg + 15) & ~15LL;
@@ -105,13 +134,13 @@ static Plan make_plan(const hr_ivf_index* ix, int64_t nq, int nprobe, int k)
     p.seg_c = (int)seg;
     p.nseg_c = (int)((nlist + seg - 1) / seg);
     p.items_c = p.nseg_c * p.nqt_c;
-    p.cw_s = cols_per_item(ix->dtype);
+    p.cw_s = cols_per_wave(ix->dtype) * 4 * (p.nw_s ? p.nw_s : 1);
     const int64_t pairs = nq * nprobe;
     p.item_cap = (int)(kItemTarget + pairs / p.cw_s + (pairs < nlist ? pairs : nlist) + 8);
 
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
-    p.n_zero = (size_t)nlist + DYN_COUNT + 8;
+    p.n_zero = (size_t)nlist + DYN_COUNT + 24;     // + 8 counters, 8 queue lengths, 8 queue heads
     p.o_zero = take(p.n_zero * 4);
     p.o_thr = take((size_t)nq * 2 * 4);
     p.o_qop_c = take((size_t)nq * 2 * ix->d * 2);
@@ -125,6 +154,7 @@ static Plan make_plan(const hr_ivf_index* ix, int64_t nq, int nprobe, int k)
     p.o_bucket_q = take((size_t)pairs * 4);
     p.o_item_base = take((size_t)(nlist + 1) * 4);
     p.o_item_tab = take((size_t)p.item_cap * sizeof(int4));
+    p.o_xq = take((size_t)p.item_cap * 8 * 4);
     size_t slots_c = (size_t)p.items_c * p.cw_c, slots_s = (size_t)p.item_cap * p.cw_s;
     size_t slots = slots_c > slots_s ? slots_c : slots_s;
     p.o_slot_cnt = take(slots * 4);
@@ -288,18 +318,22 @@ size_t hr_ivf_workspace_bytes(const hr_ivf_index* ix, int64_t nq, int32_t nprobe
 }  // extern "C"
 
 // ---------------------------------------------------------------------------------------
-static int scan_grid(const hr_ivf_index* ix, size_t lds)
+// persistent workgroups: as many as can be resident (LDS and, for 8-wave groups, registers)
+static long long* g_dbg = nullptr;   // TEMP
+extern "C" void hr_debug_scan_timing(void* p) { g_dbg = (long long*)p; }
+
+static int scan_grid(const hr_ivf_index* ix, size_t lds, int nw)
 {
-    int occ = (int)((size_t)ix->lds_limit / lds);
+    int occ = (int)((size_t)kLdsLimit / lds);
     if (occ < 1) occ = 1;
-    if (occ > 3) occ = 3;
+    if (occ > (nw == 8 ? 1 : 2)) occ = nw == 8 ? 1 : 2;
     return ix->num_cus * occ;
 }
 
 static int enqueue_clear(const Plan& p, char* ws, int64_t nq, hipStream_t s)
 {
     HR_HIP(launch_fill_i32((int*)(ws + p.o_zero), (int64_t)p.n_zero, 0, s));
-    HR_HIP(launch_fill_i32((int*)(ws + p.o_thr), nq * 2, kEncNegInf, s));
+    HR_HIP(launch_fill_i32((int*)(ws + p.o_thr), nq * 2, (int)kKeyNegInf, s));
     return HR_OK;
 }
 
@@ -307,16 +341,16 @@ static int enqueue_clear(const Plan& p, char* ws, int64_t nq, hipStream_t s)
 static int enqueue_coarse(const hr_ivf_index* ix, const Plan& p, char* ws, int64_t nq, int nprobe,
                           int metric, int32_t* out_probe, float* out_scores, hipStream_t s)
 {
-    const size_t lds = scan_lds_bytes(HR_F32, ix->d, nprobe);
-    if (lds > (size_t)ix->lds_limit)
-        return fail(HR_ERR_UNSUPPORTED, "coarse step needs %zu bytes of LDS (d=%d, nprobe=%d), device has %d", lds, ix->d, nprobe, ix->lds_limit);
+    if (!p.nw_c)
+        return fail(HR_ERR_UNSUPPORTED, "coarse step does not fit in LDS (d=%d, nprobe=%d)", ix->d, nprobe);
+    const size_t lds = scan_lds_bytes(HR_F32, ix->d, nprobe, p.nw_c);
     int* zero = (int*)(ws + p.o_zero);
     ScanArgs a{};
     a.rows = ix->centroids;
     a.row_norm = ix->d_cent_norm;
     a.row_ids = nullptr;
     a.qop = ws + p.o_qop_c;
-    a.thr = (int*)(ws + p.o_thr);
+    a.thr = (uint32_t*)(ws + p.o_thr);
     a.slot_cnt = (int*)(ws + p.o_slot_cnt);
     a.slot_ent = (Cand*)(ws + p.o_slot_ent);
     a.work_counter = zero + ix->nlist + DYN_COUNT;
@@ -326,9 +360,9 @@ static int enqueue_coarse(const hr_ivf_index* ix, const Plan& p, char* ws, int64
     a.dense_seg_rows = p.seg_c;
     a.dense_nrows = (int)ix->nlist;
     a.nq = (int)nq; a.k = nprobe; a.cap = sel_cap(nprobe); a.l2 = metric == HR_METRIC_L2;
-    int grid = scan_grid(ix, lds);
+    int grid = scan_grid(ix, lds, p.nw_c);
     if (grid > p.items_c) grid = p.items_c;
-    HR_HIP(launch_scan(HR_F32, ix->d, a, grid, lds, s));
+    HR_HIP(launch_scan(HR_F32, ix->d, a, p.nw_c, grid, lds, s));
     MergeArgs m{};
     m.slot_cnt = a.slot_cnt; m.slot_ent = a.slot_ent;
     m.row_ids = nullptr;
@@ -345,9 +379,9 @@ static int enqueue_coarse(const hr_ivf_index* ix, const Plan& p, char* ws, int64
 static int enqueue_scan(const hr_ivf_index* ix, const Plan& p, char* ws, int64_t nq, const int32_t* probe,
                         int nprobe, int k, int metric, int64_t* out_ids, float* out_scores, hipStream_t s)
 {
-    const size_t lds = scan_lds_bytes(ix->dtype, ix->d, k);
-    if (lds > (size_t)ix->lds_limit)
-        return fail(HR_ERR_UNSUPPORTED, "scan needs %zu bytes of LDS (d=%d, k=%d), device has %d", lds, ix->d, k, ix->lds_limit);
+    if (!p.nw_s)
+        return fail(HR_ERR_UNSUPPORTED, "list scan does not fit in LDS (d=%d, k=%d)", ix->d, k);
+    const size_t lds = scan_lds_bytes(ix->dtype, ix->d, k, p.nw_s);
     int* zero = (int*)(ws + p.o_zero);
     BucketArgs b{};
     b.probe = probe; b.nq = (int)nq; b.nprobe = nprobe; b.nlist = (int)ix->nlist; b.cw = p.cw_s;
@@ -359,15 +393,28 @@ static int enqueue_scan(const hr_ivf_index* ix, const Plan& p, char* ws, int64_t
     b.item_base = (int*)(ws + p.o_item_base);
     b.item_tab = (int4*)(ws + p.o_item_tab);
     b.dyn = zero + ix->nlist;
+    b.xq = (int*)(ws + p.o_xq);
+    b.xq_count = zero + ix->nlist + DYN_COUNT + 8;
     b.item_cap = p.item_cap;
     HR_HIP(launch_bucketing(b, s));
+
+    // starting lower bounds from the first rows of every query's best-ranked list
+    SeedArgs sd{};
+    sd.rows = ix->vectors; sd.row_norm = ix->d_row_norm; sd.qop = ws + p.o_qop_s;
+    sd.probe = probe; sd.list_off = ix->d_list_off;
+    sd.thr = (uint32_t*)(ws + p.o_thr) + nq;
+    sd.nq = (int)nq; sd.nprobe = nprobe; sd.nlist = (int)ix->nlist; sd.k = k;
+    sd.seed_rows = k + 28 < 64 ? 64 : ((k + 28 + 15) & ~15);
+    if (sd.seed_rows > 192) sd.seed_rows = 192;
+    sd.l2 = metric == HR_METRIC_L2;
+    HR_HIP(launch_seed(ix->dtype, ix->d, sd, s));
 
     ScanArgs a{};
     a.rows = ix->vectors;
     a.row_norm = ix->d_row_norm;
     a.row_ids = ix->ids;
     a.qop = ws + p.o_qop_s;
-    a.thr = (int*)(ws + p.o_thr) + nq;
+    a.thr = (uint32_t*)(ws + p.o_thr) + nq;
     a.slot_cnt = (int*)(ws + p.o_slot_cnt);
     a.slot_ent = (Cand*)(ws + p.o_slot_ent);
     a.work_counter = zero + ix->nlist + DYN_COUNT + 1;
@@ -376,12 +423,17 @@ static int enqueue_scan(const hr_ivf_index* ix, const Plan& p, char* ws, int64_t
     a.bucket_q = b.bucket_q;
     a.item_tab = b.item_tab;
     a.dyn = b.dyn;
+    a.xq = b.xq;
+    a.xq_count = b.xq_count;
+    a.xq_head = zero + ix->nlist + DYN_COUNT + 16;
+    a.xq_stride = p.item_cap;
+    a.dbg = g_dbg;
     a.dense = 0;
     a.nq = (int)nq; a.k = k; a.cap = sel_cap(k); a.l2 = metric == HR_METRIC_L2;
     hr_ivf_index* mix = const_cast<hr_ivf_index*>(ix);
     const bool timed = mix->prof_ev && mix->prof_n < mix->prof_cap;
     if (timed) HR_HIP(hipEventRecord(mix->prof_ev[2 * mix->prof_n], s));
-    HR_HIP(launch_scan(ix->dtype, ix->d, a, scan_grid(ix, lds), lds, s));
+    HR_HIP(launch_scan(ix->dtype, ix->d, a, p.nw_s, scan_grid(ix, lds, p.nw_s), lds, s));
     if (timed) {
         HR_HIP(hipEventRecord(mix->prof_ev[2 * mix->prof_n + 1], s));
         mix->prof_n++;

@@ -228,8 +228,12 @@ __global__ void k_bucket_scatter(BucketArgs a)
     a.bucket_q[a.bucket_off[l] + e] = (int)(i / a.nprobe);
 }
 
-// One wave per list writes the list's work items: segment-major, query tile minor, so the
-// tiles that re-read a segment run next to each other in time.
+// One wave per list writes the list's work items and queues them.  Items are numbered
+// list-major (segment-major, query tile minor inside a list); that number addresses the
+// item's result slots.  The order of execution is given by eight queues, one per XCD: all
+// query tiles of one (list, segment) go to the same queue, next to each other, so the
+// workgroups that re-read that segment run on one XCD at about the same time and share it
+// through that XCD's L2.
 __global__ __launch_bounds__(256) void k_item_expand(BucketArgs a)
 {
     int l = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -240,11 +244,18 @@ __global__ __launch_bounds__(256) void k_item_expand(BucketArgs a)
     if (w <= 0 || len <= 0) return;
     int seg = a.dyn[DYN_SEG_ROWS];
     int nqt = (w + a.cw - 1) / a.cw;
-    long long n = (long long)((len + seg - 1) / seg) * nqt;
+    int nseg = (len + seg - 1) / seg;
     long long base = a.item_base[l];
-    for (long long i = lane; i < n; i += 64) {
-        long long idx = base + i;
-        if (idx < a.item_cap) a.item_tab[idx] = make_int4(l, (int)(i / nqt), (int)(i % nqt), 0);
+    for (int s = lane; s < nseg; s += 64) {
+        int x = (l + s) & 7;
+        int pos = atomicAdd(&a.xq_count[x], nqt);
+        for (int t = 0; t < nqt; t++) {
+            long long idx = base + (long long)s * nqt + t;
+            if (idx < a.item_cap && pos + t < a.item_cap) {
+                a.item_tab[idx] = make_int4(l, s, t, 0);
+                a.xq[(size_t)x * a.item_cap + pos + t] = (int)idx;
+            }
+        }
     }
 }
 
@@ -269,7 +280,7 @@ constexpr int kMergeCap = 256;     // candidates buffered per query (k <= 128, u
 __global__ __launch_bounds__(256) void k_merge(MergeArgs a)
 {
     __shared__ Cand s_buf[4][kMergeCap];
-    __shared__ int64_t s_tie[4][kMergeCap];
+    __shared__ int64_t s_tie[4][HR_K_MAX];
     __shared__ int s_pref[4][HR_NPROBE_MAX + 1];
     __shared__ int s_cnt[4];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -312,7 +323,7 @@ __global__ __launch_bounds__(256) void k_merge(MergeArgs a)
     if (lane == 0) s_cnt[wave] = 0;
     wave_sync();
 
-    float thr = -__builtin_inff();
+    uint32_t thr = 0;                              // below every encoded key
     for (int f0 = 0; f0 < total; f0 += 64) {
         const int f = f0 + lane;
         int c = 0;
@@ -343,25 +354,25 @@ __global__ __launch_bounds__(256) void k_merge(MergeArgs a)
         for (int j = 0; j < maxc; j++) {
             if (j < c) {
                 Cand cd = a.slot_ent[slot * k + j];
-                if (__builtin_bit_cast(float, cd.key) >= thr) {
+                if (cd.key >= thr) {
                     int pos = atomicAdd(&s_cnt[wave], 1);
                     buf[pos] = cd;
                 }
             }
             wave_sync();
-            int n = s_cnt[wave];
+            int n = __builtin_amdgcn_readfirstlane(s_cnt[wave]);
             if (n > kMergeCap - 64) {
-                float kth = wave_prune<4>(buf, n, k, a.row_ids, tie);
-                thr = fmaxf(thr, kth);
+                uint32_t kth = wave_select<4>(buf, n, k, a.row_ids);
+                thr = kth > thr ? kth : thr;
                 if (lane == 0) s_cnt[wave] = k;
                 wave_sync();
             }
         }
     }
     wave_sync();
-    int n = s_cnt[wave];
+    int n = __builtin_amdgcn_readfirstlane(s_cnt[wave]);
     if (n > k) {
-        wave_prune<4>(buf, n, k, a.row_ids, tie);
+        wave_select<4>(buf, n, k, a.row_ids);
         n = k;
     }
     wave_sync();
@@ -379,20 +390,18 @@ __global__ __launch_bounds__(256) void k_merge(MergeArgs a)
     wave_sync();
     int pos[2] = {0, 0};
     for (int i = 0; i < n; i++) {
-        float so = __builtin_bit_cast(float, buf[i].key);
+        uint32_t so = buf[i].key;
         int64_t oid = tie[i];
 #pragma unroll
-        for (int m = 0; m < 2; m++) {
-            float sm = __builtin_bit_cast(float, e[m].key);
-            pos[m] += (so > sm || (so == sm && oid < id[m])) ? 1 : 0;
-        }
+        for (int m = 0; m < 2; m++)
+            pos[m] += (so > e[m].key || (so == e[m].key && oid < id[m])) ? 1 : 0;
     }
     const float qn = (a.l2 && a.qnorm) ? a.qnorm[q] : 0.f;
 #pragma unroll
     for (int m = 0; m < 2; m++) {
         int idx = lane + 64 * m;
         if (idx < n) {
-            float key = __builtin_bit_cast(float, e[m].key);
+            float key = dec_key(e[m].key);
             float score = a.l2 ? fmaxf(qn - key, 0.f) : key;
             size_t o = (size_t)q * k + pos[m];
             if (a.out_ids) a.out_ids[o] = id[m];

@@ -8,40 +8,41 @@
 namespace hr {
 
 constexpr int kWave = 64;
-constexpr int kScanThreads = 256;          // 4 waves per workgroup
 constexpr int kBlockRows = 16;             // rows per MFMA block (M of 16x16x32)
-constexpr int kRowPad = 16;                // bytes of LDS padding per staged row (bank spread)
+constexpr int kRowPad = 32;                // bytes of LDS padding per staged row: measured conflict-free
+                                           // for the 16-rows x 16-byte MFMA fragment reads (16 is 2-way)
 constexpr int kAppendMax = 16;             // most candidates one column can gain per block
-constexpr int kMinSegRows = 128;           // smallest rows-per-work-item
-constexpr int kItemTarget = 32768;         // aimed number of scan work items per batch
+constexpr int kMinSegRows = 256;           // smallest rows-per-work-item
+constexpr int kItemTarget = 8192;         // aimed number of scan work items per batch
 
-// columns (queries) per work item: 16 per wave when the query operand is one binary16
-// row, 8 per wave when it is a (hi, lo) pair occupying two MFMA columns.
-__host__ __device__ constexpr int cols_per_item(int dtype) { return dtype == HR_F16 ? 64 : 32; }
+// columns (queries) per wave: 16 when the query operand is one binary16 row, 8 when it is a
+// (hi, lo) pair occupying two MFMA columns.  A wave owns ncs such sets, a work item 4 waves' worth.
+__host__ __device__ constexpr int cols_per_wave(int dtype) { return dtype == HR_F16 ? 16 : 8; }
 
-// selection buffer capacity per column for a given k
+// selection buffer capacity per column for a given k: room for k kept entries plus a batch of
+// new ones between two prunes (a prune costs about the same for any fill up to 64 entries per
+// lane slot, so bigger batches make each candidate cheaper), bounded by LDS
 __host__ __device__ constexpr int sel_cap(int k)
 {
-    int a = 2 * k + 12, b = k + 60;
-    int c = a < b ? a : b;
+    int c = k <= 24 ? 64 : (k <= 64 ? 128 : 192);
     if (c < k + kAppendMax + 4) c = k + kAppendMax + 4;
-    return (c + 3) & ~3;
+    return c;
 }
 
-// order-preserving map float -> int32 (for atomicMax on scores)
-__host__ __device__ inline int enc_order(float f)
+// order-preserving map float -> uint32 (larger float = larger unsigned), and back
+__host__ __device__ inline uint32_t enc_key(float f)
 {
-    int b = __builtin_bit_cast(int, f);
-    return b ^ ((b >> 31) & 0x7fffffff);
+    uint32_t b = __builtin_bit_cast(uint32_t, f);
+    return b ^ ((b >> 31) ? 0xffffffffu : 0x80000000u);
 }
-__host__ __device__ inline float dec_order(int i)
+__host__ __device__ inline float dec_key(uint32_t u)
 {
-    int b = i ^ ((i >> 31) & 0x7fffffff);
+    uint32_t b = (u >> 31) ? (u ^ 0x80000000u) : ~u;
     return __builtin_bit_cast(float, b);
 }
-constexpr int kEncNegInf = (int)0x807fffff;   // enc_order(-inf): 0xff800000 ^ 0x7fffffff
+constexpr uint32_t kKeyNegInf = 0x007fffffu;   // enc_key(-inf)
 
-// One candidate: key (float bits, larger is better) and row number.
+// One candidate: key (enc_key of the score, larger is better) and row number.
 struct Cand { uint32_t key; uint32_t row; };
 
 // Arguments of the scan kernel (both uses: centroid table with all queries as one dense
@@ -51,7 +52,7 @@ struct ScanArgs {
     const float* row_norm;      // [nrows] squared norms (used when l2 != 0)
     const int64_t* row_ids;     // [nrows] labels, or nullptr: label = row number
     const void* qop;            // query operand rows (layout depends on dtype)
-    int* thr;                   // [nq] running per-query lower bound of the k-th key (ordered int)
+    uint32_t* thr;              // [nq] running per-query lower bound of the k-th key (enc_key)
     int* slot_cnt;              // [items * CW]
     Cand* slot_ent;             // [items * CW * k]
     int* work_counter;          // zeroed before launch
@@ -61,9 +62,24 @@ struct ScanArgs {
     const int* bucket_q;        // [pairs] query index per bucket entry
     const int4* item_tab;       // [items] (list, segment, query tile, 0)
     const int* dyn;             // device scalars: [0] = items, [1] = rows per segment
+    const int* xq;              // [8][xq_stride] item numbers queued per XCD
+    const int* xq_count;        // [8] queue lengths
+    int* xq_head;               // [8] next position to pop (zeroed before launch)
+    int xq_stride;
     // dense mode (dense != 0): one list = all rows, bucket = all queries
     int dense, dense_items, dense_nqt, dense_seg_rows, dense_nrows;
     int nq, k, cap, l2;
+    long long* dbg;             // per-workgroup phase timers (only in HR_SCAN_TIMING builds)
+};
+
+struct SeedArgs {
+    const void* rows;           // [nrows, d] storage
+    const float* row_norm;      // [nrows]
+    const void* qop;            // query operand rows
+    const int* probe;           // [nq, nprobe]; column 0 is the list used
+    const int* list_off;        // [nlist+1]
+    uint32_t* thr;              // [nq]
+    int nq, nprobe, nlist, k, seed_rows, l2;
 };
 
 // Device scalars written by the bucketing kernels (ints in workspace)
@@ -90,9 +106,10 @@ struct MergeArgs {
 };
 
 // launchers implemented in the .hip files
-hipError_t launch_scan(int dtype, int d, const ScanArgs& a, int grid, size_t lds_bytes, hipStream_t s);
-size_t scan_lds_bytes(int dtype, int d, int k);
+hipError_t launch_scan(int dtype, int d, const ScanArgs& a, int ncs, int grid, size_t lds_bytes, hipStream_t s);
+size_t scan_lds_bytes(int dtype, int d, int k, int ncs);
 hipError_t launch_merge(const MergeArgs& a, hipStream_t s);
+hipError_t launch_seed(int dtype, int d, const SeedArgs& a, hipStream_t s);
 hipError_t launch_row_norms(const void* rows, int dtype, int64_t nrows, int d, float* out, hipStream_t s);
 hipError_t launch_prep_queries(const float* q, int64_t nq, int d, int dtype, void* qop_coarse,
                                float* qnorm_coarse, void* qop_scan, float* qnorm_scan, hipStream_t s);
@@ -109,6 +126,8 @@ struct BucketArgs {
     int* item_base;             // [nlist+1]
     int4* item_tab;             // [item_cap]
     int* dyn;                   // device scalars
+    int* xq;                    // [8][item_cap] per-XCD queues of item numbers
+    int* xq_count;              // [8] (zeroed before launch)
     int item_cap;
 };
 hipError_t launch_bucketing(const BucketArgs& a, hipStream_t s);
