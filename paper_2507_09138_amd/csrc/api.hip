@@ -43,7 +43,7 @@ size_t scan_lds_bytes(int dtype, int d, int k, int ncs)
     const size_t buf = (size_t)kBlockRows * (d * 2 + kRowPad) * planes;
     const size_t cap = sel_cap(k);
     const size_t cw = (size_t)cols_per_wave(dtype) * ncs * 4;
-    return 2 * buf + cw * cap * sizeof(Cand) + cw * sizeof(int) + 16;
+    return 2 * buf + cw * cap * sizeof(Cand) + cw * sizeof(int) + 2 * kBlockRows * sizeof(float) + 16;
 }
 }  // namespace hr
 

@@ -17,14 +17,31 @@
 //            query likewise; the four partial products are recombined with their scales,
 //            which keeps about 22 bits of each factor with float32 accumulation.
 #pragma once
+#include <utility>
+
 #include "common.h"
 
 namespace hr {
+
+// compile-time loop: f(std::integral_constant<int, 0>) ... f(std::integral_constant<int, N-1>)
+template <typename F, int... I>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>)
+{
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f)
+{
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef _Float16 half4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
+// 16 bytes as a register vector (a struct such as HIP's uint4 is copied with memcpy semantics,
+// which can pin a local array of them to scratch memory)
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
 
@@ -156,18 +173,22 @@ struct ScanShape {
 #define HR_TOC(acc, var)
 #endif
 
+// Every thread always loads (chunks past the end of the segment re-read its last chunk; the
+// rows they would belong to are masked out of the selection): an unconditional load keeps the
+// ring registers free of the zero-fill writes that would otherwise have to wait for the
+// loads still in flight.
 template <typename S>
-__device__ __forceinline__ void load_block(const char* src, int valid_chunks, uint4 (&regs)[S::nld])
+__device__ __forceinline__ void load_block(const char* src, int valid_chunks, u32x4 (&regs)[S::nld])
 {
 #pragma unroll
     for (int m = 0; m < S::nld; m++) {
-        int c = threadIdx.x + S::threads * m;
-        regs[m] = (c < valid_chunks) ? *(const uint4*)(src + (size_t)c * 16) : uint4{0, 0, 0, 0};
+        int c = min((int)threadIdx.x + S::threads * m, valid_chunks - 1);
+        regs[m] = *(const u32x4*)(src + (size_t)c * 16);
     }
 }
 
 template <int DT, typename S>
-__device__ __forceinline__ void stage_block(char* buf, const uint4 (&regs)[S::nld])
+__device__ __forceinline__ void stage_block(char* buf, const u32x4 (&regs)[S::nld])
 {
 #pragma unroll
     for (int m = 0; m < S::nld; m++) {
@@ -176,8 +197,8 @@ __device__ __forceinline__ void stage_block(char* buf, const uint4 (&regs)[S::nl
         constexpr int cpr = S::rowb / 16;              // chunks per row
         int r = c / cpr, p = c % cpr;
         if constexpr (DT == HR_F32) {
-            float x[4] = {__builtin_bit_cast(float, regs[m].x), __builtin_bit_cast(float, regs[m].y),
-                          __builtin_bit_cast(float, regs[m].z), __builtin_bit_cast(float, regs[m].w)};
+            const floatx4 xv = __builtin_bit_cast(floatx4, regs[m]);
+            const float x[4] = {xv[0], xv[1], xv[2], xv[3]};
             half4 hi, lo;
 #pragma unroll
             for (int i = 0; i < 4; i++) {
@@ -188,7 +209,7 @@ __device__ __forceinline__ void stage_block(char* buf, const uint4 (&regs)[S::nl
             *(half4*)(buf + r * S::rowp + p * 8) = hi;
             *(half4*)(buf + S::plane_bytes + r * S::rowp + p * 8) = lo;
         } else {
-            *(uint4*)(buf + r * S::rowp + p * 16) = regs[m];
+            *(u32x4*)(buf + r * S::rowp + p * 16) = regs[m];
         }
     }
 }
@@ -199,7 +220,7 @@ __device__ __forceinline__ void stage_block(char* buf, const uint4 (&regs)[S::nl
 // barriers keep the compiler from sinking each read next to its use, which would expose the
 // LDS latency 24 times per block).
 template <int DT, int KSTEPS, int NCS, int NA, typename S>
-__device__ __forceinline__ void mfma_block(const char* ap, const uint4 (&bfrag)[NCS][KSTEPS], floatx4 (&acc)[NCS][2])
+__device__ __forceinline__ void mfma_block(const char* ap, const u32x4 (&bfrag)[NCS][KSTEPS], floatx4 (&acc)[NCS][2])
 {
     constexpr int G = KSTEPS < 8 ? KSTEPS : 8;       // k-steps per group
     constexpr int NG = KSTEPS / G;
@@ -207,11 +228,11 @@ __device__ __forceinline__ void mfma_block(const char* ap, const uint4 (&bfrag)[
     static_assert(KSTEPS % G == 0, "k-steps must split into whole groups");
 #pragma unroll
     for (int s = 0; s < NA; s++) { acc[s][0] = floatx4{0.f, 0.f, 0.f, 0.f}; acc[s][1] = floatx4{0.f, 0.f, 0.f, 0.f}; }
-    uint4 af[2][P][G];
+    u32x4 af[2][P][G];
 #pragma unroll
     for (int i = 0; i < G; i++)
 #pragma unroll
-        for (int pl = 0; pl < P; pl++) af[0][pl][i] = *(const uint4*)(ap + pl * S::plane_bytes + i * 64);
+        for (int pl = 0; pl < P; pl++) af[0][pl][i] = *(const u32x4*)(ap + pl * S::plane_bytes + i * 64);
 #pragma unroll
     for (int gi = 0; gi < NG; gi++) {
         if (gi + 1 < NG) {
@@ -219,7 +240,7 @@ __device__ __forceinline__ void mfma_block(const char* ap, const uint4 (&bfrag)[
             for (int i = 0; i < G; i++)
 #pragma unroll
                 for (int pl = 0; pl < P; pl++)
-                    af[(gi + 1) & 1][pl][i] = *(const uint4*)(ap + pl * S::plane_bytes + ((gi + 1) * G + i) * 64);
+                    af[(gi + 1) & 1][pl][i] = *(const u32x4*)(ap + pl * S::plane_bytes + ((gi + 1) * G + i) * 64);
         }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -261,11 +282,12 @@ __global__ __launch_bounds__(kScanWaves * 64, 1) void k_scan(ScanArgs a)
     constexpr int WC = S::wcols;
     constexpr int PF = S::pf;
     extern __shared__ __align__(16) char smem[];
-    // LDS: [2 staging buffers][selection buffers cw*cap][cnt cw][item]
+    // LDS: [2 staging buffers][selection buffers cw*cap][cnt cw][2 x 16 row norms][item]
     char* stage = smem;
     Cand* sel = (Cand*)(smem + 2 * S::buf_bytes);
     int* cnt = (int*)(sel + S::cw * a.cap);
-    int* s_item = cnt + S::cw;
+    float* nstage = (float*)(cnt + S::cw);
+    int* s_item = (int*)(nstage + 2 * kBlockRows);
 
     const int lane = lane_id();
     const int wave = threadIdx.x >> 6;
@@ -330,21 +352,31 @@ __global__ __launch_bounds__(kScanWaves * 64, 1) void k_scan(ScanArgs a)
         const int nrows = row_end - row0;
         const int nblk = (nrows + kBlockRows - 1) / kBlockRows;
         const char* src = (const char*)a.rows + (size_t)row0 * S::rowb;
-        auto block_chunks = [&](int blk) { return min(nrows - blk * kBlockRows, kBlockRows) * (S::rowb / 16); };
-        auto block_src = [&](int blk) { return src + (size_t)blk * kBlockRows * S::rowb; };
+        // Loads for a block past the end of the segment re-read its last block: every path then
+        // issues the same number of loads per iteration, which is what lets the staging code
+        // wait for "all but the newest PF-1 blocks" with a fixed counter value instead of
+        // draining the whole prefetch ring.
+        auto block_chunks = [&](int blk) __attribute__((always_inline)) { return min(nrows - min(blk, nblk - 1) * kBlockRows, kBlockRows) * (S::rowb / 16); };
+        auto block_src = [&](int blk) __attribute__((always_inline)) { return src + (size_t)min(blk, nblk - 1) * kBlockRows * S::rowb; };
 
         // ---- first row blocks on their way before anything else
-        uint4 ring[PF][S::nld];
-#pragma unroll
-        for (int p = 0; p < PF; p++)
-            if (p < nblk) load_block<S>(block_src(p), block_chunks(p), ring[p]);
+        // (the squared row norms of a block travel with it: a separate load inside the block
+        // loop would make every block wait for all the prefetches issued before it)
+        u32x4 ring[PF][S::nld];
+        float nring[PF];
+        auto load_norm = [&](int blk) __attribute__((always_inline)) {
+            const int r = min(row0 + min(blk, nblk - 1) * kBlockRows + (int)(threadIdx.x & (kBlockRows - 1)), row_end - 1);
+            return a.row_norm[r];
+        };
+        load_block<S>(block_src(0), block_chunks(0), ring[0]);
+        nring[0] = load_norm(0);
 
         // ---- query operands of this lane's columns into registers (B fragments)
         const int ecol0 = qt * S::cw + wave * WC + jcol;     // entry inside the bucket, set 0
         bool col_ok[NCS];
         int q[NCS];
         float thr[NCS];
-        uint4 bfrag[NCS][KSTEPS];
+        u32x4 bfrag[NCS][KSTEPS];
 #pragma unroll
         for (int s = 0; s < NCS; s++) {
             const int ecol = ecol0 + s * NC;
@@ -358,7 +390,7 @@ __global__ __launch_bounds__(kScanWaves * 64, 1) void k_scan(ScanArgs a)
             const char* qp = (const char*)a.qop + qrow * (size_t)(S::d * 2) + g * 16;
 #pragma unroll
             for (int t = 0; t < KSTEPS; t++)
-                bfrag[s][t] = col_ok[s] ? *(const uint4*)(qp + t * 64) : uint4{0, 0, 0, 0};
+                bfrag[s][t] = col_ok[s] ? *(const u32x4*)(qp + t * 64) : u32x4{0, 0, 0, 0};
             thr[s] = col_ok[s] ? dec_key(a.thr[q[s]]) : __builtin_inff();
         }
         if (lane < WC) mycnt[lane] = 0;
@@ -368,26 +400,33 @@ __global__ __launch_bounds__(kScanWaves * 64, 1) void k_scan(ScanArgs a)
 #pragma unroll
         for (int s = 0; s < NCS; s++) nact += __builtin_amdgcn_ballot_w64(col_ok[s]) != 0 ? 1 : 0;
 
+        // Everything loaded so far (query operands, thresholds, first row block) is waited for
+        // here, once, and only then are the next PF blocks requested, oldest ring slot first.
+        // The loop is thus entered with exactly the loads in flight, in exactly the order, that
+        // every later iteration sees; the compiler's wait-count analysis (which merges the two
+        // ways into the loop) can then let the staging of a block wait for that block alone,
+        // with the PF-1 younger blocks still in flight, instead of draining the ring.
+        __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0) only
         stage_block<DT, S>(stage, ring[0]);
-        if (PF < nblk) load_block<S>(block_src(PF), block_chunks(PF), ring[0]);
+        nstage[threadIdx.x & (kBlockRows - 1)] = nring[0];      // (same value from 16 threads each)
+        static_for<PF>([&](auto pc) __attribute__((always_inline)) {
+            constexpr int slot = (decltype(pc)::value + 1) % PF;
+            load_block<S>(block_src(decltype(pc)::value + 1), block_chunks(decltype(pc)::value + 1), ring[slot]);
+            nring[slot] = load_norm(decltype(pc)::value + 1);
+        });
         __syncthreads();
         HR_TOC(t_setup, tk);
 
         for (int b0 = 0; b0 < nblk; b0 += PF) {
-#pragma unroll
-            for (int p = 0; p < PF; p++) {
+            static_for<PF>([&](auto pc) __attribute__((always_inline)) {
+                constexpr int p = decltype(pc)::value;
                 const int blk = b0 + p;
-                if (blk >= nblk) continue;
+                if (blk >= nblk) return;
                 char* cur = stage + (blk & 1) * S::buf_bytes;
                 const int rbase = row0 + blk * kBlockRows + g * 4;   // first of this lane's 4 rows
 
                 if (nact > 0) {
-                    float nrm[4] = {0.f, 0.f, 0.f, 0.f};
-                    if (a.l2) {
-#pragma unroll
-                        for (int r = 0; r < 4; r++)
-                            if (rbase + r < row_end) nrm[r] = a.row_norm[rbase + r];
-                    }
+                    const floatx4 nrm = *(const floatx4*)(nstage + (blk & 1) * kBlockRows + g * 4);
                     floatx4 acc[NCS][2];
                     const char* ap = cur + (lane & 15) * S::rowp + g * 16;
                     if (NCS == 2 && nact == 2) mfma_block<DT, KSTEPS, NCS, NCS, S>(ap, bfrag, acc);
@@ -396,7 +435,7 @@ __global__ __launch_bounds__(kScanWaves * 64, 1) void k_scan(ScanArgs a)
 
 #pragma unroll
                     for (int s = 0; s < NCS; s++) {
-                        if (s >= nact) continue;
+                        if (s >= nact) break;
                         // ---- keys of this lane's 4 (row, column) pairs of set s
                         float key[4];
                         bool pass[4];
@@ -453,16 +492,17 @@ __global__ __launch_bounds__(kScanWaves * 64, 1) void k_scan(ScanArgs a)
                 }
 
                 // ---- next block: registers -> LDS, and refill the ring slot it leaves
-                if (blk + 1 < nblk) {
-                    const int pn = (p + 1) % PF;
+                {
+                    constexpr int pn = (p + 1) % PF;
                     stage_block<DT, S>(stage + ((blk + 1) & 1) * S::buf_bytes, ring[pn]);
-                    if (blk + 1 + PF < nblk)
-                        load_block<S>(block_src(blk + 1 + PF), block_chunks(blk + 1 + PF), ring[pn]);
+                    nstage[((blk + 1) & 1) * kBlockRows + (threadIdx.x & (kBlockRows - 1))] = nring[pn];
+                    load_block<S>(block_src(blk + 1 + PF), block_chunks(blk + 1 + PF), ring[pn]);
+                    nring[pn] = load_norm(blk + 1 + PF);
                 }
                 HR_TOC(t_stage, tk);
                 __syncthreads();
                 HR_TOC(t_bar, tk);
-            }
+            });
         }
 
         // ---- hand what is left to the item's slots: columns still over k are cut down first
@@ -573,12 +613,12 @@ __global__ __launch_bounds__(256) void k_seed(SeedArgs a)
     const int g = lane >> 4;
     const int part = (NC == 8) ? ((lane >> 3) & 1) : 0;
     const bool bcol = (lane & (NC - 1)) == 0;          // MFMA column 0 (and its lo twin)
-    uint4 bfrag[KSTEPS];
+    u32x4 bfrag[KSTEPS];
     {
         const size_t qrow = (NC == 8) ? ((size_t)q * 2 + part) : (size_t)q;
         const char* qp = (const char*)a.qop + qrow * (size_t)(d * 2) + g * 16;
 #pragma unroll
-        for (int t = 0; t < KSTEPS; t++) bfrag[t] = bcol ? *(const uint4*)(qp + t * 64) : uint4{0, 0, 0, 0};
+        for (int t = 0; t < KSTEPS; t++) bfrag[t] = bcol ? *(const u32x4*)(qp + t * 64) : u32x4{0, 0, 0, 0};
     }
     uint32_t* keys = s_keys[wave];
     const int nblk = (nrows + 15) / 16;
@@ -591,12 +631,11 @@ __global__ __launch_bounds__(256) void k_seed(SeedArgs a)
         for (int t = 0; t < KSTEPS; t++) {
             if constexpr (DT == HR_F32) {
                 float x[8];
-                uint4 v0 = rv ? *(const uint4*)(rp + t * 128 + g * 32) : uint4{0, 0, 0, 0};
-                uint4 v1 = rv ? *(const uint4*)(rp + t * 128 + g * 32 + 16) : uint4{0, 0, 0, 0};
-                x[0] = __builtin_bit_cast(float, v0.x); x[1] = __builtin_bit_cast(float, v0.y);
-                x[2] = __builtin_bit_cast(float, v0.z); x[3] = __builtin_bit_cast(float, v0.w);
-                x[4] = __builtin_bit_cast(float, v1.x); x[5] = __builtin_bit_cast(float, v1.y);
-                x[6] = __builtin_bit_cast(float, v1.z); x[7] = __builtin_bit_cast(float, v1.w);
+                u32x4 v0 = rv ? *(const u32x4*)(rp + t * 128 + g * 32) : u32x4{0, 0, 0, 0};
+                u32x4 v1 = rv ? *(const u32x4*)(rp + t * 128 + g * 32 + 16) : u32x4{0, 0, 0, 0};
+                const floatx4 f0 = __builtin_bit_cast(floatx4, v0), f1 = __builtin_bit_cast(floatx4, v1);
+#pragma unroll
+                for (int i = 0; i < 4; i++) { x[i] = f0[i]; x[4 + i] = f1[i]; }
                 half8 hi, lo;
 #pragma unroll
                 for (int i = 0; i < 8; i++) {
@@ -608,7 +647,7 @@ __global__ __launch_bounds__(256) void k_seed(SeedArgs a)
                 acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(hi, b, acc0, 0, 0, 0);
                 acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(lo, b, acc1, 0, 0, 0);
             } else {
-                uint4 v = rv ? *(const uint4*)(rp + t * 64 + g * 16) : uint4{0, 0, 0, 0};
+                u32x4 v = rv ? *(const u32x4*)(rp + t * 64 + g * 16) : u32x4{0, 0, 0, 0};
                 if constexpr (DT == HR_F16) {
                     half8 b = __builtin_bit_cast(half8, bfrag[t]);
                     if (t & 1) acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, v), b, acc1, 0, 0, 0);
