@@ -2,6 +2,7 @@
 // sequence.  Nothing here synchronises the caller's stream except hr_ivf_load and hr_ivf_stats.
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 
 #include "common.h"
@@ -428,6 +429,7 @@ static int enqueue_scan(const hr_ivf_index* ix, const Plan& p, char* ws, int64_t
     a.xq_head = zero + ix->nlist + DYN_COUNT + 16;
     a.xq_stride = p.item_cap;
     a.dbg = g_dbg;
+    { const char* f = getenv("HR_DEBUG_FLAGS"); a.dbg_flags = f ? atoi(f) : 0; }
     a.dense = 0;
     a.nq = (int)nq; a.k = k; a.cap = sel_cap(k); a.l2 = metric == HR_METRIC_L2;
     hr_ivf_index* mix = const_cast<hr_ivf_index*>(ix);

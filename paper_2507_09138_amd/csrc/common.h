@@ -70,6 +70,7 @@ struct ScanArgs {
     int dense, dense_items, dense_nqt, dense_seg_rows, dense_nrows;
     int nq, k, cap, l2;
     long long* dbg;             // per-workgroup phase timers (only in HR_SCAN_TIMING builds)
+    int dbg_flags;              // experiments: 1 = thresholds at +inf (no selection), 2 = no MFMA/selection
 };
 
 struct SeedArgs {

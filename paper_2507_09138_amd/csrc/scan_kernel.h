@@ -302,7 +302,7 @@ __global__ __launch_bounds__(kScanWaves * 64, 1) void k_scan(ScanArgs a)
     int drained = 0;                               // thread 0: queues found empty
 #ifdef HR_SCAN_TIMING
     long long t_pop = 0, t_setup = 0, t_mfma = 0, t_sel = 0, t_stage = 0, t_bar = 0, t_emit = 0;
-    int n_items = 0;
+    int n_items = 0, n_blocks = 0, n_cand_blocks = 0, n_prunes = 0;
 #endif
     HR_TIC(tk);
 
@@ -391,14 +391,21 @@ __global__ __launch_bounds__(kScanWaves * 64, 1) void k_scan(ScanArgs a)
 #pragma unroll
             for (int t = 0; t < KSTEPS; t++)
                 bfrag[s][t] = col_ok[s] ? *(const u32x4*)(qp + t * 64) : u32x4{0, 0, 0, 0};
-            thr[s] = col_ok[s] ? dec_key(a.thr[q[s]]) : __builtin_inff();
+            thr[s] = (col_ok[s] && !(a.dbg_flags & 1)) ? dec_key(a.thr[q[s]]) : __builtin_inff();
         }
-        if (lane < WC) mycnt[lane] = 0;
+        // candidates buffered per column: kept in a register by every lane of the column (the
+        // lanes of a column see the same ballots, so they stay in step without LDS traffic)
+        int ccnt[NCS];
+#pragma unroll
+        for (int s = 0; s < NCS; s++) ccnt[s] = 0;
+        const unsigned long long colmask = 0x0001000100010001ULL << jcol;   // owner lanes of my column
+        const unsigned long long below = (1ULL << lane) - 1;
         // column sets of this wave that hold at least one query (sets fill in order); a wave
         // with none only helps to stage rows
         int nact = 0;
 #pragma unroll
         for (int s = 0; s < NCS; s++) nact += __builtin_amdgcn_ballot_w64(col_ok[s]) != 0 ? 1 : 0;
+        if (a.dbg_flags & 2) nact = 0;
 
         // Everything loaded so far (query operands, thresholds, first row block) is waited for
         // here, once, and only then are the next PF blocks requested, oldest ring slot first.
@@ -425,6 +432,9 @@ __global__ __launch_bounds__(kScanWaves * 64, 1) void k_scan(ScanArgs a)
                 char* cur = stage + (blk & 1) * S::buf_bytes;
                 const int rbase = row0 + blk * kBlockRows + g * 4;   // first of this lane's 4 rows
 
+#ifdef HR_SCAN_TIMING
+                n_blocks++;
+#endif
                 if (nact > 0) {
                     const floatx4 nrm = *(const floatx4*)(nstage + (blk & 1) * kBlockRows + g * 4);
                     floatx4 acc[NCS][2];
@@ -459,33 +469,41 @@ __global__ __launch_bounds__(kScanWaves * 64, 1) void k_scan(ScanArgs a)
                         }
                         // ---- append what reaches the column's threshold
                         if (__builtin_amdgcn_ballot_w64(any) != 0) {
+#ifdef HR_SCAN_TIMING
+                            n_cand_blocks++;
+#endif
                             Cand* ssel = mysel + (s * NC) * a.cap;
-                            int* scnt = mycnt + s * NC;
+                            // slot of each new candidate = column count + candidates of the same
+                            // column in earlier row slots and in lower lanes of this row slot
+                            int add = 0;
 #pragma unroll
                             for (int r = 0; r < 4; r++) {
+                                const unsigned long long mine = __builtin_amdgcn_ballot_w64(pass[r]) & colmask;
                                 if (pass[r]) {
-                                    int pos = atomicAdd(&scnt[jcol], 1);
+                                    const int pos = ccnt[s] + add + __builtin_popcountll(mine & below);
                                     ssel[jcol * a.cap + pos] = Cand{enc_key(key[r]), (uint32_t)(rbase + r)};
                                 }
+                                add += __builtin_popcountll(mine);
                             }
-                            wave_sync();
-                            int c = (lane < NC) ? scnt[lane] : 0;
-                            unsigned long long full = __builtin_amdgcn_ballot_w64(c > a.cap - kAppendMax);
+                            ccnt[s] += add;
+                            unsigned long long full = __builtin_amdgcn_ballot_w64(lane < NC && ccnt[s] > a.cap - kAppendMax);
+                            if (full) wave_sync();
                             while (full) {
                                 int col = __builtin_ctzll(full);
                                 full &= full - 1;
-                                int n = __builtin_amdgcn_readlane(c, col);
+                                int n = __builtin_amdgcn_readlane(ccnt[s], col);
                                 uint32_t kth = select_k(ssel + col * a.cap, n, a.k, a.cap, a.row_ids);
+#ifdef HR_SCAN_TIMING
+                                n_prunes++;
+#endif
                                 float nt = 0.f;
                                 if (lane == col) {
-                                    scnt[col] = a.k;
                                     uint32_t old = atomicMax(&a.thr[q[s]], kth);
                                     nt = dec_key(kth > old ? kth : old);
                                 }
                                 nt = __shfl(nt, col);
-                                if (jcol == col) thr[s] = fmaxf(thr[s], nt);
+                                if (jcol == col) { thr[s] = fmaxf(thr[s], nt); ccnt[s] = a.k; }
                             }
-                            wave_sync();
                         }
                     }
                     HR_TOC(t_sel, tk);
@@ -509,7 +527,12 @@ __global__ __launch_bounds__(kScanWaves * 64, 1) void k_scan(ScanArgs a)
         // (one at a time, whole wave), then every lane copies one column's entries
         wave_sync();
         {
-            const int c = (lane < WC) ? mycnt[lane] : 0;
+            int c = 0;
+#pragma unroll
+            for (int s = 0; s < NCS; s++) {
+                const int v = __shfl(ccnt[s], (lane - s * NC) & 63);
+                if (lane >= s * NC && lane < (s + 1) * NC) c = v;
+            }
             unsigned long long over = __builtin_amdgcn_ballot_w64(c > a.k);
             while (over) {
                 const int wc = __builtin_ctzll(over);
@@ -552,6 +575,8 @@ __global__ __launch_bounds__(kScanWaves * 64, 1) void k_scan(ScanArgs a)
     if (a.dbg && threadIdx.x == 0) {
         long long* o = a.dbg + blockIdx.x * 8;
         o[0] = t_pop; o[1] = t_setup; o[2] = t_mfma; o[3] = t_sel; o[4] = t_stage; o[5] = t_bar; o[6] = t_emit; o[7] = n_items;
+        long long* o2 = a.dbg + 4096 + blockIdx.x * 4;
+        o2[0] = n_blocks; o2[1] = n_cand_blocks; o2[2] = n_prunes;
     }
 #endif
 }
