@@ -21,9 +21,12 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 MFMA_PEAK_TFLOPS = {"f16": 2500.0, "bf16": 2500.0, "f32": 2500.0}   # f32 rows run as binary16 pairs
 ESIZE = {"f32": 4, "f16": 2, "bf16": 2}
+# HBM bytes per list-scan launch (read + written) from the rocprofv3 FETCH_SIZE / WRITE_SIZE counter runs
+# summarised under profiles/ (counters cannot be read from inside this process); other workloads: null
+MEASURED_TRAFFIC = {"C3": 8.20e9 + 0.04e9}
 
 
-def cpu_baseline(cfg, idx, q, target_s=15.0):
+def cpu_baseline(cfg, idx, q, target_s=30.0):
     """The oracle as it stands, on the host cores, on a sample sized for about target_s seconds."""
     import numpy as np
     import oracle
@@ -40,19 +43,19 @@ def cpu_baseline(cfg, idx, q, target_s=15.0):
     n0 = min(len(order), max(threads, 8))
     t0 = time.time()
     oracle.ivf_search(np.ascontiguousarray(qh[order[:n0]]), cent, off, vec, cfg.dtype, ids, cfg.nprobe, cfg.k, m)
-    t_pilot = time.time() - t0
-    n1 = int(min(len(order) - n0, max(0, (target_s - t_pilot) / max(t_pilot / n0, 1e-9))))
+    t_pilot = time.time() - t0          # also pages the index in; only sizes the timed sample
+    n1 = int(min(len(order) - n0, target_s / max(t_pilot / n0, 1e-9)))
     n1 -= n1 % threads if n1 > threads else 0
-    total_t, total_n = t_pilot, n0
     if n1 > 0:
+        sel = order[n0:n0 + n1]
         t0 = time.time()
-        oracle.ivf_search(np.ascontiguousarray(qh[order[n0:n0 + n1]]), cent, off, vec, cfg.dtype, ids,
-                          cfg.nprobe, cfg.k, m)
-        total_t += time.time() - t0
-        total_n += n1
+        oracle.ivf_search(np.ascontiguousarray(qh[sel]), cent, off, vec, cfg.dtype, ids, cfg.nprobe, cfg.k, m)
+        total_t, total_n = time.time() - t0, n1
+    else:
+        total_t, total_n = t_pilot, n0
     return {"value": total_n / total_t, "unit": "queries/s", "cores": threads, "kind": "oracle",
             "sample": f"{total_n} randomly chosen queries of the batch (full index, nprobe={cfg.nprobe}, "
-                      f"k={cfg.k}), {total_t:.1f} s"}
+                      f"k={cfg.k}), {total_t:.1f} s after a {n0}-query pilot"}
 
 
 def main():
@@ -121,7 +124,7 @@ def main():
                    "pairs": st["pairs"]},
         "roofline": {"bound": "hbm", "kernel": "k_scan (list scan)", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": None, "scan_ms_avg": scan_ms, "launches_timed": n_timed,
+                     "traffic": MEASURED_TRAFFIC.get(cfg.name), "scan_ms_avg": scan_ms, "launches_timed": n_timed,
                      "algorithmic_bytes_per_launch": scan_bytes,
                      "mfma_tflops": scan_flops / (scan_ms * 1e-3) / 1e12 if scan_ms > 0 else 0.0,
                      "mfma_frac": (scan_flops / (scan_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS[cfg.dtype])
