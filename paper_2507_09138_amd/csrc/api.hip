@@ -8,9 +8,9 @@
 #include "common.h"
 
 namespace hr {
-hipError_t launch_scan_f32(int d, const ScanArgs& a, int ncs, int grid, size_t lds, hipStream_t s);
-hipError_t launch_scan_f16(int d, const ScanArgs& a, int ncs, int grid, size_t lds, hipStream_t s);
-hipError_t launch_scan_bf16(int d, const ScanArgs& a, int ncs, int grid, size_t lds, hipStream_t s);
+hipError_t launch_scan_f32(int d, const ScanArgs& a, int shape, int grid, size_t lds, hipStream_t s);
+hipError_t launch_scan_f16(int d, const ScanArgs& a, int shape, int grid, size_t lds, hipStream_t s);
+hipError_t launch_scan_bf16(int d, const ScanArgs& a, int shape, int grid, size_t lds, hipStream_t s);
 
 hipError_t launch_seed_f32(int d, const SeedArgs& a, hipStream_t s);
 hipError_t launch_seed_f16(int d, const SeedArgs& a, hipStream_t s);
@@ -26,37 +26,55 @@ hipError_t launch_seed(int dtype, int d, const SeedArgs& a, hipStream_t s)
     }
 }
 
-hipError_t launch_scan(int dtype, int d, const ScanArgs& a, int ncs, int grid, size_t lds, hipStream_t s)
+hipError_t launch_scan(int dtype, int d, const ScanArgs& a, int shape, int grid, size_t lds, hipStream_t s)
 {
     switch (dtype) {
-    case HR_F32: return launch_scan_f32(d, a, ncs, grid, lds, s);
-    case HR_F16: return launch_scan_f16(d, a, ncs, grid, lds, s);
-    case HR_BF16: return launch_scan_bf16(d, a, ncs, grid, lds, s);
+    case HR_F32: return launch_scan_f32(d, a, shape, grid, lds, s);
+    case HR_F16: return launch_scan_f16(d, a, shape, grid, lds, s);
+    case HR_BF16: return launch_scan_bf16(d, a, shape, grid, lds, s);
     default: return hipErrorInvalidValue;
     }
 }
 
-// LDS bytes of one workgroup with ncs column sets per wave (must match the carve-up at the top
-// of k_scan)
-size_t scan_lds_bytes(int dtype, int d, int k, int ncs)
+// LDS bytes of one workgroup of the given shape with nbuf staging buffers (must match the
+// carve-up at the top of k_scan and ScanShape::buf_bytes)
+size_t scan_lds_bytes(int dtype, int d, int k, int shape, int nbuf)
 {
-    const int planes = dtype == HR_F32 ? 2 : 1;
-    const size_t buf = (size_t)kBlockRows * (d * 2 + kRowPad) * planes;
+    const int nw = shape_waves(shape);
+    size_t buf;
+    if (dtype == HR_F32) {
+        buf = (size_t)kBlockRows * (d * 2 + kRowPad) * 2;
+    } else {
+        const int chunks = kBlockRows * d * 2 / 16, threads = nw * 64;
+        buf = (size_t)((chunks + threads - 1) / threads) * threads * 16;
+    }
     const size_t cap = sel_cap(k);
-    const size_t cw = (size_t)cols_per_wave(dtype) * ncs * 4;
-    return 2 * buf + cw * cap * sizeof(Cand) + cw * sizeof(int) + 2 * kBlockRows * sizeof(float) + 16;
+    const size_t cw = (size_t)cols_per_set(dtype) * shape_sets(shape);
+    return nbuf * buf + cw * cap * sizeof(Cand) + (size_t)nbuf * nw * 64 * sizeof(float) + 16;
 }
 }  // namespace hr
 
 static constexpr int kLdsLimit = 160 * 1024;      // LDS per workgroup on gfx950
 
-// column sets per wave for a scan: 2 (twice the query columns per pass over the rows) when the
-// selection buffers still fit in LDS, else 1; 0 = does not fit at all
-static int pick_ncs(int dtype, int d, int k)
+// Workgroup shape and number of staging buffers for a scan.  Shape: 8 waves (two per SIMD)
+// when the selection buffers of that many query columns still fit in LDS, else 4 waves with
+// half the columns.  Buffers: float32 rows are staged through registers into 2; 16-bit rows
+// go straight to LDS into as many as fit, up to 5 (4 blocks on their way).  shape -1 = no fit.
+struct ScanPick { int shape, nbuf; };
+static ScanPick pick_shape(int dtype, int d, int k)
 {
-    if (hr::scan_lds_bytes(dtype, d, k, 2) <= (size_t)kLdsLimit) return 2;
-    if (hr::scan_lds_bytes(dtype, d, k, 1) <= (size_t)kLdsLimit) return 1;
-    return 0;
+    static const char* force = getenv("HR_SCAN_SHAPE");      // development switch: "<shape><nbuf>", e.g. 23
+    const int shapes[2] = {hr::SCAN_WIDE, hr::SCAN_NARROW};
+    if (force && dtype != HR_F32) {
+        const int shape = force[0] - '0', nbuf = force[1] - '0';
+        if (hr::scan_lds_bytes(dtype, d, k, shape, nbuf) <= (size_t)kLdsLimit) return {shape, nbuf};
+    }
+    for (int shape : shapes) {
+        const int most = dtype == HR_F32 ? 2 : 5;
+        for (int nbuf = most; nbuf >= 2; nbuf--)
+            if (hr::scan_lds_bytes(dtype, d, k, shape, nbuf) <= (size_t)kLdsLimit) return {shape, nbuf};
+    }
+    return {-1, 0};
 }
 
 using namespace hr;
@@ -107,9 +125,9 @@ static size_t align_up(size_t v) { return (v + HR_WORKSPACE_ALIGN - 1) & ~(size_
 // Layout of the caller's workspace for one batch shape.  Offsets in bytes.
 struct Plan {
     // coarse step: centroid table scanned with all queries as one dense bucket
-    int nw_c /* column sets per wave */, cw_c, nqt_c, seg_c, nseg_c, items_c;
+    int shape_c /* workgroup shape, -1 = no fit */, nbuf_c, cw_c, nqt_c, seg_c, nseg_c, items_c;
     // list scan
-    int nw_s, cw_s, item_cap;
+    int shape_s, nbuf_s, cw_s, item_cap;
     size_t o_zero, n_zero;          // ints cleared per call: list_w[nlist], dyn[DYN_COUNT], counters[8]
     size_t o_thr;                   // 2*nq ints set to "-inf"
     size_t o_qop_c, o_qnorm_c, o_qop_s, o_qnorm_s;
@@ -124,9 +142,10 @@ static Plan make_plan(const hr_ivf_index* ix, int64_t nq, int nprobe, int k)
     Plan p{};
     const int64_t nlist = ix->nlist;
     const int kk = k > nprobe ? k : nprobe;      // slots are shared by the two scans
-    p.nw_c = pick_ncs(HR_F32, ix->d, nprobe);
-    p.nw_s = pick_ncs(ix->dtype, ix->d, k);
-    p.cw_c = cols_per_wave(HR_F32) * 4 * (p.nw_c ? p.nw_c : 1);
+    const ScanPick pc = pick_shape(HR_F32, ix->d, nprobe), ps = pick_shape(ix->dtype, ix->d, k);
+    p.shape_c = pc.shape; p.nbuf_c = pc.nbuf;
+    p.shape_s = ps.shape; p.nbuf_s = ps.nbuf;
+    p.cw_c = cols_per_set(HR_F32) * shape_sets(p.shape_c < 0 ? 0 : p.shape_c);
     p.nqt_c = (int)((nq + p.cw_c - 1) / p.cw_c);
     int64_t seg = (nlist * (int64_t)p.nqt_c + 2047) / 2048;
     seg = (seg + 15) & ~15LL;
@@ -135,7 +154,7 @@ static Plan make_plan(const hr_ivf_index* ix, int64_t nq, int nprobe, int k)
     p.seg_c = (int)seg;
     p.nseg_c = (int)((nlist + seg - 1) / seg);
     p.items_c = p.nseg_c * p.nqt_c;
-    p.cw_s = cols_per_wave(ix->dtype) * 4 * (p.nw_s ? p.nw_s : 1);
+    p.cw_s = cols_per_set(ix->dtype) * shape_sets(p.shape_s < 0 ? 0 : p.shape_s);
     const int64_t pairs = nq * nprobe;
     p.item_cap = (int)(kItemTarget + pairs / p.cw_s + (pairs < nlist ? pairs : nlist) + 8);
 
@@ -323,11 +342,13 @@ size_t hr_ivf_workspace_bytes(const hr_ivf_index* ix, int64_t nq, int32_t nprobe
 static long long* g_dbg = nullptr;   // TEMP
 extern "C" void hr_debug_scan_timing(void* p) { g_dbg = (long long*)p; }
 
-static int scan_grid(const hr_ivf_index* ix, size_t lds, int nw)
+// persistent workgroups: one per CU (8-wave shape), or two where LDS lets two 4-wave ones share a CU
+static int scan_grid(const hr_ivf_index* ix, size_t lds, int shape)
 {
     int occ = (int)((size_t)kLdsLimit / lds);
     if (occ < 1) occ = 1;
-    if (occ > (nw == 8 ? 1 : 2)) occ = nw == 8 ? 1 : 2;
+    const int most = shape == SCAN_WIDE ? 1 : 2;
+    if (occ > most) occ = most;
     return ix->num_cus * occ;
 }
 
@@ -342,9 +363,9 @@ static int enqueue_clear(const Plan& p, char* ws, int64_t nq, hipStream_t s)
 static int enqueue_coarse(const hr_ivf_index* ix, const Plan& p, char* ws, int64_t nq, int nprobe,
                           int metric, int32_t* out_probe, float* out_scores, hipStream_t s)
 {
-    if (!p.nw_c)
+    if (p.shape_c < 0)
         return fail(HR_ERR_UNSUPPORTED, "coarse step does not fit in LDS (d=%d, nprobe=%d)", ix->d, nprobe);
-    const size_t lds = scan_lds_bytes(HR_F32, ix->d, nprobe, p.nw_c);
+    const size_t lds = scan_lds_bytes(HR_F32, ix->d, nprobe, p.shape_c, p.nbuf_c);
     int* zero = (int*)(ws + p.o_zero);
     ScanArgs a{};
     a.rows = ix->centroids;
@@ -361,9 +382,10 @@ static int enqueue_coarse(const hr_ivf_index* ix, const Plan& p, char* ws, int64
     a.dense_seg_rows = p.seg_c;
     a.dense_nrows = (int)ix->nlist;
     a.nq = (int)nq; a.k = nprobe; a.cap = sel_cap(nprobe); a.l2 = metric == HR_METRIC_L2;
-    int grid = scan_grid(ix, lds, p.nw_c);
+    a.nbuf = p.nbuf_c;
+    int grid = scan_grid(ix, lds, p.shape_c);
     if (grid > p.items_c) grid = p.items_c;
-    HR_HIP(launch_scan(HR_F32, ix->d, a, p.nw_c, grid, lds, s));
+    HR_HIP(launch_scan(HR_F32, ix->d, a, p.shape_c, grid, lds, s));
     MergeArgs m{};
     m.slot_cnt = a.slot_cnt; m.slot_ent = a.slot_ent;
     m.row_ids = nullptr;
@@ -380,9 +402,9 @@ static int enqueue_coarse(const hr_ivf_index* ix, const Plan& p, char* ws, int64
 static int enqueue_scan(const hr_ivf_index* ix, const Plan& p, char* ws, int64_t nq, const int32_t* probe,
                         int nprobe, int k, int metric, int64_t* out_ids, float* out_scores, hipStream_t s)
 {
-    if (!p.nw_s)
+    if (p.shape_s < 0)
         return fail(HR_ERR_UNSUPPORTED, "list scan does not fit in LDS (d=%d, k=%d)", ix->d, k);
-    const size_t lds = scan_lds_bytes(ix->dtype, ix->d, k, p.nw_s);
+    const size_t lds = scan_lds_bytes(ix->dtype, ix->d, k, p.shape_s, p.nbuf_s);
     int* zero = (int*)(ws + p.o_zero);
     BucketArgs b{};
     b.probe = probe; b.nq = (int)nq; b.nprobe = nprobe; b.nlist = (int)ix->nlist; b.cw = p.cw_s;
@@ -432,10 +454,11 @@ static int enqueue_scan(const hr_ivf_index* ix, const Plan& p, char* ws, int64_t
     { const char* f = getenv("HR_DEBUG_FLAGS"); a.dbg_flags = f ? atoi(f) : 0; }
     a.dense = 0;
     a.nq = (int)nq; a.k = k; a.cap = sel_cap(k); a.l2 = metric == HR_METRIC_L2;
+    a.nbuf = p.nbuf_s;
     hr_ivf_index* mix = const_cast<hr_ivf_index*>(ix);
     const bool timed = mix->prof_ev && mix->prof_n < mix->prof_cap;
     if (timed) HR_HIP(hipEventRecord(mix->prof_ev[2 * mix->prof_n], s));
-    HR_HIP(launch_scan(ix->dtype, ix->d, a, p.nw_s, scan_grid(ix, lds, p.nw_s), lds, s));
+    HR_HIP(launch_scan(ix->dtype, ix->d, a, p.shape_s, scan_grid(ix, lds, p.shape_s), lds, s));
     if (timed) {
         HR_HIP(hipEventRecord(mix->prof_ev[2 * mix->prof_n + 1], s));
         mix->prof_n++;

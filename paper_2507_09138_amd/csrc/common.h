@@ -15,9 +15,42 @@ constexpr int kAppendMax = 16;             // most candidates one column can gai
 constexpr int kMinSegRows = 256;           // smallest rows-per-work-item
 constexpr int kItemTarget = 8192;         // aimed number of scan work items per batch
 
-// columns (queries) per wave: 16 when the query operand is one binary16 row, 8 when it is a
-// (hi, lo) pair occupying two MFMA columns.  A wave owns ncs such sets, a work item 4 waves' worth.
-__host__ __device__ constexpr int cols_per_wave(int dtype) { return dtype == HR_F16 ? 16 : 8; }
+// columns (queries) per 16-column MFMA set: 16 when the query operand is one binary16 row, 8
+// when it is a (hi, lo) pair occupying two MFMA columns.
+__host__ __device__ constexpr int cols_per_set(int dtype) { return dtype == HR_F16 ? 16 : 8; }
+
+// Workgroup shapes of the scan kernel: waves x column sets per wave.  A work item covers
+// shape_sets(shape) * cols_per_set(dtype) queries of a bucket.
+enum { SCAN_NARROW = 0 /* 4 waves x 1 set */, SCAN_WIDE4 = 1 /* 4 waves x 2 sets */, SCAN_WIDE = 2 /* 8 waves x 1 set */ };
+__host__ __device__ constexpr int shape_waves(int shape) { return shape == SCAN_WIDE ? 8 : 4; }
+__host__ __device__ constexpr int shape_ncs(int shape) { return shape == SCAN_WIDE4 ? 2 : 1; }
+__host__ __device__ constexpr int shape_sets(int shape) { return shape_waves(shape) * shape_ncs(shape); }
+
+// k-steps (of 32 elements) whose row fragments a wave fetches from LDS together
+__host__ __device__ constexpr int scan_group(int dtype, int ksteps, int nw)
+{
+    #ifdef HR_TRY_G
+    return ksteps < 8 ? (ksteps < 4 ? ksteps : 4) : (nw == 8 ? HR_TRY_G : 8);
+#else
+    return ksteps < 8 ? (ksteps < 4 ? ksteps : 4) : (nw == 8 ? 4 : 8);
+#endif
+}
+// row blocks a wave keeps in flight in registers ahead of the one being staged: what the
+// register budget (512 per lane with one wave per SIMD, 256 with two) leaves after the query
+// operand, two groups of row fragments and working registers; at most 4
+__host__ __device__ constexpr int scan_prefetch(int dtype, int ksteps, int ncs, int nw)
+{
+    const int planes = dtype == HR_F32 ? 2 : 1;
+    const int rowb = ksteps * 32 * (dtype == HR_F32 ? 4 : 2);
+    const int chunks = kBlockRows * rowb / 16;
+    const int nld = (chunks + nw * 64 - 1) / (nw * 64);
+    const int left = (nw == 8 ? 256 : 512) - ncs * ksteps * 4 - 2 * planes * scan_group(dtype, ksteps, nw) * 4 - (nw == 8 ? 67 : 64);
+    const int fit = left / (nld * 4 + 1);
+#ifdef HR_TRY_PF
+    if (nw == 8) return HR_TRY_PF;
+#endif
+    return fit < 1 ? 1 : (fit > 4 ? 4 : fit);
+}
 
 // selection buffer capacity per column for a given k: room for k kept entries plus a batch of
 // new ones between two prunes (a prune costs about the same for any fill up to 64 entries per
@@ -69,6 +102,7 @@ struct ScanArgs {
     // dense mode (dense != 0): one list = all rows, bucket = all queries
     int dense, dense_items, dense_nqt, dense_seg_rows, dense_nrows;
     int nq, k, cap, l2;
+    int nbuf;                   // staging buffers in LDS (16-bit storage; float32 always uses 2)
     long long* dbg;             // per-workgroup phase timers (only in HR_SCAN_TIMING builds)
     int dbg_flags;              // experiments: 1 = thresholds at +inf (no selection), 2 = no MFMA/selection
 };
@@ -107,8 +141,8 @@ struct MergeArgs {
 };
 
 // launchers implemented in the .hip files
-hipError_t launch_scan(int dtype, int d, const ScanArgs& a, int ncs, int grid, size_t lds_bytes, hipStream_t s);
-size_t scan_lds_bytes(int dtype, int d, int k, int ncs);
+hipError_t launch_scan(int dtype, int d, const ScanArgs& a, int shape, int grid, size_t lds_bytes, hipStream_t s);
+size_t scan_lds_bytes(int dtype, int d, int k, int shape, int nbuf);
 hipError_t launch_merge(const MergeArgs& a, hipStream_t s);
 hipError_t launch_seed(int dtype, int d, const SeedArgs& a, hipStream_t s);
 hipError_t launch_row_norms(const void* rows, int dtype, int64_t nrows, int d, float* out, hipStream_t s);

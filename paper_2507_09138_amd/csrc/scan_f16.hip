@@ -2,9 +2,9 @@
 #include "scan_kernel.h"
 
 namespace hr {
-hipError_t launch_scan_f16(int d, const ScanArgs& a, int ncs, int grid, size_t lds, hipStream_t s)
+hipError_t launch_scan_f16(int d, const ScanArgs& a, int shape, int grid, size_t lds, hipStream_t s)
 {
-    return launch_scan_dtype<HR_F16>(d, a, ncs, grid, lds, s);
+    return launch_scan_dtype<HR_F16>(d, a, shape, grid, lds, s);
 }
 hipError_t launch_seed_f16(int d, const SeedArgs& a, hipStream_t s) { return launch_seed_dtype<HR_F16>(d, a, s); }
 }  // namespace hr

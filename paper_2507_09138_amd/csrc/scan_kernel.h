@@ -57,6 +57,32 @@ __device__ __forceinline__ int lanes_below(unsigned long long mask)
     return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0));
 }
 
+// ---- global memory -> LDS without passing through registers (global_load_lds).  Every lane
+// gives a byte offset from a wave-uniform base address; the 64 chunks of a wave land next to
+// each other from the wave-uniform LDS address on (lane * 16 or lane * 4 bytes in).
+// Written as inline assembly on purpose: when the compiler knows of such a load it makes every
+// later LDS read wait for all of them, which would undo the prefetching.  The loads complete
+// in order and are counted by vmcnt, so "all but the n youngest have landed" is wait_vmcnt<n>;
+// loads the compiler issues itself in between only make that wait longer, never shorter.
+// (m0 is reserved: the compiler sets it immediately before each of its own uses.)
+__device__ __forceinline__ uint32_t lds_addr(const void* p)
+{
+    return (uint32_t)(size_t)(__attribute__((address_space(3))) const char*)p;
+}
+__device__ __forceinline__ void lds_dma16(const void* base, uint32_t byte_off, uint32_t lds)
+{
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" :: "s"(lds), "v"(byte_off), "s"(base) : "memory");
+}
+__device__ __forceinline__ void lds_dma4(const void* base, uint32_t byte_off, uint32_t lds)
+{
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, %2" :: "s"(lds), "v"(byte_off), "s"(base) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
+}
+
 // Keep the k best of the n (> k) candidates in buf[0..n): afterwards buf[0..k) holds them, in
 // no particular order.  Order: key descending, then label ascending (label = row number when
 // ids == nullptr; labels are only fetched when equal keys straddle the k-th place).
@@ -145,25 +171,49 @@ template <> struct StoreTraits<HR_F32>  { static constexpr int esize = 4, planes
 template <> struct StoreTraits<HR_F16>  { static constexpr int esize = 2, planes = 1, nc = 16; };
 template <> struct StoreTraits<HR_BF16> { static constexpr int esize = 2, planes = 1, nc = 8;  };
 
-constexpr int kScanWaves = 4;                 // one wave per SIMD: each may use all 512 registers
-
+// NW = waves per workgroup (4: one per SIMD, each may use all 512 registers; 8: two per SIMD
+// with 256 registers each, so that one wave's MFMAs run while the other selects or waits).
 // NCS = 16-column MFMA sets per wave (1 or 2).  Every wave owns NCS * nc query columns, so a
-// work item covers 4 * NCS * nc queries of a bucket; all waves share the staged rows.
-template <int DT, int KSTEPS, int NCS>
+// work item covers NW * NCS * nc queries of a bucket; all waves share the staged rows.
+//
+// Two ways of staging a block of 16 rows in LDS:
+//   direct (16-bit storage): global_load_lds moves 16-byte chunks from HBM straight into LDS,
+//     no registers and no LDS store instructions in between.  Such a load writes the 64 chunks
+//     of a wave next to each other, so rows cannot be padded; instead chunk c of row r sits at
+//     position c ^ (r & 15) of its row, which spreads the 16 rows of an MFMA fragment read over
+//     all banks.  Up to four blocks are in flight or waiting in LDS ahead of the one in use.
+//   through registers (float32 storage): rows are split into binary16 hi and lo planes on the
+//     way, from a ring of prefetch registers into two padded buffers.
+constexpr int kAcc = 2;                       // accumulators per column set (independent MFMA chains)
+constexpr int kMaxAhead = 4;                  // most blocks staged ahead of the one in use (direct)
+
+template <int DT, int KSTEPS, int NCS, int NW>
 struct ScanShape {
-    static constexpr int threads = kScanWaves * 64;
+    static constexpr int nw = NW;
+    static constexpr int threads = NW * 64;
     static constexpr int d = KSTEPS * 32;
+    static constexpr int planes = StoreTraits<DT>::planes;
+    static constexpr bool direct = planes == 1;
     static constexpr int rowb = d * StoreTraits<DT>::esize;        // bytes of one stored row
-    static constexpr int rowp = d * 2 + kRowPad;                   // bytes of one staged row (one plane)
+    static constexpr int cpr = rowb / 16;                          // 16-byte chunks per stored row
+    static constexpr int swz = (cpr < 16 ? cpr : 16) - 1;          // row bits xor-ed into the chunk position
+    static constexpr int rowp = direct ? rowb : d * 2 + kRowPad;   // bytes of one staged row (one plane)
     static constexpr int plane_bytes = kBlockRows * rowp;
-    static constexpr int buf_bytes = plane_bytes * StoreTraits<DT>::planes;
-    static constexpr int chunks = kBlockRows * rowb / 16;          // 16-byte chunks per block
+    static constexpr int chunks = kBlockRows * cpr;                // 16-byte chunks per block
     static constexpr int nld = (chunks + threads - 1) / threads;   // chunks per thread per block
-    // row blocks kept in flight in registers ahead of the one being staged
-    static constexpr int pf = 24 / nld < 1 ? 1 : (24 / nld > 4 ? 4 : 24 / nld);
+    // (direct: every wave always issues nld loads, so a buffer is a whole number of them)
+    static constexpr int buf_bytes = direct ? nld * threads * 16 : plane_bytes * planes;
+    // k-steps whose row fragments are fetched from LDS together, ahead of their MFMAs
+    static constexpr int grp = scan_group(DT, KSTEPS, NW);
+    // register path: row blocks kept in flight in registers ahead of the one being staged
+    static constexpr int pf = scan_prefetch(DT, KSTEPS, NCS, NW);
     static constexpr int wcols = StoreTraits<DT>::nc * NCS;        // query columns per wave
-    static constexpr int cw = wcols * kScanWaves;                  // query columns per item
+    static constexpr int cw = wcols * NW;                          // query columns per item
 };
+
+// s_waitcnt immediate that waits for all but n vector-memory operations (n <= 63) and for
+// nothing else
+__host__ __device__ constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }
 
 #ifdef HR_SCAN_TIMING
 #define HR_TIC(var) long long var = clock64()
@@ -214,25 +264,30 @@ __device__ __forceinline__ void stage_block(char* buf, const u32x4 (&regs)[S::nl
     }
 }
 
-// 16 staged rows x NA column sets x d: the MFMA chain of one block.  acc[s][0..1] are the two
-// partial accumulators of set s (for HR_F32: hi-row and lo-row products).  The row fragments
+// 16 staged rows x NA column sets x d: the MFMA chain of one block.  acc[s][*] are the partial
+// accumulators of set s (for HR_F32: [0] hi-row and [1] lo-row products; else summed at the end).  The row fragments
 // are fetched from LDS a group of k-steps ahead of the MFMAs that use them (the scheduling
 // barriers keep the compiler from sinking each read next to its use, which would expose the
-// LDS latency 24 times per block).
+// LDS latency 24 times per block).  The fragment of k-step t is at ap[t & 3] + (t >> 2) * 256:
+// with padded rows the four bases are 64 bytes apart, with the xor-ed chunk positions of the
+// direct staging they are permuted per lane.
 template <int DT, int KSTEPS, int NCS, int NA, typename S>
-__device__ __forceinline__ void mfma_block(const char* ap, const u32x4 (&bfrag)[NCS][KSTEPS], floatx4 (&acc)[NCS][2])
+__device__ __forceinline__ void mfma_block(const char* const (&ap)[4], const u32x4 (&bfrag)[NCS][KSTEPS], floatx4 (&acc)[NCS][kAcc])
 {
-    constexpr int G = KSTEPS < 8 ? KSTEPS : 8;       // k-steps per group
+    constexpr int G = S::grp;                        // k-steps per group
     constexpr int NG = KSTEPS / G;
+    constexpr int AM = (NA == 1 ? kAcc : 2) - 1;     // a lone set spreads over all accumulators
     constexpr int P = StoreTraits<DT>::planes;
     static_assert(KSTEPS % G == 0, "k-steps must split into whole groups");
 #pragma unroll
-    for (int s = 0; s < NA; s++) { acc[s][0] = floatx4{0.f, 0.f, 0.f, 0.f}; acc[s][1] = floatx4{0.f, 0.f, 0.f, 0.f}; }
+    for (int s = 0; s < NA; s++)
+#pragma unroll
+        for (int i = 0; i < kAcc; i++) acc[s][i] = floatx4{0.f, 0.f, 0.f, 0.f};
     u32x4 af[2][P][G];
 #pragma unroll
     for (int i = 0; i < G; i++)
 #pragma unroll
-        for (int pl = 0; pl < P; pl++) af[0][pl][i] = *(const u32x4*)(ap + pl * S::plane_bytes + i * 64);
+        for (int pl = 0; pl < P; pl++) af[0][pl][i] = *(const u32x4*)(ap[i & 3] + pl * S::plane_bytes + (i >> 2) * 256);
 #pragma unroll
     for (int gi = 0; gi < NG; gi++) {
         if (gi + 1 < NG) {
@@ -240,7 +295,7 @@ __device__ __forceinline__ void mfma_block(const char* ap, const u32x4 (&bfrag)[
             for (int i = 0; i < G; i++)
 #pragma unroll
                 for (int pl = 0; pl < P; pl++)
-                    af[(gi + 1) & 1][pl][i] = *(const u32x4*)(ap + pl * S::plane_bytes + ((gi + 1) * G + i) * 64);
+                    af[(gi + 1) & 1][pl][i] = *(const u32x4*)(ap[((gi + 1) * G + i) & 3] + pl * S::plane_bytes + (((gi + 1) * G + i) >> 2) * 256);
         }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -254,10 +309,10 @@ __device__ __forceinline__ void mfma_block(const char* ap, const u32x4 (&bfrag)[
                     acc[s][1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, af[gi & 1][1][i]), b, acc[s][1], 0, 0, 0);
                 } else if constexpr (DT == HR_F16) {
                     half8 b = __builtin_bit_cast(half8, bfrag[s][t]);
-                    acc[s][t & 1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, af[gi & 1][0][i]), b, acc[s][t & 1], 0, 0, 0);
+                    acc[s][t & AM] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, af[gi & 1][0][i]), b, acc[s][t & AM], 0, 0, 0);
                 } else {
                     bf16x8 b = __builtin_bit_cast(bf16x8, bfrag[s][t]);
-                    acc[s][t & 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af[gi & 1][0][i]), b, acc[s][t & 1], 0, 0, 0);
+                    acc[s][t & AM] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af[gi & 1][0][i]), b, acc[s][t & AM], 0, 0, 0);
                 }
             }
         }
@@ -273,33 +328,62 @@ __device__ __forceinline__ uint32_t select_k(Cand* buf, int n, int k, int cap, c
     return wave_select<3>(buf, n, k, ids);
 }
 
-template <int DT, int KSTEPS, int NCS>
-__global__ __launch_bounds__(kScanWaves * 64, 1) void k_scan(ScanArgs a)
+template <int DT, int KSTEPS, int NCS, int NW>
+__global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
 {
-    using S = ScanShape<DT, KSTEPS, NCS>;
+    using S = ScanShape<DT, KSTEPS, NCS, NW>;
     using T = StoreTraits<DT>;
     constexpr int NC = T::nc;
     constexpr int WC = S::wcols;
     constexpr int PF = S::pf;
+    constexpr int NLD = S::nld;
     extern __shared__ __align__(16) char smem[];
-    // LDS: [2 staging buffers][selection buffers cw*cap][cnt cw][2 x 16 row norms][item]
+    // staging buffers in LDS: a.nbuf of them (direct) or 2 (through registers); block blk of an
+    // item uses buffer blk % NB, and the blocks up to blk + NB - 1 are on their way meanwhile
+    const int NB = S::direct ? a.nbuf : 2;
+    const int D = NB - 1;
+    // LDS: [NB staging buffers][selection buffers cw*cap][row norms NB x NW x 64][item]
     char* stage = smem;
-    Cand* sel = (Cand*)(smem + 2 * S::buf_bytes);
-    int* cnt = (int*)(sel + S::cw * a.cap);
-    float* nstage = (float*)(cnt + S::cw);
-    int* s_item = (int*)(nstage + 2 * kBlockRows);
+    Cand* sel = (Cand*)(smem + NB * S::buf_bytes);
+    float* nstage = (float*)(sel + S::cw * a.cap);
+    int* s_item = (int*)(nstage + NB * NW * 64);
 
     const int lane = lane_id();
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int g = lane >> 4;                       // k-group / output row group
     const int jcol = lane & (NC - 1);              // column inside a set
     const int part = (NC == 8) ? ((lane >> 3) & 1) : 0;   // 0 = hi, 1 = lo operand column
     const bool owner = (NC == 16) || part == 0;    // lane whose accumulator holds the full dot
     Cand* mysel = sel + (wave * WC) * a.cap;
-    int* mycnt = cnt + wave * WC;
     const int seg_rows = a.dense ? a.dense_seg_rows : a.dyn[DYN_SEG_ROWS];
     const int myx = blockIdx.x & 7;                // workgroups are dealt round-robin to the 8 XCDs
     int drained = 0;                               // thread 0: queues found empty
+
+    // ---- per-lane constants of the staging layout
+    // row fragment of k-step t of this lane: abase[t & 3] + (t >> 2) * 256 inside a buffer
+    int abase[4];
+    // direct: byte offset inside a stored block of the chunk that load m of this lane moves
+    uint32_t goff[NLD];
+    {
+        const int i = lane & 15;
+        if constexpr (S::direct) {
+            const int hi = (i & S::swz) >> 2, lo = i & 3;
+#pragma unroll
+            for (int j = 0; j < 4; j++) abase[j] = i * S::rowp + 64 * (j ^ hi) + 16 * (g ^ lo);
+#pragma unroll
+            for (int m = 0; m < NLD; m++) {
+                const int L = (m * NW + wave) * 64 + lane;      // chunk position inside the buffer
+                const int r = L / S::cpr, pos = L % S::cpr;
+                goff[m] = (uint32_t)(min(r, kBlockRows - 1) * S::cpr + (pos ^ (r & S::swz))) * 16u;
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; j++) abase[j] = i * S::rowp + g * 16 + j * 64;
+#pragma unroll
+            for (int m = 0; m < NLD; m++) goff[m] = 0;
+        }
+    }
+    if (a.dbg_flags & 4) { abase[0] = abase[1] = abase[2] = abase[3] = 0; }   // experiment: broadcast reads
 #ifdef HR_SCAN_TIMING
     long long t_pop = 0, t_setup = 0, t_mfma = 0, t_sel = 0, t_stage = 0, t_bar = 0, t_emit = 0;
     int n_items = 0, n_blocks = 0, n_cand_blocks = 0, n_prunes = 0;
@@ -326,7 +410,7 @@ __global__ __launch_bounds__(kScanWaves * 64, 1) void k_scan(ScanArgs a)
             *s_item = item;
         }
         __syncthreads();
-        const int item = *s_item;
+        const int item = __builtin_amdgcn_readfirstlane(*s_item);
         if (item < 0) break;
         HR_TOC(t_pop, tk);
 
@@ -352,24 +436,52 @@ __global__ __launch_bounds__(kScanWaves * 64, 1) void k_scan(ScanArgs a)
         const int nrows = row_end - row0;
         const int nblk = (nrows + kBlockRows - 1) / kBlockRows;
         const char* src = (const char*)a.rows + (size_t)row0 * S::rowb;
-        // Loads for a block past the end of the segment re-read its last block: every path then
-        // issues the same number of loads per iteration, which is what lets the staging code
-        // wait for "all but the newest PF-1 blocks" with a fixed counter value instead of
-        // draining the whole prefetch ring.
-        auto block_chunks = [&](int blk) __attribute__((always_inline)) { return min(nrows - min(blk, nblk - 1) * kBlockRows, kBlockRows) * (S::rowb / 16); };
-        auto block_src = [&](int blk) __attribute__((always_inline)) { return src + (size_t)min(blk, nblk - 1) * kBlockRows * S::rowb; };
 
-        // ---- first row blocks on their way before anything else
-        // (the squared row norms of a block travel with it: a separate load inside the block
-        // loop would make every block wait for all the prefetches issued before it)
-        u32x4 ring[PF][S::nld];
-        float nring[PF];
+        // ---- staging.  Requests for a block past the end of the segment fetch its last block
+        // again (nobody reads the copy): every wave then has the same, fixed number of loads
+        // in flight at every point of the loop, which is what the wait counts below rely on.
+        //
+        // direct: block blk -> buffer buf, straight from HBM; the squared norms of its rows go
+        // to a place of this wave's own (each wave fetches its own copy: 64 bytes)
+        auto fill_direct = [&](int blk, int buf) __attribute__((always_inline)) {
+            const int bl = min(blk, nblk - 1);
+            const int valid = min(nrows - bl * kBlockRows, kBlockRows);
+            const char* bsrc = src + (size_t)bl * kBlockRows * S::rowb;
+            const uint32_t dst = lds_addr(stage) + buf * S::buf_bytes + wave * 1024;
+            if (valid == kBlockRows) {
+#pragma unroll
+                for (int m = 0; m < NLD; m++) lds_dma16(bsrc, goff[m], dst + m * NW * 1024);
+            } else {
+                // ragged last block: rows past the end repeat the last valid one (their scores
+                // are masked out of the selection)
+#pragma unroll
+                for (int m = 0; m < NLD; m++) {
+                    const int L = (m * NW + wave) * 64 + lane;
+                    const int r = L / S::cpr, pos = L % S::cpr;
+                    const uint32_t o = (uint32_t)(min(r, valid - 1) * S::cpr + (pos ^ (r & S::swz))) * 16u;
+                    lds_dma16(bsrc, o, dst + m * NW * 1024);
+                }
+            }
+            lds_dma4(a.row_norm + row0 + bl * kBlockRows, (uint32_t)min(lane & 15, valid - 1) * 4u,
+                     lds_addr(nstage) + (buf * NW + wave) * 256);
+        };
+        // through registers: a ring of PF blocks in flight
+        u32x4 ring[S::direct ? 1 : PF][NLD];
+        float nring[S::direct ? 1 : PF];
+        auto block_chunks = [&](int blk) __attribute__((always_inline)) { return min(nrows - min(blk, nblk - 1) * kBlockRows, kBlockRows) * S::cpr; };
+        auto block_src = [&](int blk) __attribute__((always_inline)) { return src + (size_t)min(blk, nblk - 1) * kBlockRows * S::rowb; };
         auto load_norm = [&](int blk) __attribute__((always_inline)) {
             const int r = min(row0 + min(blk, nblk - 1) * kBlockRows + (int)(threadIdx.x & (kBlockRows - 1)), row_end - 1);
             return a.row_norm[r];
         };
-        load_block<S>(block_src(0), block_chunks(0), ring[0]);
-        nring[0] = load_norm(0);
+
+        // ---- first row blocks on their way before anything else
+        if constexpr (S::direct) {
+            for (int i = 0; i < D; i++) fill_direct(i, i);
+        } else {
+            load_block<S>(block_src(0), block_chunks(0), ring[0]);
+            nring[0] = load_norm(0);
+        }
 
         // ---- query operands of this lane's columns into registers (B fragments)
         const int ecol0 = qt * S::cw + wave * WC + jcol;     // entry inside the bucket, set 0
@@ -391,7 +503,7 @@ __global__ __launch_bounds__(kScanWaves * 64, 1) void k_scan(ScanArgs a)
 #pragma unroll
             for (int t = 0; t < KSTEPS; t++)
                 bfrag[s][t] = col_ok[s] ? *(const u32x4*)(qp + t * 64) : u32x4{0, 0, 0, 0};
-            thr[s] = (col_ok[s] && !(a.dbg_flags & 1)) ? dec_key(a.thr[q[s]]) : __builtin_inff();
+            thr[s] = (owner && col_ok[s] && !(a.dbg_flags & 1)) ? dec_key(a.thr[q[s]]) : __builtin_inff();
         }
         // candidates buffered per column: kept in a register by every lane of the column (the
         // lanes of a column see the same ballots, so they stay in step without LDS traffic)
@@ -407,120 +519,178 @@ __global__ __launch_bounds__(kScanWaves * 64, 1) void k_scan(ScanArgs a)
         for (int s = 0; s < NCS; s++) nact += __builtin_amdgcn_ballot_w64(col_ok[s]) != 0 ? 1 : 0;
         if (a.dbg_flags & 2) nact = 0;
 
-        // Everything loaded so far (query operands, thresholds, first row block) is waited for
-        // here, once, and only then are the next PF blocks requested, oldest ring slot first.
-        // The loop is thus entered with exactly the loads in flight, in exactly the order, that
-        // every later iteration sees; the compiler's wait-count analysis (which merges the two
-        // ways into the loop) can then let the staging of a block wait for that block alone,
-        // with the PF-1 younger blocks still in flight, instead of draining the ring.
-        __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0) only
-        stage_block<DT, S>(stage, ring[0]);
-        nstage[threadIdx.x & (kBlockRows - 1)] = nring[0];      // (same value from 16 threads each)
-        static_for<PF>([&](auto pc) __attribute__((always_inline)) {
-            constexpr int slot = (decltype(pc)::value + 1) % PF;
-            load_block<S>(block_src(decltype(pc)::value + 1), block_chunks(decltype(pc)::value + 1), ring[slot]);
-            nring[slot] = load_norm(decltype(pc)::value + 1);
-        });
-        __syncthreads();
+        if constexpr (!S::direct) {
+            // Everything loaded so far (query operands, thresholds, first row block) is waited
+            // for here, once, and only then are the next PF blocks requested, oldest ring slot
+            // first.  The loop is thus entered with exactly the loads in flight, in exactly the
+            // order, that every later iteration sees; the compiler's wait-count analysis can
+            // then let the staging of a block wait for that block alone, with the PF-1 younger
+            // blocks still in flight, instead of draining the ring.
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+            stage_block<DT, S>(stage, ring[0]);
+            nstage[threadIdx.x & (kBlockRows - 1)] = nring[0];      // (same value from several threads)
+            static_for<PF>([&](auto pc) __attribute__((always_inline)) {
+                constexpr int slot = (decltype(pc)::value + 1) % PF;
+                load_block<S>(block_src(decltype(pc)::value + 1), block_chunks(decltype(pc)::value + 1), ring[slot]);
+                nring[slot] = load_norm(decltype(pc)::value + 1);
+            });
+        } else {
+            // The query operands and thresholds are waited for here, once (the first blocks
+            // with them): if the compiler still counted them as in flight inside the loop it
+            // would wait for "everything" at their first use in every iteration, and that
+            // includes the blocks on their way to LDS.
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+        }
         HR_TOC(t_setup, tk);
 
-        for (int b0 = 0; b0 < nblk; b0 += PF) {
-            static_for<PF>([&](auto pc) __attribute__((always_inline)) {
-                constexpr int p = decltype(pc)::value;
-                const int blk = b0 + p;
-                if (blk >= nblk) return;
-                char* cur = stage + (blk & 1) * S::buf_bytes;
-                const int rbase = row0 + blk * kBlockRows + g * 4;   // first of this lane's 4 rows
-
-#ifdef HR_SCAN_TIMING
-                n_blocks++;
-#endif
-                if (nact > 0) {
-                    const floatx4 nrm = *(const floatx4*)(nstage + (blk & 1) * kBlockRows + g * 4);
-                    floatx4 acc[NCS][2];
-                    const char* ap = cur + (lane & 15) * S::rowp + g * 16;
-                    if (NCS == 2 && nact == 2) mfma_block<DT, KSTEPS, NCS, NCS, S>(ap, bfrag, acc);
-                    else                       mfma_block<DT, KSTEPS, NCS, 1, S>(ap, bfrag, acc);
-                    HR_TOC(t_mfma, tk);
-
+        // ---- the blocks of the segment.  Per block (direct staging): (1) this wave's part of
+        // the block has landed, (2) barrier: so has everybody's, and nobody reads the previous
+        // block any more, (3) request block blk + D into the buffer the previous block leaves,
+        // (4) multiply, (5) select.
+        //
+        // ---- selection over the scores of one block: acc = accumulators of the block, nrm =
+        // squared norms of this lane's 4 rows, rbase = first of those rows
+        auto select_block = [&](const floatx4 (&acc)[NCS][kAcc], const floatx4 nrm, const int rbase) __attribute__((always_inline)) {
 #pragma unroll
-                    for (int s = 0; s < NCS; s++) {
-                        if (s >= nact) break;
-                        // ---- keys of this lane's 4 (row, column) pairs of set s
-                        float key[4];
-                        bool pass[4];
-                        bool any = false;
+            for (int s = 0; s < NCS; s++) {
+                if (s >= nact) break;
+                // ---- keys of this lane's 4 (row, column) pairs of set s.  The common case is
+                // that none reaches the column's threshold: that is decided with one compare
+                // of the largest of the four (thr is +inf in lanes that own no query column).
+                float key[4];
 #pragma unroll
-                        for (int r = 0; r < 4; r++) {
-                            float dot;
-                            if constexpr (DT == HR_F32) {
-                                float t0 = __shfl_xor(acc[s][0][r], 8);       // hi rows x lo query
-                                float t1 = __shfl_xor(acc[s][1][r], 8);       // lo rows x lo query
-                                dot = acc[s][0][r] + (t0 + acc[s][1][r]) * (1.0f / 2048.0f) + t1 * (1.0f / 4194304.0f);
-                            } else if constexpr (DT == HR_BF16) {
-                                float v = acc[s][0][r] + acc[s][1][r];
-                                dot = v + __shfl_xor(v, 8);
-                            } else {
-                                dot = acc[s][0][r] + acc[s][1][r];
-                            }
-                            key[r] = a.l2 ? (2.0f * dot - nrm[r]) : dot;
-                            pass[r] = owner && col_ok[s] && (rbase + r < row_end) && key[r] >= thr[s];
-                            any |= pass[r];
-                        }
-                        // ---- append what reaches the column's threshold
-                        if (__builtin_amdgcn_ballot_w64(any) != 0) {
-#ifdef HR_SCAN_TIMING
-                            n_cand_blocks++;
-#endif
-                            Cand* ssel = mysel + (s * NC) * a.cap;
-                            // slot of each new candidate = column count + candidates of the same
-                            // column in earlier row slots and in lower lanes of this row slot
-                            int add = 0;
-#pragma unroll
-                            for (int r = 0; r < 4; r++) {
-                                const unsigned long long mine = __builtin_amdgcn_ballot_w64(pass[r]) & colmask;
-                                if (pass[r]) {
-                                    const int pos = ccnt[s] + add + __builtin_popcountll(mine & below);
-                                    ssel[jcol * a.cap + pos] = Cand{enc_key(key[r]), (uint32_t)(rbase + r)};
-                                }
-                                add += __builtin_popcountll(mine);
-                            }
-                            ccnt[s] += add;
-                            unsigned long long full = __builtin_amdgcn_ballot_w64(lane < NC && ccnt[s] > a.cap - kAppendMax);
-                            if (full) wave_sync();
-                            while (full) {
-                                int col = __builtin_ctzll(full);
-                                full &= full - 1;
-                                int n = __builtin_amdgcn_readlane(ccnt[s], col);
-                                uint32_t kth = select_k(ssel + col * a.cap, n, a.k, a.cap, a.row_ids);
-#ifdef HR_SCAN_TIMING
-                                n_prunes++;
-#endif
-                                float nt = 0.f;
-                                if (lane == col) {
-                                    uint32_t old = atomicMax(&a.thr[q[s]], kth);
-                                    nt = dec_key(kth > old ? kth : old);
-                                }
-                                nt = __shfl(nt, col);
-                                if (jcol == col) { thr[s] = fmaxf(thr[s], nt); ccnt[s] = a.k; }
-                            }
-                        }
+                for (int r = 0; r < 4; r++) {
+                    float dot;
+                    if constexpr (DT == HR_F32) {
+                        float t0 = __shfl_xor(acc[s][0][r], 8);       // hi rows x lo query
+                        float t1 = __shfl_xor(acc[s][1][r], 8);       // lo rows x lo query
+                        dot = acc[s][0][r] + (t0 + acc[s][1][r]) * (1.0f / 2048.0f) + t1 * (1.0f / 4194304.0f);
+                    } else if constexpr (DT == HR_BF16) {
+                        float v = acc[s][0][r] + acc[s][1][r];
+                        dot = v + __shfl_xor(v, 8);
+                    } else {
+                        dot = acc[s][0][r] + acc[s][1][r];
                     }
-                    HR_TOC(t_sel, tk);
+                    key[r] = dot;
                 }
+                if (a.l2) {
+#pragma unroll
+                    for (int r = 0; r < 4; r++) key[r] = 2.0f * key[r] - nrm[r];
+                }
+                const float best = fmaxf(fmaxf(key[0], key[1]), fmaxf(key[2], key[3]));
+                // ---- append what reaches the column's threshold
+                if (__builtin_amdgcn_ballot_w64(best >= thr[s]) != 0) {
+#ifdef HR_SCAN_TIMING
+                    n_cand_blocks++;
+#endif
+                    bool pass[4];
+#pragma unroll
+                    for (int r = 0; r < 4; r++) pass[r] = key[r] >= thr[s] && (rbase + r < row_end);
+                    Cand* ssel = mysel + (s * NC) * a.cap;
+                    // slot of each new candidate = column count + candidates of the same
+                    // column in earlier row slots and in lower lanes of this row slot
+                    int add = 0;
+#pragma unroll
+                    for (int r = 0; r < 4; r++) {
+                        const unsigned long long mine = __builtin_amdgcn_ballot_w64(pass[r]) & colmask;
+                        if (pass[r]) {
+                            const int pos = ccnt[s] + add + __builtin_popcountll(mine & below);
+                            ssel[jcol * a.cap + pos] = Cand{enc_key(key[r]), (uint32_t)(rbase + r)};
+                        }
+                        add += __builtin_popcountll(mine);
+                    }
+                    ccnt[s] += add;
+                    unsigned long long full = __builtin_amdgcn_ballot_w64(lane < NC && ccnt[s] > a.cap - kAppendMax);
+                    if (full) wave_sync();
+                    while (full) {
+                        int col = __builtin_ctzll(full);
+                        full &= full - 1;
+                        int n = __builtin_amdgcn_readlane(ccnt[s], col);
+                        uint32_t kth = select_k(ssel + col * a.cap, n, a.k, a.cap, a.row_ids);
+#ifdef HR_SCAN_TIMING
+                        n_prunes++;
+#endif
+                        float nt = 0.f;
+                        if (lane == col) {
+                            uint32_t old = atomicMax(&a.thr[q[s]], kth);
+                            nt = dec_key(kth > old ? kth : old);
+                        }
+                        nt = __shfl(nt, col);
+                        if (jcol == col) { thr[s] = fmaxf(thr[s], nt); ccnt[s] = a.k; }
+                    }
+                }
+            }
+            HR_TOC(t_sel, tk);
+        };
 
-                // ---- next block: registers -> LDS, and refill the ring slot it leaves
-                {
-                    constexpr int pn = (p + 1) % PF;
-                    stage_block<DT, S>(stage + ((blk + 1) & 1) * S::buf_bytes, ring[pn]);
-                    nstage[((blk + 1) & 1) * kBlockRows + (threadIdx.x & (kBlockRows - 1))] = nring[pn];
-                    load_block<S>(block_src(blk + 1 + PF), block_chunks(blk + 1 + PF), ring[pn]);
-                    nring[pn] = load_norm(blk + 1 + PF);
-                }
-                HR_TOC(t_stage, tk);
-                __syncthreads();
-                HR_TOC(t_bar, tk);
-            });
+        int bi = 0;                                              // blk % NB
+        floatx4 accs[1][NCS][kAcc];
+        floatx4 nrms[1] = {floatx4{0.f, 0.f, 0.f, 0.f}};
+        // direct staging: (1) this wave's part of block blk has landed, (2) barrier: so has
+        // everybody's, and nobody reads block blk-1 any more, (3) request block blk+D into the
+        // buffer that one leaves, (4) multiply, (5) select
+        auto step_direct = [&](int blk) __attribute__((always_inline)) {
+            // all but the D-1 youngest requests of this wave (NLD + 1 loads each) are done
+            switch (D) {
+            case 1: wait_vmcnt<0>(); break;
+            case 2: wait_vmcnt<NLD + 1>(); break;
+            case 3: wait_vmcnt<2 * (NLD + 1)>(); break;
+            default: wait_vmcnt<3 * (NLD + 1)>(); break;
+            }
+            __builtin_amdgcn_s_barrier();
+            HR_TOC(t_bar, tk);
+#ifdef HR_SCAN_TIMING
+            n_blocks++;
+#endif
+            fill_direct(blk + D, bi == 0 ? NB - 1 : bi - 1);
+            HR_TOC(t_stage, tk);
+            if (nact > 0) {
+                const char* cur = stage + bi * S::buf_bytes;
+                if (a.l2) nrms[0] = *(const floatx4*)(nstage + (bi * NW + wave) * 64 + g * 4);
+                const char* const ap[4] = {cur + abase[0], cur + abase[1], cur + abase[2], cur + abase[3]};
+                if (NCS == 2 && nact == 2) mfma_block<DT, KSTEPS, NCS, NCS, S>(ap, bfrag, accs[0]);
+                else                       mfma_block<DT, KSTEPS, NCS, 1, S>(ap, bfrag, accs[0]);
+                HR_TOC(t_mfma, tk);
+                select_block(accs[0], nrms[0], row0 + blk * kBlockRows + g * 4);
+            }
+            bi = bi + 1 == NB ? 0 : bi + 1;
+        };
+        // through registers: (1) barrier: block blk is complete in LDS and nobody reads block
+        // blk-1 any more, (2) block blk+1 from the ring into the buffer that one leaves, and
+        // its ring slot refilled, (3) multiply, (4) select
+        auto step_regs = [&](int blk, auto pc) __attribute__((always_inline)) {
+            constexpr int p = decltype(pc)::value;               // ring position
+            const bool live = blk < nblk;
+            __syncthreads();
+            HR_TOC(t_bar, tk);
+            constexpr int pn = (p + 1) % PF;
+            stage_block<DT, S>(stage + (bi ^ 1) * S::buf_bytes, ring[pn]);
+            nstage[(bi ^ 1) * kBlockRows + (threadIdx.x & (kBlockRows - 1))] = nring[pn];
+            load_block<S>(block_src(blk + 1 + PF), block_chunks(blk + 1 + PF), ring[pn]);
+            nring[pn] = load_norm(blk + 1 + PF);
+            HR_TOC(t_stage, tk);
+#ifdef HR_SCAN_TIMING
+            n_blocks++;
+#endif
+            if (live && nact > 0) {
+                const char* cur = stage + bi * S::buf_bytes;
+                nrms[0] = *(const floatx4*)(nstage + bi * kBlockRows + g * 4);
+                const char* const ap[4] = {cur + abase[0], cur + abase[1], cur + abase[2], cur + abase[3]};
+                if (NCS == 2 && nact == 2) mfma_block<DT, KSTEPS, NCS, NCS, S>(ap, bfrag, accs[0]);
+                else                       mfma_block<DT, KSTEPS, NCS, 1, S>(ap, bfrag, accs[0]);
+                HR_TOC(t_mfma, tk);
+                select_block(accs[0], nrms[0], row0 + blk * kBlockRows + g * 4);
+            }
+            bi ^= 1;
+        };
+        if constexpr (S::direct) {
+            for (int blk = 0; blk < nblk; blk++) step_direct(blk);
+        } else {
+            // (iterations past the last block of a ragged round still stage and load: an early
+            // exit would be a path with fewer loads in flight, and the compiler would size
+            // every wait in the loop for that path)
+            for (int b0 = 0; b0 < nblk; b0 += PF)
+                static_for<PF>([&](auto pc) __attribute__((always_inline)) { step_regs(b0 + decltype(pc)::value, pc); });
         }
 
         // ---- hand what is left to the item's slots: columns still over k are cut down first
@@ -581,15 +751,15 @@ __global__ __launch_bounds__(kScanWaves * 64, 1) void k_scan(ScanArgs a)
 #endif
 }
 
-template <int DT, int NCS>
-inline hipError_t launch_scan_ncs(int d, const ScanArgs& a, int grid, size_t lds, hipStream_t s)
+template <int DT, int NCS, int NW>
+inline hipError_t launch_scan_shape(int d, const ScanArgs& a, int grid, size_t lds, hipStream_t s)
 {
 #define HR_SCAN_CASE(KS)                                                                           \
     case KS * 32: {                                                                                \
-        auto kern = k_scan<DT, KS, NCS>;                                                           \
+        auto kern = k_scan<DT, KS, NCS, NW>;                                                       \
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
         if (e != hipSuccess) return e;                                                             \
-        hipLaunchKernelGGL(kern, dim3(grid), dim3(kScanWaves * 64), lds, s, a);                    \
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(NW * 64), lds, s, a);                            \
         return hipGetLastError();                                                                  \
     }
     switch (d) {
@@ -605,9 +775,13 @@ inline hipError_t launch_scan_ncs(int d, const ScanArgs& a, int grid, size_t lds
 }
 
 template <int DT>
-inline hipError_t launch_scan_dtype(int d, const ScanArgs& a, int ncs, int grid, size_t lds, hipStream_t s)
+inline hipError_t launch_scan_dtype(int d, const ScanArgs& a, int shape, int grid, size_t lds, hipStream_t s)
 {
-    return ncs == 2 ? launch_scan_ncs<DT, 2>(d, a, grid, lds, s) : launch_scan_ncs<DT, 1>(d, a, grid, lds, s);
+    switch (shape) {
+    case SCAN_WIDE: return launch_scan_shape<DT, 1, 8>(d, a, grid, lds, s);
+    case SCAN_WIDE4: return launch_scan_shape<DT, 2, 4>(d, a, grid, lds, s);
+    default: return launch_scan_shape<DT, 1, 4>(d, a, grid, lds, s);
+    }
 }
 
 // ------------------------------------------------------------------------------------------
