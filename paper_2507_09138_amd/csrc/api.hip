@@ -36,9 +36,10 @@ hipError_t launch_scan(int dtype, int d, const ScanArgs& a, int shape, int grid,
     }
 }
 
-// LDS bytes of one workgroup of the given shape with nbuf staging buffers (must match the
-// carve-up at the top of k_scan and ScanShape::buf_bytes)
-size_t scan_lds_bytes(int dtype, int d, int k, int shape, int nbuf)
+// LDS bytes of one workgroup of the given shape with nbuf staging buffers and selection
+// buffers of cap entries per query column (must match the carve-up at the top of k_scan and
+// ScanShape::buf_bytes)
+size_t scan_lds_bytes(int dtype, int d, int cap, int shape, int nbuf)
 {
     const int nw = shape_waves(shape);
     size_t buf;
@@ -48,33 +49,45 @@ size_t scan_lds_bytes(int dtype, int d, int k, int shape, int nbuf)
         const int chunks = kBlockRows * d * 2 / 16, threads = nw * 64;
         buf = (size_t)((chunks + threads - 1) / threads) * threads * 16;
     }
-    const size_t cap = sel_cap(k);
     const size_t cw = (size_t)cols_per_set(dtype) * shape_sets(shape);
-    return nbuf * buf + cw * cap * sizeof(Cand) + (size_t)nbuf * nw * 64 * sizeof(float) + 16;
+    return nbuf * buf + cw * cap * sizeof(Cand) + (size_t)nbuf * kBlockRows * sizeof(float) + 16;
 }
 }  // namespace hr
 
 static constexpr int kLdsLimit = 160 * 1024;      // LDS per workgroup on gfx950
 
-// Workgroup shape and number of staging buffers for a scan.  Shape: 8 waves (two per SIMD)
-// when the selection buffers of that many query columns still fit in LDS, else 4 waves with
-// half the columns.  Buffers: float32 rows are staged through registers into 2; 16-bit rows
-// go straight to LDS into as many as fit, up to 5 (4 blocks on their way).  shape -1 = no fit.
-struct ScanPick { int shape, nbuf; };
+// Workgroup shape, number of staging buffers and selection buffer capacity for a scan.
+// Shape: 8 waves (two per SIMD) when the selection buffers of that many query columns still
+// fit in LDS, else 4 waves with half the columns.  Buffers: float32 rows are staged through
+// registers into 2; 16-bit rows go straight to LDS, best into 4 (blocks in pairs, one barrier
+// per pair), for which the selection buffers may give up a little of their capacity, else
+// into 3 or 2.  shape -1 = no fit.
+struct ScanPick { int shape, nbuf, cap; };
 static ScanPick pick_shape(int dtype, int d, int k)
 {
     static const char* force = getenv("HR_SCAN_SHAPE");      // development switch: "<shape><nbuf>", e.g. 23
-    const int shapes[2] = {hr::SCAN_WIDE, hr::SCAN_NARROW};
+    const int cap = hr::sel_cap(k);
+    const int cap_min = k + hr::kAppendMax + 4 + 24 < cap ? k + hr::kAppendMax + 4 + 24 : cap;   // least worth having
+    auto fit_cap = [&](int shape, int nbuf) {     // largest capacity (multiple of 4) that fits, or 0
+        for (int c = cap; c >= cap_min; c -= 4)
+            if (hr::scan_lds_bytes(dtype, d, c, shape, nbuf) <= (size_t)kLdsLimit) return c;
+        return 0;
+    };
     if (force && dtype != HR_F32) {
         const int shape = force[0] - '0', nbuf = force[1] - '0';
-        if (hr::scan_lds_bytes(dtype, d, k, shape, nbuf) <= (size_t)kLdsLimit) return {shape, nbuf};
+        if (const int c = fit_cap(shape, nbuf)) return {shape, nbuf, c};
     }
+    const int shapes[2] = {hr::SCAN_WIDE, hr::SCAN_NARROW};
     for (int shape : shapes) {
-        const int most = dtype == HR_F32 ? 2 : 5;
-        for (int nbuf = most; nbuf >= 2; nbuf--)
-            if (hr::scan_lds_bytes(dtype, d, k, shape, nbuf) <= (size_t)kLdsLimit) return {shape, nbuf};
+        if (dtype == HR_F32) {
+            if (hr::scan_lds_bytes(dtype, d, cap, shape, 2) <= (size_t)kLdsLimit) return {shape, 2, cap};
+            continue;
+        }
+        if (const int c = fit_cap(shape, 4)) return {shape, 4, c};
+        for (int nbuf = 3; nbuf >= 2; nbuf--)
+            if (hr::scan_lds_bytes(dtype, d, cap, shape, nbuf) <= (size_t)kLdsLimit) return {shape, nbuf, cap};
     }
-    return {-1, 0};
+    return {-1, 0, 0};
 }
 
 using namespace hr;
@@ -125,10 +138,11 @@ static size_t align_up(size_t v) { return (v + HR_WORKSPACE_ALIGN - 1) & ~(size_
 // Layout of the caller's workspace for one batch shape.  Offsets in bytes.
 struct Plan {
     // coarse step: centroid table scanned with all queries as one dense bucket
-    int shape_c /* workgroup shape, -1 = no fit */, nbuf_c, cw_c, nqt_c, seg_c, nseg_c, items_c;
+    int shape_c /* workgroup shape, -1 = no fit */, nbuf_c, cap_c, cw_c, nqt_c, seg_c, nseg_c, items_c;
     // list scan
-    int shape_s, nbuf_s, cw_s, item_cap;
-    size_t o_zero, n_zero;          // ints cleared per call: list_w[nlist], dyn[DYN_COUNT], counters[8]
+    int shape_s, nbuf_s, cap_s, cw_s, item_cap;
+    size_t o_zero, n_zero;          // ints cleared per call: list_w[nlist], dyn[DYN_COUNT], counters[8], ..., then
+    size_t zoff_hist, zoff_hpar;    // (in ints from o_zero) per-query key histograms and their parameters
     size_t o_thr;                   // 2*nq ints set to "-inf"
     size_t o_qop_c, o_qnorm_c, o_qop_s, o_qnorm_s;
     size_t o_probe;
@@ -143,8 +157,8 @@ static Plan make_plan(const hr_ivf_index* ix, int64_t nq, int nprobe, int k)
     const int64_t nlist = ix->nlist;
     const int kk = k > nprobe ? k : nprobe;      // slots are shared by the two scans
     const ScanPick pc = pick_shape(HR_F32, ix->d, nprobe), ps = pick_shape(ix->dtype, ix->d, k);
-    p.shape_c = pc.shape; p.nbuf_c = pc.nbuf;
-    p.shape_s = ps.shape; p.nbuf_s = ps.nbuf;
+    p.shape_c = pc.shape; p.nbuf_c = pc.nbuf; p.cap_c = pc.cap;
+    p.shape_s = ps.shape; p.nbuf_s = ps.nbuf; p.cap_s = ps.cap;
     p.cw_c = cols_per_set(HR_F32) * shape_sets(p.shape_c < 0 ? 0 : p.shape_c);
     p.nqt_c = (int)((nq + p.cw_c - 1) / p.cw_c);
     int64_t seg = (nlist * (int64_t)p.nqt_c + 2047) / 2048;
@@ -160,7 +174,9 @@ static Plan make_plan(const hr_ivf_index* ix, int64_t nq, int nprobe, int k)
 
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
-    p.n_zero = (size_t)nlist + DYN_COUNT + 24;     // + 8 counters, 8 queue lengths, 8 queue heads
+    p.zoff_hist = (size_t)nlist + DYN_COUNT + 24;   // + 8 counters, 8 queue lengths, 8 queue heads
+    p.zoff_hpar = p.zoff_hist + (size_t)nq * kHistBins;
+    p.n_zero = p.zoff_hpar + (size_t)nq * 2;
     p.o_zero = take(p.n_zero * 4);
     p.o_thr = take((size_t)nq * 2 * 4);
     p.o_qop_c = take((size_t)nq * 2 * ix->d * 2);
@@ -365,7 +381,7 @@ static int enqueue_coarse(const hr_ivf_index* ix, const Plan& p, char* ws, int64
 {
     if (p.shape_c < 0)
         return fail(HR_ERR_UNSUPPORTED, "coarse step does not fit in LDS (d=%d, nprobe=%d)", ix->d, nprobe);
-    const size_t lds = scan_lds_bytes(HR_F32, ix->d, nprobe, p.shape_c, p.nbuf_c);
+    const size_t lds = scan_lds_bytes(HR_F32, ix->d, p.cap_c, p.shape_c, p.nbuf_c);
     int* zero = (int*)(ws + p.o_zero);
     ScanArgs a{};
     a.rows = ix->centroids;
@@ -381,7 +397,7 @@ static int enqueue_coarse(const hr_ivf_index* ix, const Plan& p, char* ws, int64
     a.dense_nqt = p.nqt_c;
     a.dense_seg_rows = p.seg_c;
     a.dense_nrows = (int)ix->nlist;
-    a.nq = (int)nq; a.k = nprobe; a.cap = sel_cap(nprobe); a.l2 = metric == HR_METRIC_L2;
+    a.nq = (int)nq; a.k = nprobe; a.cap = p.cap_c; a.l2 = metric == HR_METRIC_L2;
     a.nbuf = p.nbuf_c;
     int grid = scan_grid(ix, lds, p.shape_c);
     if (grid > p.items_c) grid = p.items_c;
@@ -404,7 +420,7 @@ static int enqueue_scan(const hr_ivf_index* ix, const Plan& p, char* ws, int64_t
 {
     if (p.shape_s < 0)
         return fail(HR_ERR_UNSUPPORTED, "list scan does not fit in LDS (d=%d, k=%d)", ix->d, k);
-    const size_t lds = scan_lds_bytes(ix->dtype, ix->d, k, p.shape_s, p.nbuf_s);
+    const size_t lds = scan_lds_bytes(ix->dtype, ix->d, p.cap_s, p.shape_s, p.nbuf_s);
     int* zero = (int*)(ws + p.o_zero);
     BucketArgs b{};
     b.probe = probe; b.nq = (int)nq; b.nprobe = nprobe; b.nlist = (int)ix->nlist; b.cw = p.cw_s;
@@ -426,6 +442,7 @@ static int enqueue_scan(const hr_ivf_index* ix, const Plan& p, char* ws, int64_t
     sd.rows = ix->vectors; sd.row_norm = ix->d_row_norm; sd.qop = ws + p.o_qop_s;
     sd.probe = probe; sd.list_off = ix->d_list_off;
     sd.thr = (uint32_t*)(ws + p.o_thr) + nq;
+    sd.hpar = (float*)(zero + p.zoff_hpar);
     sd.nq = (int)nq; sd.nprobe = nprobe; sd.nlist = (int)ix->nlist; sd.k = k;
     sd.seed_rows = k + 28 < 64 ? 64 : ((k + 28 + 15) & ~15);
     if (sd.seed_rows > 192) sd.seed_rows = 192;
@@ -453,8 +470,10 @@ static int enqueue_scan(const hr_ivf_index* ix, const Plan& p, char* ws, int64_t
     a.dbg = g_dbg;
     { const char* f = getenv("HR_DEBUG_FLAGS"); a.dbg_flags = f ? atoi(f) : 0; }
     a.dense = 0;
-    a.nq = (int)nq; a.k = k; a.cap = sel_cap(k); a.l2 = metric == HR_METRIC_L2;
+    a.nq = (int)nq; a.k = k; a.cap = p.cap_s; a.l2 = metric == HR_METRIC_L2;
     a.nbuf = p.nbuf_s;
+    a.hist = getenv("HR_NO_HIST") ? nullptr : zero + p.zoff_hist;
+    a.hpar = (const float*)(zero + p.zoff_hpar);
     hr_ivf_index* mix = const_cast<hr_ivf_index*>(ix);
     const bool timed = mix->prof_ev && mix->prof_n < mix->prof_cap;
     if (timed) HR_HIP(hipEventRecord(mix->prof_ev[2 * mix->prof_n], s));

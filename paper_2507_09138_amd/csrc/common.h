@@ -13,7 +13,8 @@ constexpr int kRowPad = 32;                // bytes of LDS padding per staged ro
                                            // for the 16-rows x 16-byte MFMA fragment reads (16 is 2-way)
 constexpr int kAppendMax = 16;             // most candidates one column can gain per block
 constexpr int kMinSegRows = 256;           // smallest rows-per-work-item
-constexpr int kItemTarget = 8192;         // aimed number of scan work items per batch
+constexpr int kItemTarget = 4096;
+constexpr int kHistBins = 64;              // per-query histogram of candidate keys (one bin per lane)         // aimed number of scan work items per batch
 
 // columns (queries) per 16-column MFMA set: 16 when the query operand is one binary16 row, 8
 // when it is a (hi, lo) pair occupying two MFMA columns.
@@ -103,6 +104,8 @@ struct ScanArgs {
     int dense, dense_items, dense_nqt, dense_seg_rows, dense_nrows;
     int nq, k, cap, l2;
     int nbuf;                   // staging buffers in LDS (16-bit storage; float32 always uses 2)
+    int* hist;                  // [nq][kHistBins] keys found so far per query, by key range (or nullptr)
+    const float* hpar;          // [nq][2] lower edge of bin 0 and bin width (width 0: query has no histogram)
     long long* dbg;             // per-workgroup phase timers (only in HR_SCAN_TIMING builds)
     int dbg_flags;              // experiments: 1 = thresholds at +inf (no selection), 2 = no MFMA/selection
 };
@@ -114,6 +117,7 @@ struct SeedArgs {
     const int* probe;           // [nq, nprobe]; column 0 is the list used
     const int* list_off;        // [nlist+1]
     uint32_t* thr;              // [nq]
+    float* hpar;                // [nq][2] histogram parameters of the scan (see ScanArgs)
     int nq, nprobe, nlist, k, seed_rows, l2;
 };
 
@@ -142,7 +146,7 @@ struct MergeArgs {
 
 // launchers implemented in the .hip files
 hipError_t launch_scan(int dtype, int d, const ScanArgs& a, int shape, int grid, size_t lds_bytes, hipStream_t s);
-size_t scan_lds_bytes(int dtype, int d, int k, int shape, int nbuf);
+size_t scan_lds_bytes(int dtype, int d, int cap, int shape, int nbuf);
 hipError_t launch_merge(const MergeArgs& a, hipStream_t s);
 hipError_t launch_seed(int dtype, int d, const SeedArgs& a, hipStream_t s);
 hipError_t launch_row_norms(const void* rows, int dtype, int64_t nrows, int d, float* out, hipStream_t s);

@@ -83,6 +83,24 @@ __device__ __forceinline__ void wait_vmcnt()
     asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
 }
 
+// inclusive prefix sum over the 64 lanes of a wave (row shifts inside each group of 16 lanes,
+// then the last lane of rows 0..2 added to the rows after it)
+__device__ __forceinline__ int wave_prefix_sum(int v)
+{
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, false);   // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, false);   // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, false);   // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, false);   // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);   // row_bcast:15 into rows 1 and 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);   // row_bcast:31 into rows 2 and 3
+    return v;
+}
+
+// Lower edge of histogram bin b of a query whose bin 0 starts at base and whose bins are w
+// wide; one expression, used wherever a key is binned or a bound is derived, so that a key
+// counted in bin b is never below the edge that later readers compute for b.
+__device__ __forceinline__ float hist_edge(float base, float w, int b) { return __builtin_fmaf((float)b, w, base); }
+
 // Keep the k best of the n (> k) candidates in buf[0..n): afterwards buf[0..k) holds them, in
 // no particular order.  Order: key descending, then label ascending (label = row number when
 // ids == nullptr; labels are only fetched when equal keys straddle the k-th place).
@@ -200,9 +218,10 @@ struct ScanShape {
     static constexpr int rowp = direct ? rowb : d * 2 + kRowPad;   // bytes of one staged row (one plane)
     static constexpr int plane_bytes = kBlockRows * rowp;
     static constexpr int chunks = kBlockRows * cpr;                // 16-byte chunks per block
-    static constexpr int nld = (chunks + threads - 1) / threads;   // chunks per thread per block
+    static constexpr int nfw = NW;                                 // waves that move rows: all
+    static constexpr int nld = (chunks + nfw * 64 - 1) / (nfw * 64);   // chunks per thread per block
     // (direct: every wave always issues nld loads, so a buffer is a whole number of them)
-    static constexpr int buf_bytes = direct ? nld * threads * 16 : plane_bytes * planes;
+    static constexpr int buf_bytes = direct ? nld * nfw * 1024 : plane_bytes * planes;
     // k-steps whose row fragments are fetched from LDS together, ahead of their MFMAs
     static constexpr int grp = scan_group(DT, KSTEPS, NW);
     // register path: row blocks kept in flight in registers ahead of the one being staged
@@ -340,13 +359,18 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
     extern __shared__ __align__(16) char smem[];
     // staging buffers in LDS: a.nbuf of them (direct) or 2 (through registers); block blk of an
     // item uses buffer blk % NB, and the blocks up to blk + NB - 1 are on their way meanwhile
+    // With 4 buffers (direct) the blocks go in pairs: one barrier per two blocks, the next pair
+    // on its way meanwhile.  A barrier per block keeps the two waves of a SIMD in step (both
+    // want the matrix pipeline, then both the vector ALU); between the barriers of a pair they
+    // drift apart and overlap.
     const int NB = S::direct ? a.nbuf : 2;
-    const int D = NB - 1;
-    // LDS: [NB staging buffers][selection buffers cw*cap][row norms NB x NW x 64][item]
+    const bool pairs = S::direct && NB == 4;
+    const int D = pairs ? 2 : NB - 1;              // blocks requested ahead of the one in use
+    // LDS: [NB staging buffers][selection buffers cw*cap][row norms NB x 16][item]
     char* stage = smem;
     Cand* sel = (Cand*)(smem + NB * S::buf_bytes);
     float* nstage = (float*)(sel + S::cw * a.cap);
-    int* s_item = (int*)(nstage + NB * NW * 64);
+    int* s_item = (int*)(nstage + NB * kBlockRows);
 
     const int lane = lane_id();
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -372,7 +396,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
             for (int j = 0; j < 4; j++) abase[j] = i * S::rowp + 64 * (j ^ hi) + 16 * (g ^ lo);
 #pragma unroll
             for (int m = 0; m < NLD; m++) {
-                const int L = (m * NW + wave) * 64 + lane;      // chunk position inside the buffer
+                const int L = (m * S::nfw + wave) * 64 + lane;  // chunk position inside the buffer
                 const int r = L / S::cpr, pos = L % S::cpr;
                 goff[m] = (uint32_t)(min(r, kBlockRows - 1) * S::cpr + (pos ^ (r & S::swz))) * 16u;
             }
@@ -444,26 +468,29 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
         // direct: block blk -> buffer buf, straight from HBM; the squared norms of its rows go
         // to a place of this wave's own (each wave fetches its own copy: 64 bytes)
         auto fill_direct = [&](int blk, int buf) __attribute__((always_inline)) {
-            const int bl = min(blk, nblk - 1);
+            if (a.dbg_flags & 16) return;      // experiment: compute on whatever is in LDS
+            const int bl = (a.dbg_flags & 64) ? 0 : min(blk, nblk - 1);      // experiment 64: always the first block (L2 hits)
             const int valid = min(nrows - bl * kBlockRows, kBlockRows);
             const char* bsrc = src + (size_t)bl * kBlockRows * S::rowb;
             const uint32_t dst = lds_addr(stage) + buf * S::buf_bytes + wave * 1024;
             if (valid == kBlockRows) {
 #pragma unroll
-                for (int m = 0; m < NLD; m++) lds_dma16(bsrc, goff[m], dst + m * NW * 1024);
+                for (int m = 0; m < NLD; m++) lds_dma16(bsrc, goff[m], dst + m * S::nfw * 1024);
             } else {
                 // ragged last block: rows past the end repeat the last valid one (their scores
                 // are masked out of the selection)
 #pragma unroll
                 for (int m = 0; m < NLD; m++) {
-                    const int L = (m * NW + wave) * 64 + lane;
+                    const int L = (m * S::nfw + wave) * 64 + lane;
                     const int r = L / S::cpr, pos = L % S::cpr;
                     const uint32_t o = (uint32_t)(min(r, valid - 1) * S::cpr + (pos ^ (r & S::swz))) * 16u;
-                    lds_dma16(bsrc, o, dst + m * NW * 1024);
+                    lds_dma16(bsrc, o, dst + m * S::nfw * 1024);
                 }
             }
-            lds_dma4(a.row_norm + row0 + bl * kBlockRows, (uint32_t)min(lane & 15, valid - 1) * 4u,
-                     lds_addr(nstage) + (buf * NW + wave) * 256);
+            // (every wave writes the same 16 norms: the same number of loads per wave)
+            if (lane < kBlockRows)
+                lds_dma4(a.row_norm + row0 + bl * kBlockRows, (uint32_t)min(lane, valid - 1) * 4u,
+                         lds_addr(nstage) + buf * (kBlockRows * 4));
         };
         // through registers: a ring of PF blocks in flight
         u32x4 ring[S::direct ? 1 : PF][NLD];
@@ -646,7 +673,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
             HR_TOC(t_stage, tk);
             if (nact > 0) {
                 const char* cur = stage + bi * S::buf_bytes;
-                if (a.l2) nrms[0] = *(const floatx4*)(nstage + (bi * NW + wave) * 64 + g * 4);
+                if (a.l2) nrms[0] = *(const floatx4*)(nstage + bi * kBlockRows + g * 4);
                 const char* const ap[4] = {cur + abase[0], cur + abase[1], cur + abase[2], cur + abase[3]};
                 if (NCS == 2 && nact == 2) mfma_block<DT, KSTEPS, NCS, NCS, S>(ap, bfrag, accs[0]);
                 else                       mfma_block<DT, KSTEPS, NCS, 1, S>(ap, bfrag, accs[0]);
@@ -654,6 +681,33 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
                 select_block(accs[0], nrms[0], row0 + blk * kBlockRows + g * 4);
             }
             bi = bi + 1 == NB ? 0 : bi + 1;
+        };
+        // direct staging, 4 buffers: blocks blk and blk+1 between two barriers, blocks blk+2 and
+        // blk+3 requested into the two buffers the previous pair leaves
+        auto pair_direct = [&](int blk) __attribute__((always_inline)) {
+            wait_vmcnt<0>();
+            __builtin_amdgcn_s_barrier();
+            HR_TOC(t_bar, tk);
+            fill_direct(blk + 2, bi ^ 2);
+            fill_direct(blk + 3, (bi ^ 2) + 1);
+            HR_TOC(t_stage, tk);
+            if (nact > 0) {
+#pragma unroll
+                for (int h = 0; h < 2; h++) {
+                    if (blk + h >= nblk) break;
+#ifdef HR_SCAN_TIMING
+                    n_blocks++;
+#endif
+                    const char* cur = stage + (bi + h) * S::buf_bytes;
+                    if (a.l2) nrms[0] = *(const floatx4*)(nstage + (bi + h) * kBlockRows + g * 4);
+                    const char* const ap[4] = {cur + abase[0], cur + abase[1], cur + abase[2], cur + abase[3]};
+                    if (NCS == 2 && nact == 2) mfma_block<DT, KSTEPS, NCS, NCS, S>(ap, bfrag, accs[0]);
+                    else                       mfma_block<DT, KSTEPS, NCS, 1, S>(ap, bfrag, accs[0]);
+                    HR_TOC(t_mfma, tk);
+                    select_block(accs[0], nrms[0], row0 + (blk + h) * kBlockRows + g * 4);
+                }
+            }
+            bi ^= 2;
         };
         // through registers: (1) barrier: block blk is complete in LDS and nobody reads block
         // blk-1 any more, (2) block blk+1 from the ring into the buffer that one leaves, and
@@ -684,7 +738,11 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
             bi ^= 1;
         };
         if constexpr (S::direct) {
-            for (int blk = 0; blk < nblk; blk++) step_direct(blk);
+            if (pairs) {
+                for (int blk = 0; blk < nblk; blk += 2) pair_direct(blk);
+            } else {
+                for (int blk = 0; blk < nblk; blk++) step_direct(blk);
+            }
         } else {
             // (iterations past the last block of a ragged round still stage and load: an early
             // exit would be a path with fewer loads in flight, and the compiler would size
@@ -726,13 +784,75 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
                 bool v = __shfl(col_ok[s] ? 1 : 0, (lane - s * NC) & 63) != 0;
                 if (lane >= s * NC && lane < (s + 1) * NC) ok = v;
             }
+            const int n = min(c, a.k);
             if (lane < WC && ok) {
-                const int n = min(c, a.k);
                 const size_t slot = (size_t)item * S::cw + wave * WC + lane;
                 a.slot_cnt[slot] = n;
                 const Cand* cb = mysel + lane * a.cap;
                 Cand* out = a.slot_ent + slot * a.k;
                 for (int i = 0; i < n; i++) out[i] = cb[i];
+            }
+            // ---- what this item found tightens the lower bounds of its queries for the items
+            // still to come.  Every query has a histogram of the keys reported so far over
+            // fixed key ranges above its seed; each reported key is a distinct row (an item
+            // owns its rows), so "k keys in the bins from b up" proves that the k-th best of
+            // the query is at least the lower edge of bin b.  Counts only grow, so a reader
+            // that misses concurrent additions merely gets a weaker bound.
+            if (a.hist != nullptr) {
+                int qcol = 0;
+#pragma unroll
+                for (int s = 0; s < NCS; s++) {
+                    const int v = __shfl(q[s], (lane - s * NC) & 63);
+                    if (lane >= s * NC && lane < (s + 1) * NC) qcol = v;
+                }
+                const bool have = lane < WC && ok && n > 0;
+                float base = 0.f, wd = 0.f;
+                uint32_t now = 0;
+                if (have) {
+                    base = a.hpar[2 * (size_t)qcol];
+                    wd = a.hpar[2 * (size_t)qcol + 1];
+                    // keys under the bound other items have reached meanwhile cannot raise it
+                    now = __hip_atomic_load(&a.thr[qcol], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+                int added = 0;
+                if (have && wd > 0.f) {
+                    const Cand* cb = mysel + lane * a.cap;
+                    const float inv = 1.0f / wd;
+                    for (int i = 0; i < n; i++) {
+                        if (cb[i].key < now) continue;
+                        const float key = dec_key(cb[i].key);
+                        int b = (int)fminf(fmaxf((key - base) * inv, 0.f), (float)(kHistBins - 1));
+                        if (hist_edge(base, wd, b) > key) b--;
+                        else if (b < kHistBins - 1 && hist_edge(base, wd, b + 1) <= key) b++;
+                        // (the returned value is used so that the additions have been performed
+                        // before the counts are read back below)
+                        if (b >= 0) added += atomicAdd(&a.hist[(size_t)qcol * kHistBins + b], 1) >= 0 ? 1 : 0;
+                    }
+                }
+                const unsigned long long todo = __builtin_amdgcn_ballot_w64(added > 0);
+                // lane i looks at bin 63 - i: the prefix sum over lanes then counts the keys
+                // from the top bin down (all columns' loads go out before the first is used)
+                int h[WC];
+#pragma unroll
+                for (int cl = 0; cl < WC; cl++) {
+                    const int qc = __builtin_amdgcn_readlane(qcol, cl);
+                    h[cl] = 0;
+                    if ((todo >> cl) & 1)
+                        h[cl] = __hip_atomic_load(&a.hist[(size_t)qc * kHistBins + (kHistBins - 1 - lane)], __ATOMIC_RELAXED,
+                                                  __HIP_MEMORY_SCOPE_AGENT);
+                }
+#pragma unroll
+                for (int cl = 0; cl < WC; cl++) {
+                    if (!((todo >> cl) & 1)) continue;
+                    const unsigned long long reach = __builtin_amdgcn_ballot_w64(wave_prefix_sum(h[cl]) >= a.k);
+                    if (reach) {
+                        const int b = kHistBins - 1 - __builtin_ctzll(reach);
+                        const int qc = __builtin_amdgcn_readlane(qcol, cl);
+                        const float cb0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, base), cl));
+                        const float cw0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wd), cl));
+                        if (b > 0 && lane == 0) atomicMax(&a.thr[qc], enc_key(hist_edge(cb0, cw0, b)));
+                    }
+                }
             }
         }
         __syncthreads();
@@ -910,7 +1030,24 @@ __global__ __launch_bounds__(256) void k_seed(SeedArgs a)
         }
     }
     // a few units in the last place lower, in case a later pass rounds a sum differently
-    if (lane == 0) atomicMax(&a.thr[q], kth > 8u ? kth - 8u : 0u);
+    const uint32_t pub = kth > 8u ? kth - 8u : 0u;
+    if (lane == 0) atomicMax(&a.thr[q], pub);
+    // key ranges of the query's histogram in the scan: from the seed upwards, an eighth of
+    // the distance between the seed and the best key of the sample per bin
+    if (a.hpar != nullptr) {
+        uint32_t mx = 0;
+#pragma unroll
+        for (int m = 0; m < 3; m++) mx = max(mx, e[m]);
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) mx = max(mx, (uint32_t)__shfl_xor((int)mx, o));
+        if (lane == 0) {
+            const float base = dec_key(pub);
+            const float wd = (dec_key(mx) - base) * 0.125f;
+            const bool fine = wd > 0.f && wd < 3.0e38f && base > -3.0e38f;
+            a.hpar[2 * q] = fine ? base : 0.f;
+            a.hpar[2 * q + 1] = fine ? wd : 0.f;
+        }
+    }
 }
 
 template <int DT>
