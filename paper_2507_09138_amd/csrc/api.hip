@@ -147,6 +147,8 @@ struct Plan {
     size_t o_qop_c, o_qnorm_c, o_qop_s, o_qnorm_s;
     size_t o_probe;
     size_t o_pair_entry, o_bucket_off, o_bucket_q, o_item_base, o_item_tab, o_xq;
+    size_t o_ckeys;                 // coarse step: [cchunk, nlist] keys of one chunk of queries
+    int64_t cchunk;                 // queries per coarse chunk
     size_t o_slot_cnt, o_slot_ent;
     size_t total;
 };
@@ -155,12 +157,18 @@ static Plan make_plan(const hr_ivf_index* ix, int64_t nq, int nprobe, int k)
 {
     Plan p{};
     const int64_t nlist = ix->nlist;
-    const int kk = k > nprobe ? k : nprobe;      // slots are shared by the two scans
-    const ScanPick pc = pick_shape(HR_F32, ix->d, nprobe), ps = pick_shape(ix->dtype, ix->d, k);
-    p.shape_c = pc.shape; p.nbuf_c = pc.nbuf; p.cap_c = pc.cap;
+    // coarse step: dense scoring (no selection buffers in LDS) in the widest shape that fits
+    const ScanPick ps = pick_shape(ix->dtype, ix->d, k);
+    p.shape_c = -1; p.nbuf_c = 2; p.cap_c = 0;
+    for (int shape : {SCAN_WIDE, SCAN_NARROW})
+        if (p.shape_c < 0 && scan_lds_bytes(HR_F32, ix->d, 0, shape, 2) <= (size_t)kLdsLimit) p.shape_c = shape;
     p.shape_s = ps.shape; p.nbuf_s = ps.nbuf; p.cap_s = ps.cap;
     p.cw_c = cols_per_set(HR_F32) * shape_sets(p.shape_c < 0 ? 0 : p.shape_c);
-    p.nqt_c = (int)((nq + p.cw_c - 1) / p.cw_c);
+    // queries per coarse chunk: the [chunk, nlist] key table stays within 128 MiB
+    p.cchunk = (int64_t)(128u << 20) / (nlist * 4) / p.cw_c * p.cw_c;
+    if (p.cchunk < p.cw_c) p.cchunk = p.cw_c;
+    if (p.cchunk > nq) p.cchunk = nq > 0 ? nq : 1;
+    p.nqt_c = (int)((p.cchunk + p.cw_c - 1) / p.cw_c);
     int64_t seg = (nlist * (int64_t)p.nqt_c + 2047) / 2048;
     seg = (seg + 15) & ~15LL;
     if (seg < 32) seg = 32;
@@ -191,10 +199,10 @@ static Plan make_plan(const hr_ivf_index* ix, int64_t nq, int nprobe, int k)
     p.o_item_base = take((size_t)(nlist + 1) * 4);
     p.o_item_tab = take((size_t)p.item_cap * sizeof(int4));
     p.o_xq = take((size_t)p.item_cap * 8 * 4);
-    size_t slots_c = (size_t)p.items_c * p.cw_c, slots_s = (size_t)p.item_cap * p.cw_s;
-    size_t slots = slots_c > slots_s ? slots_c : slots_s;
+    p.o_ckeys = take((size_t)p.cchunk * nlist * 4);
+    const size_t slots = (size_t)p.item_cap * p.cw_s;
     p.o_slot_cnt = take(slots * 4);
-    p.o_slot_ent = take(slots * (size_t)kk * sizeof(Cand));
+    p.o_slot_ent = take(slots * (size_t)k * sizeof(Cand));
     p.total = o;
     return p;
 }
@@ -375,42 +383,41 @@ static int enqueue_clear(const Plan& p, char* ws, int64_t nq, hipStream_t s)
     return HR_OK;
 }
 
-// coarse scoring + top-nprobe: the scan kernel over the centroid table, then the merge
+// coarse scoring + top-nprobe: the scan kernel over the centroid table writes every key of a
+// chunk of queries, then one wave per query picks the nprobe best
 static int enqueue_coarse(const hr_ivf_index* ix, const Plan& p, char* ws, int64_t nq, int nprobe,
                           int metric, int32_t* out_probe, float* out_scores, hipStream_t s)
 {
     if (p.shape_c < 0)
-        return fail(HR_ERR_UNSUPPORTED, "coarse step does not fit in LDS (d=%d, nprobe=%d)", ix->d, nprobe);
-    const size_t lds = scan_lds_bytes(HR_F32, ix->d, p.cap_c, p.shape_c, p.nbuf_c);
+        return fail(HR_ERR_UNSUPPORTED, "coarse step does not fit in LDS (d=%d)", ix->d);
+    const size_t lds = scan_lds_bytes(HR_F32, ix->d, 0, p.shape_c, 2);
     int* zero = (int*)(ws + p.o_zero);
-    ScanArgs a{};
-    a.rows = ix->centroids;
-    a.row_norm = ix->d_cent_norm;
-    a.row_ids = nullptr;
-    a.qop = ws + p.o_qop_c;
-    a.thr = (uint32_t*)(ws + p.o_thr);
-    a.slot_cnt = (int*)(ws + p.o_slot_cnt);
-    a.slot_ent = (Cand*)(ws + p.o_slot_ent);
-    a.work_counter = zero + ix->nlist + DYN_COUNT;
-    a.dense = 1;
-    a.dense_items = p.items_c;
-    a.dense_nqt = p.nqt_c;
-    a.dense_seg_rows = p.seg_c;
-    a.dense_nrows = (int)ix->nlist;
-    a.nq = (int)nq; a.k = nprobe; a.cap = p.cap_c; a.l2 = metric == HR_METRIC_L2;
-    a.nbuf = p.nbuf_c;
-    int grid = scan_grid(ix, lds, p.shape_c);
-    if (grid > p.items_c) grid = p.items_c;
-    HR_HIP(launch_scan(HR_F32, ix->d, a, p.shape_c, grid, lds, s));
-    MergeArgs m{};
-    m.slot_cnt = a.slot_cnt; m.slot_ent = a.slot_ent;
-    m.row_ids = nullptr;
-    m.qnorm = (const float*)(ws + p.o_qnorm_c);
-    m.dense = 1; m.dense_nqt = p.nqt_c; m.dense_nseg = p.nseg_c;
-    m.nq = (int)nq; m.nprobe = nprobe; m.nlist = (int)ix->nlist; m.k = nprobe; m.cw = p.cw_c;
-    m.l2 = a.l2;
-    m.out_ids32 = out_probe; m.out_scores = out_scores;
-    HR_HIP(launch_merge(m, s));
+    float* ckeys = (float*)(ws + p.o_ckeys);
+    for (int64_t q0 = 0; q0 < nq; q0 += p.cchunk) {
+        const int64_t n = nq - q0 < p.cchunk ? nq - q0 : p.cchunk;
+        const int nqt = (int)((n + p.cw_c - 1) / p.cw_c);
+        ScanArgs a{};
+        a.rows = ix->centroids;
+        a.row_norm = ix->d_cent_norm;
+        a.qop = ws + p.o_qop_c + (size_t)q0 * 2 * ix->d * 2;
+        a.thr = (uint32_t*)(ws + p.o_thr);
+        a.work_counter = zero + ix->nlist + DYN_COUNT;
+        a.dense = 1;
+        a.dense_items = p.nseg_c * nqt;
+        a.dense_nqt = nqt;
+        a.dense_seg_rows = p.seg_c;
+        a.dense_nrows = (int)ix->nlist;
+        a.key_out = ckeys;
+        a.nq = (int)n; a.k = nprobe; a.cap = 0; a.l2 = metric == HR_METRIC_L2;
+        a.nbuf = 2;
+        if (q0 > 0) HR_HIP(launch_fill_i32(a.work_counter, 1, 0, s));
+        int grid = scan_grid(ix, lds, p.shape_c);
+        if (grid > a.dense_items) grid = a.dense_items;
+        HR_HIP(launch_scan(HR_F32, ix->d, a, p.shape_c, grid, lds, s));
+        HR_HIP(launch_topk_rows(ckeys, (const float*)(ws + p.o_qnorm_c) + q0, out_probe + q0 * nprobe,
+                                out_scores ? out_scores + q0 * nprobe : nullptr, n, (int)ix->nlist, nprobe,
+                                a.l2, s));
+    }
     return HR_OK;
 }
 

@@ -417,6 +417,117 @@ __global__ __launch_bounds__(256) void k_merge(MergeArgs a)
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// Top-k of one row of keys per wave (coarse step: the nprobe best centroids of a query out of
+// the nlist keys the dense scan wrote; Section 2.2: the closest clusters are the ones probed).
+// Exact: radix select on the order-preserving 32-bit image of the key, one 8-bit digit per pass
+// with a 256-bin histogram in LDS, then the entries above the k-th key and, of those equal to
+// it, the ones with the lowest index, ordered best first (equal keys: lower index first).
+struct TopkArgs {
+    const float* keys;          // [nq, n] larger is better
+    const float* qnorm;         // [nq] squared query norms (L2 only)
+    int32_t* out_ids;           // [nq, k]
+    float* out_scores;          // [nq, k] or nullptr
+    int nq, n, k, l2;
+};
+
+__global__ __launch_bounds__(256) void k_topk_rows(TopkArgs a)
+{
+    __shared__ int s_hist[4][256];
+    __shared__ Cand s_ent[4][HR_NPROBE_MAX];
+    const int lane = lane_id(), wave = threadIdx.x >> 6;
+    const int64_t q = (int64_t)blockIdx.x * 4 + wave;
+    if (q >= a.nq) return;
+    const float* row = a.keys + (size_t)q * a.n;
+    int* hist = s_hist[wave];
+    Cand* ent = s_ent[wave];
+    const int k = min(a.k, a.n);
+    uint32_t prefix = 0, mask = 0;
+    int need = k;                                   // entries still to take among those matching the prefix
+    for (int shift = 24; shift >= 0; shift -= 8) {
+#pragma unroll
+        for (int j = 0; j < 4; j++) hist[lane * 4 + j] = 0;
+        wave_sync();
+        for (int i = lane; i < a.n; i += 64) {
+            const uint32_t u = enc_key(row[i]);
+            if ((u & mask) == prefix) atomicAdd(&hist[(u >> shift) & 255], 1);
+        }
+        wave_sync();
+        // lane L holds digits 255-4L .. 252-4L: the prefix sum over lanes counts from the top digit down
+        int c[4], tot = 0;
+#pragma unroll
+        for (int j = 0; j < 4; j++) { c[j] = hist[255 - (lane * 4 + j)]; tot += c[j]; }
+        const int incl = wave_prefix_sum(tot);
+        const unsigned long long reach = __builtin_amdgcn_ballot_w64(incl >= need);
+        const int L = __builtin_ctzll(reach);       // (need <= number of matching entries, so some lane reaches it)
+        int digit = 0, above = 0;
+        if (lane == L) {
+            int run = incl - tot;
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                if (run < need && run + c[j] >= need) { digit = 255 - (lane * 4 + j); above = run; }
+                run += c[j];
+            }
+        }
+        digit = __builtin_amdgcn_readlane(digit, L);
+        above = __builtin_amdgcn_readlane(above, L);
+        need -= above;
+        prefix |= (uint32_t)digit << shift;
+        mask |= 255u << shift;
+        wave_sync();
+    }
+    // prefix = k-th best key; `need` of the entries equal to it are taken, lowest index first
+    int n_gt = 0, n_eq = 0;
+    for (int i0 = 0; i0 < a.n; i0 += 64) {
+        const int i = i0 + lane;
+        const uint32_t u = i < a.n ? enc_key(row[i]) : 0u;
+        const bool gt = i < a.n && u > prefix;
+        const bool eq = i < a.n && u == prefix;
+        const unsigned long long mg = __builtin_amdgcn_ballot_w64(gt), me = __builtin_amdgcn_ballot_w64(eq);
+        if (gt) ent[n_gt + lanes_below(mg)] = Cand{u, (uint32_t)i};
+        n_gt += __builtin_popcountll(mg);
+        // the equal ones go to the far end, in index order, until enough are taken
+        const int r = n_eq + lanes_below(me);
+        if (eq && r < need) ent[k - 1 - r] = Cand{u, (uint32_t)i};
+        n_eq += __builtin_popcountll(me);
+    }
+    wave_sync();
+    // order: key descending, index ascending
+    Cand e[2];
+    int pos[2] = {0, 0};
+#pragma unroll
+    for (int m = 0; m < 2; m++) e[m] = lane + 64 * m < k ? ent[lane + 64 * m] : Cand{0u, 0u};
+    for (int i = 0; i < k; i++) {
+        const Cand o = ent[i];
+#pragma unroll
+        for (int m = 0; m < 2; m++) pos[m] += (o.key > e[m].key || (o.key == e[m].key && o.row < e[m].row)) ? 1 : 0;
+    }
+    const float qn = (a.l2 && a.qnorm) ? a.qnorm[q] : 0.f;
+#pragma unroll
+    for (int m = 0; m < 2; m++) {
+        if (lane + 64 * m < k) {
+            const float key = dec_key(e[m].key);
+            const size_t o = (size_t)q * a.k + pos[m];
+            a.out_ids[o] = (int32_t)e[m].row;
+            if (a.out_scores) a.out_scores[o] = a.l2 ? fmaxf(qn - key, 0.f) : key;
+        }
+    }
+    for (int idx = k + lane; idx < a.k; idx += 64) {       // fewer than k rows: pad
+        const size_t o = (size_t)q * a.k + idx;
+        a.out_ids[o] = -1;
+        if (a.out_scores) a.out_scores[o] = a.l2 ? __builtin_inff() : -__builtin_inff();
+    }
+}
+
+hipError_t launch_topk_rows(const float* keys, const float* qnorm, int32_t* out_ids, float* out_scores,
+                            int64_t nq, int n, int k, int l2, hipStream_t s)
+{
+    if (nq <= 0) return hipSuccess;
+    TopkArgs a{keys, qnorm, out_ids, out_scores, (int)nq, n, k, l2};
+    hipLaunchKernelGGL(k_topk_rows, dim3((unsigned)((nq + 3) / 4)), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
 hipError_t launch_merge(const MergeArgs& a, hipStream_t s)
 {
     if (a.nq <= 0) return hipSuccess;

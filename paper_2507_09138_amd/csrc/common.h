@@ -104,6 +104,7 @@ struct ScanArgs {
     int dense, dense_items, dense_nqt, dense_seg_rows, dense_nrows;
     int nq, k, cap, l2;
     int nbuf;                   // staging buffers in LDS (16-bit storage; float32 always uses 2)
+    float* key_out;             // dense mode: [nq, dense_nrows] every key is written here and nothing is selected
     int* hist;                  // [nq][kHistBins] keys found so far per query, by key range (or nullptr)
     const float* hpar;          // [nq][2] lower edge of bin 0 and bin width (width 0: query has no histogram)
     long long* dbg;             // per-workgroup phase timers (only in HR_SCAN_TIMING builds)
@@ -148,6 +149,8 @@ struct MergeArgs {
 hipError_t launch_scan(int dtype, int d, const ScanArgs& a, int shape, int grid, size_t lds_bytes, hipStream_t s);
 size_t scan_lds_bytes(int dtype, int d, int cap, int shape, int nbuf);
 hipError_t launch_merge(const MergeArgs& a, hipStream_t s);
+hipError_t launch_topk_rows(const float* keys, const float* qnorm, int32_t* out_ids, float* out_scores,
+                            int64_t nq, int n, int k, int l2, hipStream_t s);
 hipError_t launch_seed(int dtype, int d, const SeedArgs& a, hipStream_t s);
 hipError_t launch_row_norms(const void* rows, int dtype, int64_t nrows, int d, float* out, hipStream_t s);
 hipError_t launch_prep_queries(const float* q, int64_t nq, int d, int dtype, void* qop_coarse,

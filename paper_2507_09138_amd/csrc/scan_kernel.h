@@ -604,6 +604,16 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
 #pragma unroll
                     for (int r = 0; r < 4; r++) key[r] = 2.0f * key[r] - nrm[r];
                 }
+                if (a.key_out != nullptr) {
+                    // dense scoring only: every key goes to its place in the [query, row] table
+                    if (owner && col_ok[s]) {
+                        float* out = a.key_out + (size_t)q[s] * a.dense_nrows + rbase;
+#pragma unroll
+                        for (int r = 0; r < 4; r++)
+                            if (rbase + r < row_end) out[r] = key[r];
+                    }
+                    continue;
+                }
                 const float best = fmaxf(fmaxf(key[0], key[1]), fmaxf(key[2], key[3]));
                 // ---- append what reaches the column's threshold
                 if (__builtin_amdgcn_ballot_w64(best >= thr[s]) != 0) {
@@ -754,7 +764,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
         // ---- hand what is left to the item's slots: columns still over k are cut down first
         // (one at a time, whole wave), then every lane copies one column's entries
         wave_sync();
-        {
+        if (a.key_out == nullptr) {
             int c = 0;
 #pragma unroll
             for (int s = 0; s < NCS; s++) {
