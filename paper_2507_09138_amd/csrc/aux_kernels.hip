@@ -448,9 +448,17 @@ __global__ __launch_bounds__(256) void k_topk_rows(TopkArgs a)
 #pragma unroll
         for (int j = 0; j < 4; j++) hist[lane * 4 + j] = 0;
         wave_sync();
-        for (int i = lane; i < a.n; i += 64) {
-            const uint32_t u = enc_key(row[i]);
-            if ((u & mask) == prefix) atomicAdd(&hist[(u >> shift) & 255], 1);
+        // (8 loads in flight per lane: the row is read once per pass and nothing else hides
+        // the latency of a load)
+        for (int i0 = 0; i0 < a.n; i0 += 64 * 8) {
+            float v[8];
+#pragma unroll
+            for (int j = 0; j < 8; j++) { const int i = i0 + j * 64 + lane; v[j] = row[min(i, a.n - 1)]; }
+#pragma unroll
+            for (int j = 0; j < 8; j++) {
+                const uint32_t u = enc_key(v[j]);
+                if (i0 + j * 64 + lane < a.n && (u & mask) == prefix) atomicAdd(&hist[(u >> shift) & 255], 1);
+            }
         }
         wave_sync();
         // lane L holds digits 255-4L .. 252-4L: the prefix sum over lanes counts from the top digit down
@@ -478,18 +486,24 @@ __global__ __launch_bounds__(256) void k_topk_rows(TopkArgs a)
     }
     // prefix = k-th best key; `need` of the entries equal to it are taken, lowest index first
     int n_gt = 0, n_eq = 0;
-    for (int i0 = 0; i0 < a.n; i0 += 64) {
-        const int i = i0 + lane;
-        const uint32_t u = i < a.n ? enc_key(row[i]) : 0u;
-        const bool gt = i < a.n && u > prefix;
-        const bool eq = i < a.n && u == prefix;
-        const unsigned long long mg = __builtin_amdgcn_ballot_w64(gt), me = __builtin_amdgcn_ballot_w64(eq);
-        if (gt) ent[n_gt + lanes_below(mg)] = Cand{u, (uint32_t)i};
-        n_gt += __builtin_popcountll(mg);
-        // the equal ones go to the far end, in index order, until enough are taken
-        const int r = n_eq + lanes_below(me);
-        if (eq && r < need) ent[k - 1 - r] = Cand{u, (uint32_t)i};
-        n_eq += __builtin_popcountll(me);
+    for (int i0 = 0; i0 < a.n; i0 += 64 * 8) {
+        float v[8];
+#pragma unroll
+        for (int j = 0; j < 8; j++) { const int i = i0 + j * 64 + lane; v[j] = row[min(i, a.n - 1)]; }
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+            const int i = i0 + j * 64 + lane;
+            const uint32_t u = enc_key(v[j]);
+            const bool gt = i < a.n && u > prefix;
+            const bool eq = i < a.n && u == prefix;
+            const unsigned long long mg = __builtin_amdgcn_ballot_w64(gt), me = __builtin_amdgcn_ballot_w64(eq);
+            if (gt) ent[n_gt + lanes_below(mg)] = Cand{u, (uint32_t)i};
+            n_gt += __builtin_popcountll(mg);
+            // the equal ones go to the far end, in index order, until enough are taken
+            const int r = n_eq + lanes_below(me);
+            if (eq && r < need) ent[k - 1 - r] = Cand{u, (uint32_t)i};
+            n_eq += __builtin_popcountll(me);
+        }
     }
     wave_sync();
     // order: key descending, index ascending
