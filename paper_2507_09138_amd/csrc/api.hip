@@ -11,6 +11,7 @@ namespace hr {
 hipError_t launch_scan_f32(int d, const ScanArgs& a, int shape, int grid, size_t lds, hipStream_t s);
 hipError_t launch_scan_f16(int d, const ScanArgs& a, int shape, int grid, size_t lds, hipStream_t s);
 hipError_t launch_scan_bf16(int d, const ScanArgs& a, int shape, int grid, size_t lds, hipStream_t s);
+hipError_t launch_scan_f16x2(int d, const ScanArgs& a, int shape, int grid, size_t lds, hipStream_t s);
 
 hipError_t launch_seed_f32(int d, const SeedArgs& a, hipStream_t s);
 hipError_t launch_seed_f16(int d, const SeedArgs& a, hipStream_t s);
@@ -32,6 +33,7 @@ hipError_t launch_scan(int dtype, int d, const ScanArgs& a, int shape, int grid,
     case HR_F32: return launch_scan_f32(d, a, shape, grid, lds, s);
     case HR_F16: return launch_scan_f16(d, a, shape, grid, lds, s);
     case HR_BF16: return launch_scan_bf16(d, a, shape, grid, lds, s);
+    case HR_F16X2: return launch_scan_f16x2(d, a, shape, grid, lds, s);
     default: return hipErrorInvalidValue;
     }
 }
@@ -45,6 +47,9 @@ size_t scan_lds_bytes(int dtype, int d, int cap, int shape, int nbuf)
     size_t buf;
     if (dtype == HR_F32) {
         buf = (size_t)kBlockRows * (d * 2 + kRowPad) * 2;
+    } else if (dtype == HR_F16X2) {
+        const int chunks = kBlockRows * d * 2 / 16, threads = nw * 64;
+        buf = (size_t)((chunks + threads - 1) / threads) * threads * 16 * 2;
     } else {
         const int chunks = kBlockRows * d * 2 / 16, threads = nw * 64;
         buf = (size_t)((chunks + threads - 1) / threads) * threads * 16;
@@ -121,6 +126,8 @@ struct hr_ivf_index {
     int* d_list_off;       // [nlist+1] int32
     float* d_row_norm;     // [N]
     float* d_cent_norm;    // [nlist]
+    void* d_cent_hi;       // [nlist, d] binary16: centroids rounded
+    void* d_cent_lo;       // [nlist, d] binary16: (centroid - hi) * 2^11
     int num_cus;
     int lds_limit;
     // optional kernel timing (hr_ivf_profile_begin/end)
@@ -159,9 +166,9 @@ static Plan make_plan(const hr_ivf_index* ix, int64_t nq, int nprobe, int k)
     const int64_t nlist = ix->nlist;
     // coarse step: dense scoring (no selection buffers in LDS) in the widest shape that fits
     const ScanPick ps = pick_shape(ix->dtype, ix->d, k);
-    p.shape_c = -1; p.nbuf_c = 2; p.cap_c = 0;
-    for (int shape : {SCAN_WIDE, SCAN_NARROW})
-        if (p.shape_c < 0 && scan_lds_bytes(HR_F32, ix->d, 0, shape, 2) <= (size_t)kLdsLimit) p.shape_c = shape;
+    p.shape_c = -1; p.nbuf_c = 0; p.cap_c = 0;
+    for (int nbuf = 3; nbuf >= 2 && p.shape_c < 0; nbuf--)
+        if (scan_lds_bytes(HR_F16X2, ix->d, 0, SCAN_WIDE, nbuf) <= (size_t)kLdsLimit) { p.shape_c = SCAN_WIDE; p.nbuf_c = nbuf; }
     p.shape_s = ps.shape; p.nbuf_s = ps.nbuf; p.cap_s = ps.cap;
     p.cw_c = cols_per_set(HR_F32) * shape_sets(p.shape_c < 0 ? 0 : p.shape_c);
     // queries per coarse chunk: the [chunk, nlist] key table stays within 128 MiB
@@ -278,15 +285,20 @@ int hr_ivf_load(const float* centroids, const int64_t* list_offsets, const void*
     if (e == hipSuccess) e = hipMalloc(&ix->d_list_off, (size_t)(nlist + 1) * 4);
     if (e == hipSuccess) e = hipMalloc(&ix->d_row_norm, (size_t)(N > 0 ? N : 1) * 4);
     if (e == hipSuccess) e = hipMalloc(&ix->d_cent_norm, (size_t)nlist * 4);
+    if (e == hipSuccess) e = hipMalloc(&ix->d_cent_hi, (size_t)nlist * d * 2);
+    if (e == hipSuccess) e = hipMalloc(&ix->d_cent_lo, (size_t)nlist * d * 2);
     if (e == hipSuccess) e = hipMemcpyAsync(ix->d_list_off, h_off, (size_t)(nlist + 1) * 4, hipMemcpyHostToDevice, s);
     if (e == hipSuccess) e = launch_row_norms(list_vectors, dtype, N, d, ix->d_row_norm, s);
     if (e == hipSuccess) e = launch_row_norms(centroids, HR_F32, nlist, d, ix->d_cent_norm, s);
+    if (e == hipSuccess) e = launch_split_f32(centroids, nlist * d, ix->d_cent_hi, ix->d_cent_lo, s);
     if (e == hipSuccess) e = hipStreamSynchronize(s);
     delete[] h_off;
     if (e != hipSuccess) {
         if (ix->d_list_off) (void)hipFree(ix->d_list_off);
         if (ix->d_row_norm) (void)hipFree(ix->d_row_norm);
         if (ix->d_cent_norm) (void)hipFree(ix->d_cent_norm);
+        if (ix->d_cent_hi) (void)hipFree(ix->d_cent_hi);
+        if (ix->d_cent_lo) (void)hipFree(ix->d_cent_lo);
         delete ix;
         return fail(HR_ERR_HIP, "hr_ivf_load: %s", hipGetErrorString(e));
     }
@@ -348,6 +360,8 @@ int hr_ivf_free(hr_ivf_index* ix)
     (void)hipFree(ix->d_list_off);
     (void)hipFree(ix->d_row_norm);
     (void)hipFree(ix->d_cent_norm);
+    (void)hipFree(ix->d_cent_hi);
+    (void)hipFree(ix->d_cent_lo);
     delete ix;
     return HR_OK;
 }
@@ -390,14 +404,15 @@ static int enqueue_coarse(const hr_ivf_index* ix, const Plan& p, char* ws, int64
 {
     if (p.shape_c < 0)
         return fail(HR_ERR_UNSUPPORTED, "coarse step does not fit in LDS (d=%d)", ix->d);
-    const size_t lds = scan_lds_bytes(HR_F32, ix->d, 0, p.shape_c, 2);
+    const size_t lds = scan_lds_bytes(HR_F16X2, ix->d, 0, p.shape_c, p.nbuf_c);
     int* zero = (int*)(ws + p.o_zero);
     float* ckeys = (float*)(ws + p.o_ckeys);
     for (int64_t q0 = 0; q0 < nq; q0 += p.cchunk) {
         const int64_t n = nq - q0 < p.cchunk ? nq - q0 : p.cchunk;
         const int nqt = (int)((n + p.cw_c - 1) / p.cw_c);
         ScanArgs a{};
-        a.rows = ix->centroids;
+        a.rows = ix->d_cent_hi;
+        a.rows_lo = ix->d_cent_lo;
         a.row_norm = ix->d_cent_norm;
         a.qop = ws + p.o_qop_c + (size_t)q0 * 2 * ix->d * 2;
         a.thr = (uint32_t*)(ws + p.o_thr);
@@ -409,11 +424,11 @@ static int enqueue_coarse(const hr_ivf_index* ix, const Plan& p, char* ws, int64
         a.dense_nrows = (int)ix->nlist;
         a.key_out = ckeys;
         a.nq = (int)n; a.k = nprobe; a.cap = 0; a.l2 = metric == HR_METRIC_L2;
-        a.nbuf = 2;
+        a.nbuf = p.nbuf_c;
         if (q0 > 0) HR_HIP(launch_fill_i32(a.work_counter, 1, 0, s));
         int grid = scan_grid(ix, lds, p.shape_c);
         if (grid > a.dense_items) grid = a.dense_items;
-        HR_HIP(launch_scan(HR_F32, ix->d, a, p.shape_c, grid, lds, s));
+        HR_HIP(launch_scan(HR_F16X2, ix->d, a, p.shape_c, grid, lds, s));
         HR_HIP(launch_topk_rows(ckeys, (const float*)(ws + p.o_qnorm_c) + q0, out_probe + q0 * nprobe,
                                 out_scores ? out_scores + q0 * nprobe : nullptr, n, (int)ix->nlist, nprobe,
                                 a.l2, s));

@@ -18,6 +18,24 @@ hipError_t launch_fill_i32(int* p, int64_t n, int v, hipStream_t s)
     return hipGetLastError();
 }
 
+// float32 -> binary16 hi + 2^11-scaled binary16 lo (the split the scan applies to float32 rows)
+__global__ void k_split_f32(const float* x, int64_t n, _Float16* hi, _Float16* lo)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const float v = x[i];
+    const _Float16 h = (_Float16)v;
+    hi[i] = h;
+    lo[i] = (_Float16)((v - (float)h) * 2048.0f);
+}
+
+hipError_t launch_split_f32(const float* x, int64_t n, void* hi, void* lo, hipStream_t s)
+{
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_split_f32, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, x, n, (_Float16*)hi, (_Float16*)lo);
+    return hipGetLastError();
+}
+
 __device__ __forceinline__ float wave_sum(float v)
 {
 #pragma unroll

@@ -8,6 +8,9 @@
 namespace hr {
 
 constexpr int kWave = 64;
+// internal storage code next to HR_F32 / HR_F16 / HR_BF16: float32 rows already split into a
+// binary16 hi table and a 2^11-scaled binary16 lo table (the centroid table, split at load)
+constexpr int HR_F16X2 = 3;
 constexpr int kBlockRows = 16;             // rows per MFMA block (M of 16x16x32)
 constexpr int kRowPad = 32;                // bytes of LDS padding per staged row: measured conflict-free
                                            // for the 16-rows x 16-byte MFMA fragment reads (16 is 2-way)
@@ -82,7 +85,8 @@ struct Cand { uint32_t key; uint32_t row; };
 // Arguments of the scan kernel (both uses: centroid table with all queries as one dense
 // bucket, and the inverted lists with the per-list buckets).
 struct ScanArgs {
-    const void* rows;           // [nrows, d] storage
+    const void* rows;           // [nrows, d] storage (HR_F16X2: the hi table)
+    const void* rows_lo;        // HR_F16X2: the lo table
     const float* row_norm;      // [nrows] squared norms (used when l2 != 0)
     const int64_t* row_ids;     // [nrows] labels, or nullptr: label = row number
     const void* qop;            // query operand rows (layout depends on dtype)
@@ -156,6 +160,7 @@ hipError_t launch_row_norms(const void* rows, int dtype, int64_t nrows, int d, f
 hipError_t launch_prep_queries(const float* q, int64_t nq, int d, int dtype, void* qop_coarse,
                                float* qnorm_coarse, void* qop_scan, float* qnorm_scan, hipStream_t s);
 hipError_t launch_fill_i32(int* p, int64_t n, int v, hipStream_t s);
+hipError_t launch_split_f32(const float* x, int64_t n, void* hi, void* lo, hipStream_t s);
 
 struct BucketArgs {
     const int* probe;           // [nq*nprobe]

@@ -188,6 +188,7 @@ template <int DT> struct StoreTraits;
 template <> struct StoreTraits<HR_F32>  { static constexpr int esize = 4, planes = 2, nc = 8;  };
 template <> struct StoreTraits<HR_F16>  { static constexpr int esize = 2, planes = 1, nc = 16; };
 template <> struct StoreTraits<HR_BF16> { static constexpr int esize = 2, planes = 1, nc = 8;  };
+template <> struct StoreTraits<HR_F16X2> { static constexpr int esize = 2, planes = 2, nc = 8; };
 
 // NW = waves per workgroup (4: one per SIMD, each may use all 512 registers; 8: two per SIMD
 // with 256 registers each, so that one wave's MFMAs run while the other selects or waits).
@@ -211,17 +212,19 @@ struct ScanShape {
     static constexpr int threads = NW * 64;
     static constexpr int d = KSTEPS * 32;
     static constexpr int planes = StoreTraits<DT>::planes;
-    static constexpr bool direct = planes == 1;
+    static constexpr bool direct = DT != HR_F32;                   // (HR_F16X2: two planes, both moved directly)
     static constexpr int rowb = d * StoreTraits<DT>::esize;        // bytes of one stored row
     static constexpr int cpr = rowb / 16;                          // 16-byte chunks per stored row
     static constexpr int swz = (cpr < 16 ? cpr : 16) - 1;          // row bits xor-ed into the chunk position
     static constexpr int rowp = direct ? rowb : d * 2 + kRowPad;   // bytes of one staged row (one plane)
-    static constexpr int plane_bytes = kBlockRows * rowp;
+    static constexpr int plane_bytes_padded = kBlockRows * rowp;
     static constexpr int chunks = kBlockRows * cpr;                // 16-byte chunks per block
     static constexpr int nfw = NW;                                 // waves that move rows: all
     static constexpr int nld = (chunks + nfw * 64 - 1) / (nfw * 64);   // chunks per thread per block
     // (direct: every wave always issues nld loads, so a buffer is a whole number of them)
-    static constexpr int buf_bytes = direct ? nld * nfw * 1024 : plane_bytes * planes;
+    static constexpr int plane_bytes = direct ? nld * nfw * 1024 : plane_bytes_padded;
+    static constexpr int buf_bytes = plane_bytes * planes;
+    static constexpr int lpf = planes * nld + 1;                   // direct: loads per wave per block (chunks + norms)
     // k-steps whose row fragments are fetched from LDS together, ahead of their MFMAs
     static constexpr int grp = scan_group(DT, KSTEPS, NW);
     // register path: row blocks kept in flight in registers ahead of the one being staged
@@ -322,7 +325,7 @@ __device__ __forceinline__ void mfma_block(const char* const (&ap)[4], const u32
             const int t = gi * G + i;
 #pragma unroll
             for (int s = 0; s < NA; s++) {
-                if constexpr (DT == HR_F32) {
+                if constexpr (StoreTraits<DT>::planes == 2) {
                     half8 b = __builtin_bit_cast(half8, bfrag[s][t]);
                     acc[s][0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, af[gi & 1][0][i]), b, acc[s][0], 0, 0, 0);
                     acc[s][1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, af[gi & 1][1][i]), b, acc[s][1], 0, 0, 0);
@@ -460,6 +463,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
         const int nrows = row_end - row0;
         const int nblk = (nrows + kBlockRows - 1) / kBlockRows;
         const char* src = (const char*)a.rows + (size_t)row0 * S::rowb;
+        const char* src_lo = S::planes == 2 ? (const char*)a.rows_lo + (size_t)row0 * S::rowb : src;
 
         // ---- staging.  Requests for a block past the end of the segment fetch its last block
         // again (nobody reads the copy): every wave then has the same, fixed number of loads
@@ -471,20 +475,23 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
             if (a.dbg_flags & 16) return;      // experiment: compute on whatever is in LDS
             const int bl = (a.dbg_flags & 64) ? 0 : min(blk, nblk - 1);      // experiment 64: always the first block (L2 hits)
             const int valid = min(nrows - bl * kBlockRows, kBlockRows);
-            const char* bsrc = src + (size_t)bl * kBlockRows * S::rowb;
-            const uint32_t dst = lds_addr(stage) + buf * S::buf_bytes + wave * 1024;
-            if (valid == kBlockRows) {
 #pragma unroll
-                for (int m = 0; m < NLD; m++) lds_dma16(bsrc, goff[m], dst + m * S::nfw * 1024);
-            } else {
-                // ragged last block: rows past the end repeat the last valid one (their scores
-                // are masked out of the selection)
+            for (int pl = 0; pl < S::planes; pl++) {
+                const char* bsrc = (pl == 0 ? src : src_lo) + (size_t)bl * kBlockRows * S::rowb;
+                const uint32_t dst = lds_addr(stage) + buf * S::buf_bytes + pl * S::plane_bytes + wave * 1024;
+                if (valid == kBlockRows) {
 #pragma unroll
-                for (int m = 0; m < NLD; m++) {
-                    const int L = (m * S::nfw + wave) * 64 + lane;
-                    const int r = L / S::cpr, pos = L % S::cpr;
-                    const uint32_t o = (uint32_t)(min(r, valid - 1) * S::cpr + (pos ^ (r & S::swz))) * 16u;
-                    lds_dma16(bsrc, o, dst + m * S::nfw * 1024);
+                    for (int m = 0; m < NLD; m++) lds_dma16(bsrc, goff[m], dst + m * S::nfw * 1024);
+                } else {
+                    // ragged last block: rows past the end repeat the last valid one (their scores
+                    // are masked out of the selection)
+#pragma unroll
+                    for (int m = 0; m < NLD; m++) {
+                        const int L = (m * S::nfw + wave) * 64 + lane;
+                        const int r = L / S::cpr, pos = L % S::cpr;
+                        const uint32_t o = (uint32_t)(min(r, valid - 1) * S::cpr + (pos ^ (r & S::swz))) * 16u;
+                        lds_dma16(bsrc, o, dst + m * S::nfw * 1024);
+                    }
                 }
             }
             // (every wave writes the same 16 norms: the same number of loads per wave)
@@ -588,7 +595,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
 #pragma unroll
                 for (int r = 0; r < 4; r++) {
                     float dot;
-                    if constexpr (DT == HR_F32) {
+                    if constexpr (T::planes == 2) {
                         float t0 = __shfl_xor(acc[s][0][r], 8);       // hi rows x lo query
                         float t1 = __shfl_xor(acc[s][1][r], 8);       // lo rows x lo query
                         dot = acc[s][0][r] + (t0 + acc[s][1][r]) * (1.0f / 2048.0f) + t1 * (1.0f / 4194304.0f);
@@ -667,12 +674,12 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
         // everybody's, and nobody reads block blk-1 any more, (3) request block blk+D into the
         // buffer that one leaves, (4) multiply, (5) select
         auto step_direct = [&](int blk) __attribute__((always_inline)) {
-            // all but the D-1 youngest requests of this wave (NLD + 1 loads each) are done
+            // all but the D-1 youngest requests of this wave (S::lpf loads each) are done
             switch (D) {
             case 1: wait_vmcnt<0>(); break;
-            case 2: wait_vmcnt<NLD + 1>(); break;
-            case 3: wait_vmcnt<2 * (NLD + 1)>(); break;
-            default: wait_vmcnt<3 * (NLD + 1)>(); break;
+            case 2: wait_vmcnt<S::lpf>(); break;
+            case 3: wait_vmcnt<2 * S::lpf>(); break;
+            default: wait_vmcnt<3 * S::lpf>(); break;
             }
             __builtin_amdgcn_s_barrier();
             HR_TOC(t_bar, tk);
@@ -907,6 +914,7 @@ inline hipError_t launch_scan_shape(int d, const ScanArgs& a, int grid, size_t l
 template <int DT>
 inline hipError_t launch_scan_dtype(int d, const ScanArgs& a, int shape, int grid, size_t lds, hipStream_t s)
 {
+    if constexpr (DT == HR_F16X2) return launch_scan_shape<DT, 1, 8>(d, a, grid, lds, s);     // (coarse step only)
     switch (shape) {
     case SCAN_WIDE: return launch_scan_shape<DT, 1, 8>(d, a, grid, lds, s);
     case SCAN_WIDE4: return launch_scan_shape<DT, 2, 4>(d, a, grid, lds, s);
