@@ -176,7 +176,7 @@ static Plan make_plan(const hr_ivf_index* ix, int64_t nq, int nprobe, int k)
     if (p.cchunk < p.cw_c) p.cchunk = p.cw_c;
     if (p.cchunk > nq) p.cchunk = nq > 0 ? nq : 1;
     p.nqt_c = (int)((p.cchunk + p.cw_c - 1) / p.cw_c);
-    int64_t seg = (nlist * (int64_t)p.nqt_c + 2047) / 2048;
+    int64_t seg = (nlist * (int64_t)p.nqt_c + 511) / 512;
     seg = (seg + 15) & ~15LL;
     if (seg < 32) seg = 32;
     if (seg > 1024) seg = 1024;

@@ -582,6 +582,30 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
         // block any more, (3) request block blk + D into the buffer the previous block leaves,
         // (4) multiply, (5) select.
         //
+        // ---- dense scoring: the keys of a block are written out at the start of the next
+        // step, right after the barrier.  Stores count in vmcnt like the requests for blocks,
+        // and may complete in any order relative to them, so the wait at the top of a step has
+        // to assume they are still outstanding; issued here they have a whole step to complete.
+        floatx4 held[NCS];
+        int held_rbase = -1;
+        auto flush_keys = [&]() __attribute__((always_inline)) {
+            if (held_rbase < 0) return;
+#pragma unroll
+            for (int s = 0; s < NCS; s++) {
+                if (s < nact && owner && col_ok[s]) {
+                    float* out = a.key_out + (size_t)q[s] * a.dense_nrows + held_rbase;
+                    if (held_rbase + 3 < row_end && (a.dense_nrows & 3) == 0) {
+                        *(floatx4*)out = held[s];
+                    } else {
+#pragma unroll
+                        for (int r = 0; r < 4; r++)
+                            if (held_rbase + r < row_end) out[r] = held[s][r];
+                    }
+                }
+            }
+            held_rbase = -1;
+        };
+
         // ---- selection over the scores of one block: acc = accumulators of the block, nrm =
         // squared norms of this lane's 4 rows, rbase = first of those rows
         auto select_block = [&](const floatx4 (&acc)[NCS][kAcc], const floatx4 nrm, const int rbase) __attribute__((always_inline)) {
@@ -612,13 +636,10 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
                     for (int r = 0; r < 4; r++) key[r] = 2.0f * key[r] - nrm[r];
                 }
                 if (a.key_out != nullptr) {
-                    // dense scoring only: every key goes to its place in the [query, row] table
-                    if (owner && col_ok[s]) {
-                        float* out = a.key_out + (size_t)q[s] * a.dense_nrows + rbase;
-#pragma unroll
-                        for (int r = 0; r < 4; r++)
-                            if (rbase + r < row_end) out[r] = key[r];
-                    }
+                    // dense scoring only: every key goes to its place in the [query, row] table,
+                    // one block late (see flush_keys)
+                    held[s] = floatx4{key[0], key[1], key[2], key[3]};
+                    held_rbase = rbase;
                     continue;
                 }
                 const float best = fmaxf(fmaxf(key[0], key[1]), fmaxf(key[2], key[3]));
@@ -686,6 +707,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
 #ifdef HR_SCAN_TIMING
             n_blocks++;
 #endif
+            if (a.key_out != nullptr) flush_keys();
             fill_direct(blk + D, bi == 0 ? NB - 1 : bi - 1);
             HR_TOC(t_stage, tk);
             if (nact > 0) {
@@ -768,6 +790,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
                 static_for<PF>([&](auto pc) __attribute__((always_inline)) { step_regs(b0 + decltype(pc)::value, pc); });
         }
 
+        if (a.key_out != nullptr) flush_keys();
         // ---- hand what is left to the item's slots: columns still over k are cut down first
         // (one at a time, whole wave), then every lane copies one column's entries
         wave_sync();
