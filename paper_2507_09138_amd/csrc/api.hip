@@ -149,7 +149,7 @@ struct Plan {
     // list scan
     int shape_s, nbuf_s, cap_s, cw_s, item_cap;
     size_t o_zero, n_zero;          // ints cleared per call: list_w[nlist], dyn[DYN_COUNT], counters[8], ..., then
-    size_t zoff_hist, zoff_hpar;    // (in ints from o_zero) per-query key histograms and their parameters
+    size_t zoff_round, zoff_hist, zoff_hpar;   // (in ints from o_zero) round counters of the queues, per-query key histograms and their parameters
     size_t o_thr;                   // 2*nq ints set to "-inf"
     size_t o_qop_c, o_qnorm_c, o_qop_s, o_qnorm_s;
     size_t o_probe;
@@ -189,7 +189,8 @@ static Plan make_plan(const hr_ivf_index* ix, int64_t nq, int nprobe, int k)
 
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
-    p.zoff_hist = (size_t)nlist + DYN_COUNT + 24;   // + 8 counters, 8 queue lengths, 8 queue heads
+    p.zoff_round = (size_t)nlist + DYN_COUNT + 24;  // + 8 counters, 8 queue lengths, 8 queue heads
+    p.zoff_hist = p.zoff_round + 2 * 8 * 64;
     p.zoff_hpar = p.zoff_hist + (size_t)nq * kHistBins;
     p.n_zero = p.zoff_hpar + (size_t)nq * 2;
     p.o_zero = take(p.n_zero * 4);
@@ -456,6 +457,8 @@ static int enqueue_scan(const hr_ivf_index* ix, const Plan& p, char* ws, int64_t
     b.dyn = zero + ix->nlist;
     b.xq = (int*)(ws + p.o_xq);
     b.xq_count = zero + ix->nlist + DYN_COUNT + 8;
+    b.round_cnt = zero + p.zoff_round;
+    b.round_cur = zero + p.zoff_round + 8 * 64;
     b.item_cap = p.item_cap;
     HR_HIP(launch_bucketing(b, s));
 

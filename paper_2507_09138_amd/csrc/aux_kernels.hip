@@ -148,18 +148,49 @@ __global__ void k_bucket_count(BucketArgs a)
     a.pair_entry[i] = (l >= 0 && l < a.nlist) ? atomicAdd(&a.list_w[l], 1) : -1;
 }
 
-// One workgroup: bucket offsets, rows per segment for this batch, first work item of every list.
+// Exclusive prefix sum over the 1024 threads of a workgroup (16 waves); total returned to all.
+__device__ __forceinline__ int block_scan_1024(int v, int* s_wave /* [17] */, int& total)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int incl = wave_prefix_sum(v);
+    __syncthreads();                                   // (s_wave may still be read from the last call)
+    if (lane == 63) s_wave[wave] = incl;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int run = 0;
+        for (int i = 0; i < 16; i++) { int x = s_wave[i]; s_wave[i] = run; run += x; }
+        s_wave[16] = run;
+    }
+    __syncthreads();
+    total = s_wave[16];
+    return s_wave[wave] + incl - v;
+}
+
+__device__ __forceinline__ long long block_sum_1024(long long v, long long* s_wave /* [16] */)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) s_wave[threadIdx.x >> 6] = v;
+    __syncthreads();
+    long long t = 0;
+    for (int i = 0; i < 16; i++) t += s_wave[i];
+    return t;
+}
+
+// One workgroup: bucket offsets, rows per segment for this batch, first work item of every
+// list.
 __global__ __launch_bounds__(1024) void k_bucket_scan(BucketArgs a)
 {
-    __shared__ long long part[1024];
-    __shared__ long long s_total;
-    __shared__ int s_seg;
+    __shared__ int s_wave[17];
+    __shared__ long long s_lwave[16];
     const int t = threadIdx.x;
     const int per = (a.nlist + 1023) / 1024;
     const int l0 = min(a.nlist, t * per), l1 = min(a.nlist, l0 + per);
 
     // pass 1: bucket offsets, cost = sum rows * query tiles, rows streamed, pairs
-    long long w_sum = 0, cost = 0, rows = 0;
+    int w_sum = 0;
+    long long cost = 0, rows = 0;
     for (int l = l0; l < l1; l++) {
         int w = a.list_w[l];
         long long len = a.list_off[l + 1] - a.list_off[l];
@@ -167,71 +198,45 @@ __global__ __launch_bounds__(1024) void k_bucket_scan(BucketArgs a)
         cost += len * ((w + a.cw - 1) / a.cw);
         if (w > 0) rows += len;
     }
-    part[t] = w_sum;
-    __syncthreads();
-    if (t == 0) {
-        long long run = 0;
-        for (int i = 0; i < 1024; i++) { long long v = part[i]; part[i] = run; run += v; }
-        s_total = run;
-    }
-    __syncthreads();
+    int total;
     {
-        long long run = part[t];
-        for (int l = l0; l < l1; l++) { a.bucket_off[l] = (int)run; run += a.list_w[l]; }
-        if (t == 0) { a.bucket_off[a.nlist] = (int)s_total; a.dyn[DYN_PAIRS] = (int)s_total; }
+        int run = block_scan_1024(w_sum, s_wave, total);
+        for (int l = l0; l < l1; l++) { a.bucket_off[l] = run; run += a.list_w[l]; }
+        if (t == 0) { a.bucket_off[a.nlist] = total; a.dyn[DYN_PAIRS] = total; }
     }
-    __syncthreads();
-    part[t] = cost;
-    __syncthreads();
+    const long long c = block_sum_1024(cost, s_lwave);
+    long long segll = (c + kItemTarget - 1) / kItemTarget;
+    segll = (segll + 15) & ~15LL;
+    if (segll < kMinSegRows) segll = kMinSegRows;
+    if (segll > (1LL << 30)) segll = 1LL << 30;
+    const int seg = (int)segll;
+    const long long r = block_sum_1024(rows, s_lwave);
     if (t == 0) {
-        long long c = 0;
-        for (int i = 0; i < 1024; i++) c += part[i];
-        long long seg = (c + kItemTarget - 1) / kItemTarget;
-        seg = (seg + 15) & ~15LL;
-        if (seg < kMinSegRows) seg = kMinSegRows;
-        if (seg > (1LL << 30)) seg = 1LL << 30;
-        s_seg = (int)seg;
-        a.dyn[DYN_SEG_ROWS] = (int)seg;
-    }
-    __syncthreads();
-    part[t] = rows;
-    __syncthreads();
-    if (t == 0) {
-        long long r = 0;
-        for (int i = 0; i < 1024; i++) r += part[i];
+        a.dyn[DYN_SEG_ROWS] = seg;
         a.dyn[DYN_ROWS_LO] = (int)(r & 0xffffffffLL);
         a.dyn[DYN_ROWS_HI] = (int)(r >> 32);
     }
-    __syncthreads();
 
     // pass 2: work items per list = segments * query tiles
-    const int seg = s_seg;
-    long long items = 0;
-    for (int l = l0; l < l1; l++) {
-        int w = a.list_w[l];
-        int len = a.list_off[l + 1] - a.list_off[l];
-        if (w > 0 && len > 0) items += (long long)((len + seg - 1) / seg) * ((w + a.cw - 1) / a.cw);
-    }
-    part[t] = items;
-    __syncthreads();
-    if (t == 0) {
-        long long run = 0;
-        for (int i = 0; i < 1024; i++) { long long v = part[i]; part[i] = run; run += v; }
-        s_total = run;
-    }
-    __syncthreads();
+    auto list_items = [&](int l, int& nseg, int& nqt) {
+        const int w = a.list_w[l];
+        const int len = a.list_off[l + 1] - a.list_off[l];
+        nseg = (w > 0 && len > 0) ? (len + seg - 1) / seg : 0;
+        nqt = (w + a.cw - 1) / a.cw;
+    };
+    int items = 0;
+    for (int l = l0; l < l1; l++) { int nseg, nqt; list_items(l, nseg, nqt); items += nseg * nqt; }
     {
-        long long run = part[t];
+        int run = block_scan_1024(items, s_wave, total);
         for (int l = l0; l < l1; l++) {
-            a.item_base[l] = (int)run;
-            int w = a.list_w[l];
-            int len = a.list_off[l + 1] - a.list_off[l];
-            if (w > 0 && len > 0) run += (long long)((len + seg - 1) / seg) * ((w + a.cw - 1) / a.cw);
+            a.item_base[l] = run;
+            int nseg, nqt; list_items(l, nseg, nqt);
+            run += nseg * nqt;
         }
         if (t == 0) {
-            a.item_base[a.nlist] = (int)s_total;
+            a.item_base[a.nlist] = total;
             // never more than the table holds (cannot happen: the host sizes it from the same bound)
-            a.dyn[DYN_ITEMS] = (int)min(s_total, (long long)a.item_cap);
+            a.dyn[DYN_ITEMS] = min(total, a.item_cap);
         }
     }
 }
@@ -246,12 +251,45 @@ __global__ void k_bucket_scatter(BucketArgs a)
     a.bucket_q[a.bucket_off[l] + e] = (int)(i / a.nprobe);
 }
 
-// One wave per list writes the list's work items and queues them.  Items are numbered
-// list-major (segment-major, query tile minor inside a list); that number addresses the
-// item's result slots.  The order of execution is given by eight queues, one per XCD: all
-// query tiles of one (list, segment) go to the same queue, next to each other, so the
-// workgroups that re-read that segment run on one XCD at about the same time and share it
-// through that XCD's L2.
+// Work items and their order of execution.  Items are numbered list-major (segment-major,
+// query tile minor inside a list); that number addresses the item's result slots.  The order
+// of execution is given by eight queues, one per XCD: all query tiles of one (list, segment)
+// go to the same queue, next to each other, so the workgroups that re-read that segment run
+// on one XCD at about the same time and share it through that XCD's L2.  Inside a queue the
+// segments are ordered in rounds: the first segment that every list has in the queue, then
+// the second ones, and so on.  The segments of a long list are thus spread over the whole
+// run, and the later ones start from the lower bounds that the earlier ones have published.
+// (Within a round the order is that of arrival; results do not depend on the order.)
+constexpr int kRounds = 64;        // segments of a list beyond that many per queue share the last round
+
+// segment s of list l: queue and round
+__device__ __forceinline__ int queue_of(int l, int s) { return (l + s) & 7; }
+__device__ __forceinline__ int round_of(int s) { return min(s >> 3, kRounds - 1); }
+
+__global__ __launch_bounds__(256) void k_round_count(BucketArgs a)
+{
+    int l = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (l >= a.nlist) return;
+    int lane = threadIdx.x & 63;
+    int w = a.list_w[l];
+    int len = a.list_off[l + 1] - a.list_off[l];
+    if (w <= 0 || len <= 0) return;
+    int seg = a.dyn[DYN_SEG_ROWS];
+    int nqt = (w + a.cw - 1) / a.cw;
+    int nseg = (len + seg - 1) / seg;
+    for (int s = lane; s < nseg; s += 64) atomicAdd(&a.round_cnt[queue_of(l, s) * kRounds + round_of(s)], nqt);
+}
+
+// 8 x kRounds counts -> where every round starts in its queue, and the queue lengths
+__global__ __launch_bounds__(64) void k_round_scan(BucketArgs a)
+{
+    const int x = threadIdx.x;
+    if (x >= 8) return;
+    int run = 0;
+    for (int r = 0; r < kRounds; r++) { int c = a.round_cnt[x * kRounds + r]; a.round_cnt[x * kRounds + r] = run; run += c; }
+    a.xq_count[x] = min(run, a.item_cap);
+}
+
 __global__ __launch_bounds__(256) void k_item_expand(BucketArgs a)
 {
     int l = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -265,8 +303,8 @@ __global__ __launch_bounds__(256) void k_item_expand(BucketArgs a)
     int nseg = (len + seg - 1) / seg;
     long long base = a.item_base[l];
     for (int s = lane; s < nseg; s += 64) {
-        int x = (l + s) & 7;
-        int pos = atomicAdd(&a.xq_count[x], nqt);
+        const int x = queue_of(l, s), slot = x * kRounds + round_of(s);
+        const int pos = a.round_cnt[slot] + atomicAdd(&a.round_cur[slot], nqt);
         for (int t = 0; t < nqt; t++) {
             long long idx = base + (long long)s * nqt + t;
             if (idx < a.item_cap && pos + t < a.item_cap) {
@@ -284,6 +322,8 @@ hipError_t launch_bucketing(const BucketArgs& a, hipStream_t s)
     hipLaunchKernelGGL(k_bucket_count, dim3(gp), dim3(256), 0, s, a);
     hipLaunchKernelGGL(k_bucket_scan, dim3(1), dim3(1024), 0, s, a);
     hipLaunchKernelGGL(k_bucket_scatter, dim3(gp), dim3(256), 0, s, a);
+    hipLaunchKernelGGL(k_round_count, dim3((unsigned)((a.nlist + 3) / 4)), dim3(256), 0, s, a);
+    hipLaunchKernelGGL(k_round_scan, dim3(1), dim3(64), 0, s, a);
     hipLaunchKernelGGL(k_item_expand, dim3((unsigned)((a.nlist + 3) / 4)), dim3(256), 0, s, a);
     return hipGetLastError();
 }

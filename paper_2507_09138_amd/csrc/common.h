@@ -174,7 +174,9 @@ struct BucketArgs {
     int4* item_tab;             // [item_cap]
     int* dyn;                   // device scalars
     int* xq;                    // [8][item_cap] per-XCD queues of item numbers
-    int* xq_count;              // [8] (zeroed before launch)
+    int* xq_count;              // [8] queue lengths
+    int* round_cnt;             // [8][64] items per queue and round, then where each round starts (zeroed before launch)
+    int* round_cur;             // [8][64] items placed so far per queue and round (zeroed before launch)
     int item_cap;
 };
 hipError_t launch_bucketing(const BucketArgs& a, hipStream_t s);
