@@ -727,13 +727,19 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
             wait_vmcnt<0>();
             __builtin_amdgcn_s_barrier();
             HR_TOC(t_bar, tk);
-            fill_direct(blk + 2, bi ^ 2);
-            fill_direct(blk + 3, (bi ^ 2) + 1);
-            HR_TOC(t_stage, tk);
-            if (nact > 0) {
+            // (the requests of all waves at once keep the address unit busy for a while, and a
+            // wave cannot go on before its own are accepted: half of the waves send theirs
+            // now, the other half after their first block, when the first half multiplies)
+            const bool early = NW != 8 || wave < 4 || nact == 0;
+            auto requests = [&]() __attribute__((always_inline)) {
+                fill_direct(blk + 2, bi ^ 2);
+                fill_direct(blk + 3, (bi ^ 2) + 1);
+                HR_TOC(t_stage, tk);
+            };
+            if (early) requests();
 #pragma unroll
-                for (int h = 0; h < 2; h++) {
-                    if (blk + h >= nblk) break;
+            for (int h = 0; h < 2; h++) {
+                if (nact > 0 && blk + h < nblk) {
 #ifdef HR_SCAN_TIMING
                     n_blocks++;
 #endif
@@ -745,6 +751,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
                     HR_TOC(t_mfma, tk);
                     select_block(accs[0], nrms[0], row0 + (blk + h) * kBlockRows + g * 4);
                 }
+                if (h == 0 && !early) requests();
             }
             bi ^= 2;
         };
