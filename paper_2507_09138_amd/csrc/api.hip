@@ -70,7 +70,6 @@ static constexpr int kLdsLimit = 160 * 1024;      // LDS per workgroup on gfx950
 struct ScanPick { int shape, nbuf, cap; };
 static ScanPick pick_shape(int dtype, int d, int k)
 {
-    static const char* force = getenv("HR_SCAN_SHAPE");      // development switch: "<shape><nbuf>", e.g. 23
     const int cap = hr::sel_cap(k);
     const int cap_min = k + hr::kAppendMax + 4 + 24 < cap ? k + hr::kAppendMax + 4 + 24 : cap;   // least worth having
     auto fit_cap = [&](int shape, int nbuf) {     // largest capacity (multiple of 4) that fits, or 0
@@ -78,10 +77,6 @@ static ScanPick pick_shape(int dtype, int d, int k)
             if (hr::scan_lds_bytes(dtype, d, c, shape, nbuf) <= (size_t)kLdsLimit) return c;
         return 0;
     };
-    if (force && dtype != HR_F32) {
-        const int shape = force[0] - '0', nbuf = force[1] - '0';
-        if (const int c = fit_cap(shape, nbuf)) return {shape, nbuf, c};
-    }
     const int shapes[2] = {hr::SCAN_WIDE, hr::SCAN_NARROW};
     for (int shape : shapes) {
         if (dtype == HR_F32) {
@@ -378,8 +373,11 @@ size_t hr_ivf_workspace_bytes(const hr_ivf_index* ix, int64_t nq, int32_t nprobe
 
 // ---------------------------------------------------------------------------------------
 // persistent workgroups: as many as can be resident (LDS and, for 8-wave groups, registers)
-static long long* g_dbg = nullptr;   // TEMP
+#ifdef HR_SCAN_TIMING
+// development builds only: where the list scan leaves its per-workgroup phase timers
+static long long* g_dbg = nullptr;
 extern "C" void hr_debug_scan_timing(void* p) { g_dbg = (long long*)p; }
+#endif
 
 // persistent workgroups: one per CU (8-wave shape), or two where LDS lets two 4-wave ones share a CU
 static int scan_grid(const hr_ivf_index* ix, size_t lds, int shape)
@@ -492,12 +490,13 @@ static int enqueue_scan(const hr_ivf_index* ix, const Plan& p, char* ws, int64_t
     a.xq_count = b.xq_count;
     a.xq_head = zero + ix->nlist + DYN_COUNT + 16;
     a.xq_stride = p.item_cap;
+#ifdef HR_SCAN_TIMING
     a.dbg = g_dbg;
-    { const char* f = getenv("HR_DEBUG_FLAGS"); a.dbg_flags = f ? atoi(f) : 0; }
+#endif
     a.dense = 0;
     a.nq = (int)nq; a.k = k; a.cap = p.cap_s; a.l2 = metric == HR_METRIC_L2;
     a.nbuf = p.nbuf_s;
-    a.hist = getenv("HR_NO_HIST") ? nullptr : zero + p.zoff_hist;
+    a.hist = zero + p.zoff_hist;
     a.hpar = (const float*)(zero + p.zoff_hpar);
     hr_ivf_index* mix = const_cast<hr_ivf_index*>(ix);
     const bool timed = mix->prof_ev && mix->prof_n < mix->prof_cap;

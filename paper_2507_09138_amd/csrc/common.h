@@ -25,19 +25,17 @@ __host__ __device__ constexpr int cols_per_set(int dtype) { return dtype == HR_F
 
 // Workgroup shapes of the scan kernel: waves x column sets per wave.  A work item covers
 // shape_sets(shape) * cols_per_set(dtype) queries of a bucket.
-enum { SCAN_NARROW = 0 /* 4 waves x 1 set */, SCAN_WIDE4 = 1 /* 4 waves x 2 sets */, SCAN_WIDE = 2 /* 8 waves x 1 set */ };
+enum { SCAN_NARROW = 0 /* 4 waves, one per SIMD */, SCAN_WIDE = 1 /* 8 waves, two per SIMD */ };
 __host__ __device__ constexpr int shape_waves(int shape) { return shape == SCAN_WIDE ? 8 : 4; }
-__host__ __device__ constexpr int shape_ncs(int shape) { return shape == SCAN_WIDE4 ? 2 : 1; }
+__host__ __device__ constexpr int shape_ncs(int) { return 1; }                         // column sets per wave
 __host__ __device__ constexpr int shape_sets(int shape) { return shape_waves(shape) * shape_ncs(shape); }
 
 // k-steps (of 32 elements) whose row fragments a wave fetches from LDS together
 __host__ __device__ constexpr int scan_group(int dtype, int ksteps, int nw)
 {
-    #ifdef HR_TRY_G
-    return ksteps < 8 ? (ksteps < 4 ? ksteps : 4) : (nw == 8 ? HR_TRY_G : 8);
-#else
-    return ksteps < 8 ? (ksteps < 4 ? ksteps : 4) : (nw == 8 ? 4 : 8);
-#endif
+    if (ksteps < 8) return ksteps < 4 ? ksteps : 4;
+    if (nw == 8) return ((dtype == HR_F32 || dtype == HR_F16X2) && ksteps >= 32) ? 2 : 4;   // (256 registers per lane)
+    return 8;
 }
 // row blocks a wave keeps in flight in registers ahead of the one being staged: what the
 // register budget (512 per lane with one wave per SIMD, 256 with two) leaves after the query
@@ -48,11 +46,8 @@ __host__ __device__ constexpr int scan_prefetch(int dtype, int ksteps, int ncs, 
     const int rowb = ksteps * 32 * (dtype == HR_F32 ? 4 : 2);
     const int chunks = kBlockRows * rowb / 16;
     const int nld = (chunks + nw * 64 - 1) / (nw * 64);
-    const int left = (nw == 8 ? 256 : 512) - ncs * ksteps * 4 - 2 * planes * scan_group(dtype, ksteps, nw) * 4 - (nw == 8 ? 67 : 64);
+    const int left = (nw == 8 ? 256 : 512) - ncs * ksteps * 4 - 2 * planes * scan_group(dtype, ksteps, nw) * 4 - (nw == 8 ? 67 : 96);
     const int fit = left / (nld * 4 + 1);
-#ifdef HR_TRY_PF
-    if (nw == 8) return HR_TRY_PF;
-#endif
     return fit < 1 ? 1 : (fit > 4 ? 4 : fit);
 }
 
@@ -111,8 +106,7 @@ struct ScanArgs {
     float* key_out;             // dense mode: [nq, dense_nrows] every key is written here and nothing is selected
     int* hist;                  // [nq][kHistBins] keys found so far per query, by key range (or nullptr)
     const float* hpar;          // [nq][2] lower edge of bin 0 and bin width (width 0: query has no histogram)
-    long long* dbg;             // per-workgroup phase timers (only in HR_SCAN_TIMING builds)
-    int dbg_flags;              // experiments: 1 = thresholds at +inf (no selection), 2 = no MFMA/selection
+    long long* dbg;             // per-workgroup phase timers (HR_SCAN_TIMING builds only, else unused)
 };
 
 struct SeedArgs {

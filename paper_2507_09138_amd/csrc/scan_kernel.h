@@ -410,7 +410,6 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
             for (int m = 0; m < NLD; m++) goff[m] = 0;
         }
     }
-    if (a.dbg_flags & 4) { abase[0] = abase[1] = abase[2] = abase[3] = 0; }   // experiment: broadcast reads
 #ifdef HR_SCAN_TIMING
     long long t_pop = 0, t_setup = 0, t_mfma = 0, t_sel = 0, t_stage = 0, t_bar = 0, t_emit = 0;
     int n_items = 0, n_blocks = 0, n_cand_blocks = 0, n_prunes = 0;
@@ -472,8 +471,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
         // direct: block blk -> buffer buf, straight from HBM; the squared norms of its rows go
         // to a place of this wave's own (each wave fetches its own copy: 64 bytes)
         auto fill_direct = [&](int blk, int buf) __attribute__((always_inline)) {
-            if (a.dbg_flags & 16) return;      // experiment: compute on whatever is in LDS
-            const int bl = (a.dbg_flags & 64) ? 0 : min(blk, nblk - 1);      // experiment 64: always the first block (L2 hits)
+            const int bl = min(blk, nblk - 1);
             const int valid = min(nrows - bl * kBlockRows, kBlockRows);
 #pragma unroll
             for (int pl = 0; pl < S::planes; pl++) {
@@ -537,7 +535,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
 #pragma unroll
             for (int t = 0; t < KSTEPS; t++)
                 bfrag[s][t] = col_ok[s] ? *(const u32x4*)(qp + t * 64) : u32x4{0, 0, 0, 0};
-            thr[s] = (owner && col_ok[s] && !(a.dbg_flags & 1)) ? dec_key(a.thr[q[s]]) : __builtin_inff();
+            thr[s] = (owner && col_ok[s]) ? dec_key(a.thr[q[s]]) : __builtin_inff();
         }
         // candidates buffered per column: kept in a register by every lane of the column (the
         // lanes of a column see the same ballots, so they stay in step without LDS traffic)
@@ -551,7 +549,6 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
         int nact = 0;
 #pragma unroll
         for (int s = 0; s < NCS; s++) nact += __builtin_amdgcn_ballot_w64(col_ok[s]) != 0 ? 1 : 0;
-        if (a.dbg_flags & 2) nact = 0;
 
         if constexpr (!S::direct) {
             // Everything loaded so far (query operands, thresholds, first row block) is waited
@@ -944,11 +941,11 @@ inline hipError_t launch_scan_shape(int d, const ScanArgs& a, int grid, size_t l
 template <int DT>
 inline hipError_t launch_scan_dtype(int d, const ScanArgs& a, int shape, int grid, size_t lds, hipStream_t s)
 {
-    if constexpr (DT == HR_F16X2) return launch_scan_shape<DT, 1, 8>(d, a, grid, lds, s);     // (coarse step only)
-    switch (shape) {
-    case SCAN_WIDE: return launch_scan_shape<DT, 1, 8>(d, a, grid, lds, s);
-    case SCAN_WIDE4: return launch_scan_shape<DT, 2, 4>(d, a, grid, lds, s);
-    default: return launch_scan_shape<DT, 1, 4>(d, a, grid, lds, s);
+    if constexpr (DT == HR_F16X2) {
+        return launch_scan_shape<DT, 1, 8>(d, a, grid, lds, s);     // (coarse step only)
+    } else {
+        return shape == SCAN_WIDE ? launch_scan_shape<DT, 1, 8>(d, a, grid, lds, s)
+                                  : launch_scan_shape<DT, 1, 4>(d, a, grid, lds, s);
     }
 }
 
