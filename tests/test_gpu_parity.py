@@ -180,6 +180,58 @@ def test_duplicates_lowest_id_wins_exactly():
     ix.close()
 
 
+def test_coarse_duplicate_centroids_lower_index_first():
+    """Every centroid appears three times: equal coarse scores; the probe lists must be the
+    oracle's exactly (lower centroid index first), for odd table sizes and nprobe up to nlist."""
+    print("case duplicate centroids", flush=True)
+    hr = _hr()
+    g = torch.Generator(device="cpu").manual_seed(41)
+    for nbase, d, nprobes in ((7, 64, (1, 5, 21)), (67, 128, (3, 64, 128)), (43, 256, (129 - 1, 2))):
+        base = torch.randn(nbase, d, generator=g)
+        cent = base.repeat(3, 1)[torch.randperm(3 * nbase, generator=g)].contiguous()
+        nlist = cent.shape[0]
+        n = nlist * 5
+        x = torch.randn(n, d, generator=g)
+        off = torch.arange(0, n + 1, 5, dtype=torch.int64)
+        ids = torch.arange(n, dtype=torch.int64)
+        q = torch.randn(77, d, generator=g)
+        ix = hr.IvfIndex(cent.cuda(), off, x.cuda(), ids.cuda())
+        for metric in ("ip", "l2"):
+            for nprobe in nprobes:
+                nprobe = min(nprobe, nlist)
+                probe, score = ix.coarse(q.cuda(), nprobe, metric)
+                probe_o, score_o = oracle.coarse(q.numpy(), cent.numpy(), nprobe, METRIC[metric])
+                assert np.array_equal(probe.cpu().numpy(), probe_o), f"nlist={nlist} {metric} nprobe={nprobe}"
+                np.testing.assert_allclose(score.cpu().numpy(), score_o, rtol=1e-4, atol=1e-4)
+        ix.close()
+
+
+def test_coarse_in_chunks_of_queries():
+    """More queries than one chunk of the coarse key table holds (128 MiB / (4 nlist) = 8192 at
+    nlist = 4096): every chunk, and the ragged last one, against the oracle."""
+    print("case coarse chunks", flush=True)
+    hr = _hr()
+    g = torch.Generator(device="cpu").manual_seed(43)
+    nlist, d, nq = 4096, 64, 8192 + 8192 + 333
+    cent = torch.randn(nlist, d, generator=g)
+    x = torch.randn(nlist, d, generator=g).to(torch.float16)
+    off = torch.arange(0, nlist + 1, dtype=torch.int64)
+    ids = torch.arange(nlist, dtype=torch.int64)
+    q = torch.randn(nq, d, generator=g)
+    ix = hr.IvfIndex(cent.cuda(), off, x.cuda(), ids.cuda())
+    probe, score = ix.coarse(q.cuda(), 16, "ip")
+    probe, score = probe.cpu().numpy(), score.cpu().numpy()
+    sel = np.concatenate([np.arange(0, 40), np.arange(8170, 8230), np.arange(16370, 16420), np.arange(nq - 40, nq)])
+    qs = np.ascontiguousarray(q.numpy()[sel])
+    probe_o, score_o = oracle.coarse(qs, cent.numpy(), 16, oracle.IP)
+    cn = float(np.sqrt((cent.numpy().astype(np.float64) ** 2).sum(1)).mean())
+    st = check_probes(probe[sel], score[sel], probe_o, score_o,
+                      lambda i, c: oracle.pair_scores(qs, cent.numpy(), "f32", oracle.IP, np.full(len(c), i), c),
+                      "ip", TAU["f32"], _scale(qs, cn, "ip"))
+    print(f"[parity coarse chunks] {st}", flush=True)
+    ix.close()
+
+
 def test_variable_length_probe_lists_and_empty_batch():
     print("case variable-length probes", flush=True)
     hr = _hr()
