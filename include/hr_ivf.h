@@ -120,6 +120,25 @@ int hr_ivf_scan(const hr_ivf_index* index, const float* queries, int64_t nq,
                 void* stream);
 
 /*
+ * hr_ivf_scan_step — hr_ivf_scan with a carried result: one sub-stage of a retrieval that a
+ * scheduler splits into several (Section 4.2: clusters are added to a request's sub-stage until
+ * the time budget is reached; Section 5: the variable-length cluster search interface).
+ *   io_ids     DEV [nq, k] int64   } on entry the result of the earlier steps of these queries, best
+ *   io_scores  DEV [nq, k] float32 } first, empty places last with id -1 (all -1: nothing yet; the
+ *                                    scores of empty places are ignored); on return the k best of
+ *                                    that result and of the lists probed in this step, in the same
+ *                                    form.  Updated in place.
+ *   A full carried result also gives the scan its starting lower bound: rows that cannot enter
+ *   the result cost one compare.  Entries are ordered by (score, id) like everywhere else; a
+ *   carried entry keeps the score it was reported with.  A list must not be probed in two steps
+ *   of the same query (its vectors would be reported twice).  Other arguments as hr_ivf_scan.
+ */
+int hr_ivf_scan_step(const hr_ivf_index* index, const float* queries, int64_t nq,
+                     const int32_t* probe_ids, int32_t nprobe, int32_t k, int32_t metric,
+                     int64_t* io_ids, float* io_scores, void* workspace, size_t workspace_bytes,
+                     void* stream);
+
+/*
  * hr_ivf_stats — host-side facts about the last hr_ivf_search / hr_ivf_scan enqueued with this
  * workspace, read back AFTER the caller has synchronised the stream (this call does a small
  * blocking device-to-host copy).  out[0] = work items of the list scan, out[1] = rows per

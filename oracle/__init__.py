@@ -113,6 +113,25 @@ def scan(queries, offsets, vectors, dtype, ids, probe, k, metric):
     return out_i, out_s
 
 
+def merge_topk(ids_a, scores_a, ids_b, scores_b, k, metric):
+    """Carrying a result from one sub-stage of a retrieval to the next (Section 4.2 of the paper:
+    a request's clusters are searched in several sub-stages): the k best of two partial results
+    over disjoint sets of lists, in the order used everywhere (score best first, then id
+    ascending); places with id -1 are empty.  Plain numpy, query by query."""
+    nq = ids_a.shape[0]
+    out_i = np.full((nq, k), -1, np.int64)
+    out_s = np.full((nq, k), np.inf if metric == L2 else -np.inf, np.float64)
+    for q in range(nq):
+        ids = np.concatenate([ids_a[q], ids_b[q]]).astype(np.int64)
+        sc = np.concatenate([scores_a[q], scores_b[q]]).astype(np.float64)
+        keep = ids >= 0
+        ids, sc = ids[keep], sc[keep]
+        order = np.lexsort((ids, sc if metric == L2 else -sc))[:k]
+        out_i[q, :len(order)] = ids[order]
+        out_s[q, :len(order)] = sc[order]
+    return out_i, out_s
+
+
 def ivf_search(queries, centroids, offsets, vectors, dtype, ids, nprobe, k, metric):
     """Whole search.  Returns (probe_ids, ids, scores)."""
     q = _as(queries, np.float32)

@@ -42,6 +42,7 @@ def _load_lib():
     L.hr_ivf_search.argtypes = [p, p, c.c_int64, c.c_int32, c.c_int32, c.c_int32, p, p, p, c.c_size_t, p]
     L.hr_ivf_coarse.argtypes = [p, p, c.c_int64, c.c_int32, c.c_int32, p, p, p, c.c_size_t, p]
     L.hr_ivf_scan.argtypes = [p, p, c.c_int64, p, c.c_int32, c.c_int32, c.c_int32, p, p, p, c.c_size_t, p]
+    L.hr_ivf_scan_step.argtypes = [p, p, c.c_int64, p, c.c_int32, c.c_int32, c.c_int32, p, p, p, c.c_size_t, p]
     L.hr_ivf_stats.argtypes = [p, p, c.c_size_t, c.c_int64, c.c_int32, c.c_int32, c.POINTER(c.c_int64)]
     L.hr_ivf_profile_begin.argtypes = [p, c.c_int32]
     L.hr_ivf_profile_end.argtypes = [p, c.POINTER(c.c_int32), c.POINTER(c.c_double)]
@@ -116,6 +117,13 @@ def hr_ivf_scan(handle, queries, nq, probe_ids, nprobe, k, metric, out_ids, out_
     _check(lib.hr_ivf_scan(handle, _addr(queries), nq, _addr(probe_ids), nprobe, k, metric,
                            _addr(out_ids), _addr(out_scores), _addr(workspace), workspace_bytes,
                            _stream(stream)))
+
+
+def hr_ivf_scan_step(handle, queries, nq, probe_ids, nprobe, k, metric, io_ids, io_scores, workspace,
+                     workspace_bytes, stream=None):
+    _check(lib.hr_ivf_scan_step(handle, _addr(queries), nq, _addr(probe_ids), nprobe, k, metric,
+                                _addr(io_ids), _addr(io_scores), _addr(workspace), workspace_bytes,
+                                _stream(stream)))
 
 
 def hr_ivf_stats(handle, workspace, workspace_bytes, nq, nprobe, k):
@@ -198,6 +206,22 @@ class IvfIndex:
         scores = torch.empty(nq, k, dtype=torch.float32, device=q.device)
         ws = self.workspace(nq, nprobe, k)
         hr_ivf_scan(self.handle, q, nq, pr, nprobe, k, _METRIC[metric], ids, scores, ws, ws.numel())
+        return ids, scores
+
+    def new_state(self, nq, k, device="cuda"):
+        """An empty carried result for scan_step: ids -1."""
+        return (torch.full((nq, k), -1, dtype=torch.int64, device=device),
+                torch.zeros(nq, k, dtype=torch.float32, device=device))
+
+    def scan_step(self, queries, probe_ids, state, metric="ip"):
+        """One sub-stage: merges the lists in probe_ids into the carried result (ids, scores), in place."""
+        q = queries.contiguous()
+        pr = probe_ids.to(torch.int32).contiguous()
+        nq, nprobe = pr.shape
+        ids, scores = state
+        k = ids.shape[1]
+        ws = self.workspace(nq, nprobe, k)
+        hr_ivf_scan_step(self.handle, q, nq, pr, nprobe, k, _METRIC[metric], ids, scores, ws, ws.numel())
         return ids, scores
 
     def stats(self, nq, nprobe, k):

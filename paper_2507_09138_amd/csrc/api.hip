@@ -437,7 +437,8 @@ static int enqueue_coarse(const hr_ivf_index* ix, const Plan& p, char* ws, int64
 
 // grouping by list + cluster-major scan + per-query merge
 static int enqueue_scan(const hr_ivf_index* ix, const Plan& p, char* ws, int64_t nq, const int32_t* probe,
-                        int nprobe, int k, int metric, int64_t* out_ids, float* out_scores, hipStream_t s)
+                        int nprobe, int k, int metric, int64_t* out_ids, float* out_scores, hipStream_t s,
+                        bool carried = false)
 {
     if (p.shape_s < 0)
         return fail(HR_ERR_UNSUPPORTED, "list scan does not fit in LDS (d=%d, k=%d)", ix->d, k);
@@ -460,7 +461,10 @@ static int enqueue_scan(const hr_ivf_index* ix, const Plan& p, char* ws, int64_t
     b.item_cap = p.item_cap;
     HR_HIP(launch_bucketing(b, s));
 
-    // starting lower bounds from the first rows of every query's best-ranked list
+    // starting lower bounds: from a carried result, and from the first rows of every query's best-ranked list
+    if (carried)
+        HR_HIP(launch_state_thr(out_ids, out_scores, (const float*)(ws + p.o_qnorm_s), nq, k, metric == HR_METRIC_L2,
+                                (uint32_t*)(ws + p.o_thr) + nq, s));
     SeedArgs sd{};
     sd.rows = ix->vectors; sd.row_norm = ix->d_row_norm; sd.qop = ws + p.o_qop_s;
     sd.probe = probe; sd.list_off = ix->d_list_off;
@@ -516,6 +520,7 @@ static int enqueue_scan(const hr_ivf_index* ix, const Plan& p, char* ws, int64_t
     m.dense = 0;
     m.nq = (int)nq; m.nprobe = nprobe; m.nlist = (int)ix->nlist; m.k = k; m.cw = p.cw_s; m.l2 = a.l2;
     m.out_ids = out_ids; m.out_scores = out_scores;
+    m.carried = carried ? 1 : 0;
     HR_HIP(launch_merge(m, s));
     return HR_OK;
 }
@@ -579,6 +584,27 @@ int hr_ivf_scan(const hr_ivf_index* ix, const float* queries, int64_t nq, const 
     HR_HIP(launch_prep_queries(queries, nq, ix->d, ix->dtype, f32 ? ws + p.o_qop_c : nullptr, nullptr,
                                f32 ? nullptr : ws + p.o_qop_s, (float*)(ws + p.o_qnorm_s), s));
     return enqueue_scan(ix, p, ws, nq, probe_ids, nprobe, k, metric, out_ids, out_scores, s);
+}
+
+int hr_ivf_scan_step(const hr_ivf_index* ix, const float* queries, int64_t nq, const int32_t* probe_ids,
+                     int32_t nprobe, int32_t k, int32_t metric, int64_t* io_ids, float* io_scores,
+                     void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (int rc = check_index(ix)) return rc;
+    if (nprobe < 1 || nprobe > HR_NPROBE_MAX) return fail(HR_ERR_ARG, "nprobe=%d must be in 1..%d", nprobe, HR_NPROBE_MAX);
+    int np_plan = nprobe > ix->nlist ? (int)ix->nlist : nprobe;
+    if (int rc = check_batch(ix, nq, np_plan, k, metric, true)) return rc;
+    if (nq == 0) return HR_OK;
+    if (!queries || !probe_ids || !io_ids || !io_scores) return fail(HR_ERR_ARG, "queries / probe_ids / state null");
+    const Plan p = make_plan(ix, nq, nprobe, k);
+    if (int rc = check_ws(p, workspace, workspace_bytes)) return rc;
+    char* ws = (char*)workspace;
+    hipStream_t s = (hipStream_t)stream;
+    if (int rc = enqueue_clear(p, ws, nq, s)) return rc;
+    const bool f32 = ix->dtype == HR_F32;
+    HR_HIP(launch_prep_queries(queries, nq, ix->d, ix->dtype, f32 ? ws + p.o_qop_c : nullptr, nullptr,
+                               f32 ? nullptr : ws + p.o_qop_s, (float*)(ws + p.o_qnorm_s), s));
+    return enqueue_scan(ix, p, ws, nq, probe_ids, nprobe, k, metric, io_ids, io_scores, s, true);
 }
 
 int hr_ivf_stats(const hr_ivf_index* ix, const void* workspace, size_t workspace_bytes, int64_t nq,

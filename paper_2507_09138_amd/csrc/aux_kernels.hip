@@ -333,6 +333,34 @@ hipError_t launch_bucketing(const BucketArgs& a, hipStream_t s)
 // the per-request merge of Section 4.4): one wave per query walks the slots that hold its
 // candidates, keeps the k best in an LDS buffer pruned as in the scan, then orders the
 // survivors by (key, label) and writes the output row.
+// Key (larger is better) of an entry of a carried result, from its reported score: the score
+// itself for the inner product; |q|^2 - distance for squared L2 (the inverse of what the merge
+// reports, up to rounding).
+__device__ __forceinline__ float key_of_score(float score, float qn, int l2) { return l2 ? qn - score : score; }
+
+// Carried results as starting lower bounds: a query whose carried result is full starts the
+// scan at the key of its worst entry (minus a margin for the rounding of the line above).
+__global__ void k_state_thr(const int64_t* ids, const float* scores, const float* qnorm, int64_t nq, int k, int l2,
+                            uint32_t* thr)
+{
+    int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (q >= nq) return;
+    if (ids[q * k + k - 1] < 0) return;                      // (best first, empty places last)
+    const float sc = scores[q * k + k - 1];
+    const float qn = l2 ? qnorm[q] : 0.f;
+    const float key = key_of_score(sc, qn, l2);
+    const float margin = l2 ? 4.0e-7f * fmaxf(fabsf(qn), fabsf(sc)) : 0.f;
+    atomicMax(&thr[q], enc_key(key - margin));
+}
+
+hipError_t launch_state_thr(const int64_t* ids, const float* scores, const float* qnorm, int64_t nq, int k, int l2,
+                            uint32_t* thr, hipStream_t s)
+{
+    if (nq <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_state_thr, dim3((unsigned)((nq + 255) / 256)), dim3(256), 0, s, ids, scores, qnorm, nq, k, l2, thr);
+    return hipGetLastError();
+}
+
 constexpr int kMergeCap = 256;     // candidates buffered per query (k <= 128, up to 64 appended per step)
 
 __global__ __launch_bounds__(256) void k_merge(MergeArgs a)
@@ -341,9 +369,13 @@ __global__ __launch_bounds__(256) void k_merge(MergeArgs a)
     __shared__ int64_t s_tie[4][HR_K_MAX];
     __shared__ int s_pref[4][HR_NPROBE_MAX + 1];
     __shared__ int s_cnt[4];
+    __shared__ int64_t s_ext_id[4][HR_K_MAX];
+    __shared__ float s_ext_score[4][HR_K_MAX];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int64_t q = (int64_t)blockIdx.x * 4 + wave;
     if (q >= a.nq) return;                       // whole wave leaves; no block barrier below
+    int64_t* ext_id = s_ext_id[wave];
+    float* ext_score = s_ext_score[wave];
     Cand* buf = s_buf[wave];
     int64_t* tie = s_tie[wave];
     int* pref = s_pref[wave];
@@ -380,6 +412,26 @@ __global__ __launch_bounds__(256) void k_merge(MergeArgs a)
     }
     if (lane == 0) s_cnt[wave] = 0;
     wave_sync();
+    // ---- a carried result joins as one more partial result (read whole before anything of
+    // this query is written: the same arrays take the merged result)
+    const float qn0 = (a.l2 && a.qnorm) ? a.qnorm[q] : 0.f;
+    if (a.carried) {
+        for (int j0 = 0; j0 < k; j0 += 64) {
+            const int j = j0 + lane;
+            const int64_t id = j < k ? a.out_ids[(size_t)q * k + j] : -1;
+            const bool have = id >= 0;
+            const unsigned long long m = __builtin_amdgcn_ballot_w64(have);
+            if (have) {
+                const float sc = a.out_scores[(size_t)q * k + j];
+                ext_id[j] = id;
+                ext_score[j] = sc;
+                buf[s_cnt[wave] + lanes_below(m)] = Cand{enc_key(key_of_score(sc, qn0, a.l2)), kCarried | (uint32_t)j};
+            }
+            wave_sync();
+            if (lane == 0) s_cnt[wave] += __builtin_popcountll(m);
+            wave_sync();
+        }
+    }
 
     uint32_t thr = 0;                              // below every encoded key
     for (int f0 = 0; f0 < total; f0 += 64) {
@@ -420,7 +472,7 @@ __global__ __launch_bounds__(256) void k_merge(MergeArgs a)
             wave_sync();
             int n = __builtin_amdgcn_readfirstlane(s_cnt[wave]);
             if (n > kMergeCap - 64) {
-                uint32_t kth = wave_select<4>(buf, n, k, a.row_ids);
+                uint32_t kth = wave_select<4>(buf, n, k, a.row_ids, ext_id);
                 thr = kth > thr ? kth : thr;
                 if (lane == 0) s_cnt[wave] = k;
                 wave_sync();
@@ -430,7 +482,7 @@ __global__ __launch_bounds__(256) void k_merge(MergeArgs a)
     wave_sync();
     int n = __builtin_amdgcn_readfirstlane(s_cnt[wave]);
     if (n > k) {
-        wave_select<4>(buf, n, k, a.row_ids);
+        wave_select<4>(buf, n, k, a.row_ids, ext_id);
         n = k;
     }
     wave_sync();
@@ -442,7 +494,7 @@ __global__ __launch_bounds__(256) void k_merge(MergeArgs a)
     for (int m = 0; m < 2; m++) {
         int idx = lane + 64 * m;
         e[m] = (idx < n) ? buf[idx] : Cand{0u, 0u};
-        id[m] = (idx < n) ? (a.row_ids ? a.row_ids[e[m].row] : (int64_t)e[m].row) : INT64_MAX;
+        id[m] = (idx < n) ? label_of(e[m].row, a.row_ids, ext_id) : INT64_MAX;
         if (idx < n) tie[idx] = id[m];
     }
     wave_sync();
@@ -461,6 +513,7 @@ __global__ __launch_bounds__(256) void k_merge(MergeArgs a)
         if (idx < n) {
             float key = dec_key(e[m].key);
             float score = a.l2 ? fmaxf(qn - key, 0.f) : key;
+            if (e[m].row & kCarried) score = ext_score[e[m].row & ~kCarried];     // (as it was reported)
             size_t o = (size_t)q * k + pos[m];
             if (a.out_ids) a.out_ids[o] = id[m];
             if (a.out_ids32) a.out_ids32[o] = (int32_t)id[m];

@@ -138,6 +138,7 @@ struct MergeArgs {
     // dense mode
     int dense, dense_nqt, dense_nseg;
     int nq, nprobe, nlist, k, cw, l2;
+    int carried;                // out_ids / out_scores hold a previous result on entry: merged in (ids < 0: empty places)
     int64_t* out_ids;           // [nq, k] or nullptr
     int32_t* out_ids32;         // [nq, k] (coarse) or nullptr
     float* out_scores;          // [nq, k] or nullptr
@@ -154,6 +155,8 @@ hipError_t launch_row_norms(const void* rows, int dtype, int64_t nrows, int d, f
 hipError_t launch_prep_queries(const float* q, int64_t nq, int d, int dtype, void* qop_coarse,
                                float* qnorm_coarse, void* qop_scan, float* qnorm_scan, hipStream_t s);
 hipError_t launch_fill_i32(int* p, int64_t n, int v, hipStream_t s);
+hipError_t launch_state_thr(const int64_t* ids, const float* scores, const float* qnorm, int64_t nq, int k, int l2,
+                            uint32_t* thr, hipStream_t s);
 hipError_t launch_split_f32(const float* x, int64_t n, void* hi, void* lo, hipStream_t s);
 
 struct BucketArgs {

@@ -106,8 +106,17 @@ __device__ __forceinline__ float hist_edge(float base, float w, int b) { return 
 // ids == nullptr; labels are only fetched when equal keys straddle the k-th place).
 // Binary radix select on the 32 key bits: the cost does not depend on n.  Called by a whole
 // converged wave with wave-uniform arguments.  Returns the k-th best key.
+// Label of a candidate for tie-breaking and output: rows with the top bit set are entries of
+// a carried result (index into ext), the others stored rows.
+constexpr uint32_t kCarried = 0x80000000u;
+__device__ __forceinline__ int64_t label_of(uint32_t row, const int64_t* ids, const int64_t* ext)
+{
+    if (row & kCarried) return ext[row & ~kCarried];
+    return ids ? ids[row] : (int64_t)row;
+}
+
 template <int CAPE>   // entries held per lane: CAPE * 64 >= n
-__device__ __forceinline__ uint32_t wave_select(Cand* buf, int n, int k, const int64_t* ids)
+__device__ __forceinline__ uint32_t wave_select(Cand* buf, int n, int k, const int64_t* ids, const int64_t* ext = nullptr)
 {
     const int lane = lane_id();
     Cand e[CAPE];
@@ -152,7 +161,7 @@ __device__ __forceinline__ uint32_t wave_select(Cand* buf, int n, int k, const i
 #pragma unroll
         for (int m = 0; m < CAPE; m++) {
             const bool mine = (alive[m] >> lane) & 1;
-            label[m] = mine ? (ids ? ids[e[m].row] : (int64_t)e[m].row) : INT64_MAX;
+            label[m] = mine ? label_of(e[m].row, ids, ext) : INT64_MAX;
             rank[m] = 0;
         }
 #pragma unroll

@@ -232,6 +232,46 @@ def test_coarse_in_chunks_of_queries():
     ix.close()
 
 
+@pytest.mark.parametrize("dtype,metric", [("f16", "ip"), ("f32", "l2"), ("bf16", "l2")])
+def test_scan_in_steps_with_carried_result(dtype, metric):
+    """A retrieval split into sub-stages: the probe lists of every query are searched in four
+    steps (ragged: some places empty), the result carried from step to step.  The final result
+    must be that of one scan over all the lists: against the oracle's scan of the union, and,
+    for the inner product (a carried score is the key itself), bit for bit against the GPU's own
+    one-call scan.  A step that leaves fewer than k candidates carries empty places."""
+    print(f"case steps {dtype} {metric}", flush=True)
+    hr = _hr()
+    idx = _random_index(24000, 128, 60, dtype, seed=51)
+    host = Host(idx)
+    g = torch.Generator(device="cpu").manual_seed(12)
+    nq, nprobe, k = 150, 24, 40
+    q = torch.randn(nq, 128, generator=g).cuda()
+    probe = torch.stack([torch.randperm(60, generator=g)[:nprobe] for _ in range(nq)]).to(torch.int32)
+    probe[5, 3:] = -1                       # three lists in all for this query
+    probe[6, :] = -1                        # none at all
+    probe[7, 1::2] = -1                     # holes
+    ix = hr.IvfIndex(idx.centroids, idx.list_offsets, idx.list_vectors, idx.list_ids)
+    state = ix.new_state(nq, k)
+    for s0 in range(0, nprobe, 6):
+        ix.scan_step(q, probe[:, s0:s0 + 6].cuda(), state, metric)
+    ids_st, sc_st = state[0].cpu().numpy(), state[1].cpu().numpy()
+    ids_1, sc_1 = ix.scan(q, probe.cuda(), k, metric)
+    ids_1, sc_1 = ids_1.cpu().numpy(), sc_1.cpu().numpy()
+    qn = synth.to_numpy(q)
+    m = METRIC[metric]
+    ids_o, sc_o = oracle.scan(qn, host.off, host.vec, dtype, host.ids, probe.numpy(), k, m)
+    st = check_topk(ids_st, sc_st, ids_o, sc_o,
+                    lambda i, ids: oracle.pair_scores(qn, host.vec, dtype, m, np.full(len(ids), i), host.rows_of(ids)),
+                    metric, TAU[dtype], _scale(qn, host.xnorm(), metric))
+    print(f"[parity steps {dtype} {metric}] {st} same as one call: {float((ids_st == ids_1).all(1).mean()):.4f}", flush=True)
+    assert (ids_st[6] == -1).all() and (ids_1[6] == -1).all()
+    if metric == "ip":
+        assert np.array_equal(ids_st, ids_1) and np.array_equal(sc_st, sc_1)
+    else:
+        assert (ids_st == ids_1).all(1).mean() > 0.98
+    ix.close()
+
+
 def test_variable_length_probe_lists_and_empty_batch():
     print("case variable-length probes", flush=True)
     hr = _hr()

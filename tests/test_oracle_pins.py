@@ -286,3 +286,26 @@ def test_argument_errors():
         oracle.coarse(q, c, 4, oracle.IP)            # nprobe > nlist
     with pytest.raises(RuntimeError):
         oracle.coarse(q, c, 1, 7)                    # unknown metric
+
+
+def test_merge_of_two_partial_scans_is_the_scan_of_the_union():
+    """Carrying a result across sub-stages: scanning two disjoint halves of the probe lists and
+    merging equals scanning all of them (ids exactly, scores bitwise), also when a half finds
+    fewer than k candidates."""
+    rng = np.random.default_rng(77)
+    n, d, nlist, nq = 900, 24, 30, 40
+    x = rng.standard_normal((n, d)).astype(np.float32)
+    x[100:140] = x[60:100]                                   # equal scores across lists
+    off = np.sort(np.concatenate([[0, n], rng.integers(0, n + 1, nlist - 1)])).astype(np.int64)
+    ids = rng.permutation(n).astype(np.int64) * 5 + 3
+    q = rng.standard_normal((nq, d)).astype(np.float32)
+    probe = np.stack([rng.permutation(nlist)[:12] for _ in range(nq)]).astype(np.int32)
+    probe[3, 7:] = -1
+    for metric in (oracle.IP, oracle.L2):
+        for k in (1, 7, 64):
+            whole_i, whole_s = oracle.scan(q, off, x, "f32", ids, probe, k, metric)
+            a_i, a_s = oracle.scan(q, off, x, "f32", ids, probe[:, :5], k, metric)
+            b_i, b_s = oracle.scan(q, off, x, "f32", ids, probe[:, 5:], k, metric)
+            m_i, m_s = oracle.merge_topk(a_i, a_s, b_i, b_s, k, metric)
+            assert np.array_equal(m_i, whole_i)
+            assert np.array_equal(m_s, whole_s)
