@@ -16,6 +16,9 @@
 //   HR_F32   rows are float32, split on the fly into binary16 hi + 2^11-scaled lo planes; the
 //            query likewise; the four partial products are recombined with their scales,
 //            which keeps about 22 bits of each factor with float32 accumulation.
+//   HR_F16X2 (internal) the same arithmetic on rows that were split into hi and lo tables
+//            beforehand (the centroid table: the coarse step of Section 2.2 runs this kernel
+//            in "dense" mode, all queries against all rows, and writes every key out).
 #pragma once
 #include <utility>
 
