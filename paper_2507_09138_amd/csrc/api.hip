@@ -143,6 +143,7 @@ struct Plan {
     int shape_c /* workgroup shape, -1 = no fit */, nbuf_c, cap_c, cw_c, nqt_c, seg_c, nseg_c, items_c;
     // list scan
     int shape_s, nbuf_s, cap_s, cw_s, item_cap;
+    int slot_stride;                // entries per result slot of the list scan
     size_t o_zero, n_zero;          // ints cleared per call: list_w[nlist], dyn[DYN_COUNT], counters[8], ..., then
     size_t zoff_round, zoff_hist, zoff_hpar;   // (in ints from o_zero) round counters of the queues, per-query key histograms and their parameters
     size_t o_thr;                   // 2*nq ints set to "-inf"
@@ -205,7 +206,8 @@ static Plan make_plan(const hr_ivf_index* ix, int64_t nq, int nprobe, int k)
     p.o_ckeys = take((size_t)p.cchunk * nlist * 4);
     const size_t slots = (size_t)p.item_cap * p.cw_s;
     p.o_slot_cnt = take(slots * 4);
-    p.o_slot_ent = take(slots * (size_t)k * sizeof(Cand));
+    p.slot_stride = p.cap_s <= 64 && p.cap_s > k ? p.cap_s : k;      // small k: whole selection buffers, nothing to cut
+    p.o_slot_ent = take(slots * (size_t)p.slot_stride * sizeof(Cand));
     p.total = o;
     return p;
 }
@@ -484,6 +486,7 @@ static int enqueue_scan(const hr_ivf_index* ix, const Plan& p, char* ws, int64_t
     a.thr = (uint32_t*)(ws + p.o_thr) + nq;
     a.slot_cnt = (int*)(ws + p.o_slot_cnt);
     a.slot_ent = (Cand*)(ws + p.o_slot_ent);
+    a.slot_stride = p.slot_stride;
     a.work_counter = zero + ix->nlist + DYN_COUNT + 1;
     a.list_off = ix->d_list_off;
     a.bucket_off = b.bucket_off;
@@ -512,7 +515,7 @@ static int enqueue_scan(const hr_ivf_index* ix, const Plan& p, char* ws, int64_t
     }
 
     MergeArgs m{};
-    m.slot_cnt = a.slot_cnt; m.slot_ent = a.slot_ent;
+    m.slot_cnt = a.slot_cnt; m.slot_ent = a.slot_ent; m.slot_stride = p.slot_stride;
     m.row_ids = ix->ids;
     m.qnorm = (const float*)(ws + p.o_qnorm_s);
     m.probe = probe; m.pair_entry = b.pair_entry;

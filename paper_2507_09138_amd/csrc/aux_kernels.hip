@@ -463,7 +463,7 @@ __global__ __launch_bounds__(256) void k_merge(MergeArgs a)
         for (int o = 32; o > 0; o >>= 1) maxc = max(maxc, __shfl_xor(maxc, o));
         for (int j = 0; j < maxc; j++) {
             if (j < c) {
-                Cand cd = a.slot_ent[slot * k + j];
+                Cand cd = a.slot_ent[slot * a.slot_stride + j];
                 if (cd.key >= thr) {
                     int pos = atomicAdd(&s_cnt[wave], 1);
                     buf[pos] = cd;

@@ -87,7 +87,8 @@ struct ScanArgs {
     const void* qop;            // query operand rows (layout depends on dtype)
     uint32_t* thr;              // [nq] running per-query lower bound of the k-th key (enc_key)
     int* slot_cnt;              // [items * CW]
-    Cand* slot_ent;             // [items * CW * k]
+    Cand* slot_ent;             // [items * CW * slot_stride]
+    int slot_stride;            // entries per slot: k, or cap where that is small (no cut at the end of an item)
     int* work_counter;          // zeroed before launch
     // bucket mode
     const int* list_off;        // [nlist+1] row offsets
@@ -126,6 +127,7 @@ enum { DYN_ITEMS = 0, DYN_SEG_ROWS = 1, DYN_ROWS_LO = 2, DYN_ROWS_HI = 3, DYN_PA
 struct MergeArgs {
     const int* slot_cnt;
     const Cand* slot_ent;
+    int slot_stride;
     const int64_t* row_ids;     // nullptr: label = row number
     const float* qnorm;         // [nq] squared norm of the query operand (L2 only)
     // bucket mode

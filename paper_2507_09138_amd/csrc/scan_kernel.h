@@ -807,8 +807,10 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
         }
 
         if (a.key_out != nullptr) flush_keys();
-        // ---- hand what is left to the item's slots: columns still over k are cut down first
-        // (one at a time, whole wave), then every lane copies one column's entries
+        // ---- hand what is left to the item's slots: columns with more entries than a slot holds
+        // (slot_stride: k, or the whole buffer for small k, when nothing has to be cut) are cut
+        // down to the k best first (one at a time, whole wave), then every lane copies one
+        // column's entries
         wave_sync();
         if (a.key_out == nullptr) {
             int c = 0;
@@ -817,7 +819,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
                 const int v = __shfl(ccnt[s], (lane - s * NC) & 63);
                 if (lane >= s * NC && lane < (s + 1) * NC) c = v;
             }
-            unsigned long long over = __builtin_amdgcn_ballot_w64(c > a.k);
+            unsigned long long over = __builtin_amdgcn_ballot_w64(c > a.slot_stride);
             while (over) {
                 const int wc = __builtin_ctzll(over);
                 over &= over - 1;
@@ -840,12 +842,12 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
                 bool v = __shfl(col_ok[s] ? 1 : 0, (lane - s * NC) & 63) != 0;
                 if (lane >= s * NC && lane < (s + 1) * NC) ok = v;
             }
-            const int n = min(c, a.k);
+            const int n = c > a.slot_stride ? a.k : c;
             if (lane < WC && ok) {
                 const size_t slot = (size_t)item * S::cw + wave * WC + lane;
                 a.slot_cnt[slot] = n;
                 const Cand* cb = mysel + lane * a.cap;
-                Cand* out = a.slot_ent + slot * a.k;
+                Cand* out = a.slot_ent + slot * a.slot_stride;
                 for (int i = 0; i < n; i++) out[i] = cb[i];
             }
             // ---- what this item found tightens the lower bounds of its queries for the items
