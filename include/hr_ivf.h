@@ -45,7 +45,7 @@ enum {
 };
 
 #define HR_K_MAX 128          /* largest k */
-#define HR_NPROBE_MAX 128     /* largest nprobe */
+#define HR_NPROBE_MAX 512     /* largest nprobe (the paper probes 128 to 512 clusters: Section 6.1) */
 #define HR_WORKSPACE_ALIGN 256
 
 /*

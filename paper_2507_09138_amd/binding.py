@@ -14,7 +14,7 @@ import torch
 
 HR_METRIC_IP, HR_METRIC_L2 = 0, 1
 HR_F32, HR_F16, HR_BF16 = 0, 1, 2
-HR_K_MAX, HR_NPROBE_MAX = 128, 128
+HR_K_MAX, HR_NPROBE_MAX = 128, 512
 _ERR = {-1: "HR_ERR_ARG", -2: "HR_ERR_HANDLE", -3: "HR_ERR_WORKSPACE", -4: "HR_ERR_HIP",
         -5: "HR_ERR_UNSUPPORTED"}
 _DTYPE = {torch.float32: HR_F32, torch.float16: HR_F16, torch.bfloat16: HR_BF16}

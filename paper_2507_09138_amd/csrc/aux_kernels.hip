@@ -617,19 +617,20 @@ __global__ __launch_bounds__(256) void k_topk_rows(TopkArgs a)
         }
     }
     wave_sync();
-    // order: key descending, index ascending
-    Cand e[2];
-    int pos[2] = {0, 0};
+    // order: key descending, index ascending (rank of every entry = entries ahead of it)
+    constexpr int PER = HR_NPROBE_MAX / 64;         // entries per lane
+    Cand e[PER];
+    int pos[PER];
 #pragma unroll
-    for (int m = 0; m < 2; m++) e[m] = lane + 64 * m < k ? ent[lane + 64 * m] : Cand{0u, 0u};
+    for (int m = 0; m < PER; m++) { e[m] = lane + 64 * m < k ? ent[lane + 64 * m] : Cand{0u, 0u}; pos[m] = 0; }
     for (int i = 0; i < k; i++) {
         const Cand o = ent[i];
 #pragma unroll
-        for (int m = 0; m < 2; m++) pos[m] += (o.key > e[m].key || (o.key == e[m].key && o.row < e[m].row)) ? 1 : 0;
+        for (int m = 0; m < PER; m++) pos[m] += (o.key > e[m].key || (o.key == e[m].key && o.row < e[m].row)) ? 1 : 0;
     }
     const float qn = (a.l2 && a.qnorm) ? a.qnorm[q] : 0.f;
 #pragma unroll
-    for (int m = 0; m < 2; m++) {
+    for (int m = 0; m < PER; m++) {
         if (lane + 64 * m < k) {
             const float key = dec_key(e[m].key);
             const size_t o = (size_t)q * a.k + pos[m];

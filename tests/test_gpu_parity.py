@@ -161,6 +161,16 @@ def test_nprobe_max_many_lists():
     compare_all(idx, q, nprobe=128, k=20, metric="ip")
 
 
+def test_nprobe_512_paper_range():
+    """The paper probes 128 to 512 clusters with k = 1 (Section 6.1): nprobe 512 over 700 lists."""
+    print("case nprobe=512 over 700 lists, k=1", flush=True)
+    idx = _random_index(30000, 64, 700, "f16", seed=37)
+    g = torch.Generator(device="cpu").manual_seed(10)
+    q = torch.randn(21, 64, generator=g).cuda()
+    compare_all(idx, q, nprobe=512, k=1, metric="l2")
+    compare_all(idx, q, nprobe=256, k=5, metric="ip")
+
+
 def test_duplicates_lowest_id_wins_exactly():
     """Every vector is stored four times: equal scores; the ids must be the oracle's exactly."""
     print("case duplicates", flush=True)
