@@ -67,18 +67,20 @@ __device__ __forceinline__ int lanes_below(unsigned long long mask)
 // later LDS read wait for all of them, which would undo the prefetching.  The loads complete
 // in order and are counted by vmcnt, so "all but the n youngest have landed" is wait_vmcnt<n>;
 // loads the compiler issues itself in between only make that wait longer, never shorter.
-// (m0 is reserved: the compiler sets it immediately before each of its own uses.)
+// (m0 is reserved: the compiler sets it immediately before each of its own uses.  The s_nop is
+// the wait state between a scalar write of m0 and a memory instruction that reads it; inside
+// inline assembly nobody else would insert it.)
 __device__ __forceinline__ uint32_t lds_addr(const void* p)
 {
     return (uint32_t)(size_t)(__attribute__((address_space(3))) const char*)p;
 }
 __device__ __forceinline__ void lds_dma16(const void* base, uint32_t byte_off, uint32_t lds)
 {
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" :: "s"(lds), "v"(byte_off), "s"(base) : "memory");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" :: "s"(lds), "v"(byte_off), "s"(base) : "memory");
 }
 __device__ __forceinline__ void lds_dma4(const void* base, uint32_t byte_off, uint32_t lds)
 {
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, %2" :: "s"(lds), "v"(byte_off), "s"(base) : "memory");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" :: "s"(lds), "v"(byte_off), "s"(base) : "memory");
 }
 template <int N>
 __device__ __forceinline__ void wait_vmcnt()
