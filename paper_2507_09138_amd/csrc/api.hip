@@ -520,7 +520,6 @@ static int enqueue_scan(const hr_ivf_index* ix, const Plan& p, char* ws, int64_t
     m.qnorm = (const float*)(ws + p.o_qnorm_s);
     m.probe = probe; m.pair_entry = b.pair_entry;
     m.list_off = ix->d_list_off; m.bucket_off = b.bucket_off; m.item_base = b.item_base; m.dyn = b.dyn;
-    m.dense = 0;
     m.nq = (int)nq; m.nprobe = nprobe; m.nlist = (int)ix->nlist; m.k = k; m.cw = p.cw_s; m.l2 = a.l2;
     m.out_ids = out_ids; m.out_scores = out_scores;
     m.carried = carried ? 1 : 0;

@@ -380,13 +380,11 @@ __global__ __launch_bounds__(256) void k_merge(MergeArgs a)
     int64_t* tie = s_tie[wave];
     int* pref = s_pref[wave];
     const int k = a.k;
-    const int seg_rows = a.dense ? 1 : a.dyn[DYN_SEG_ROWS];
+    const int seg_rows = a.dyn[DYN_SEG_ROWS];
 
     // ---- how many segments (= slots) does each probed list contribute
     int total;
-    if (a.dense) {
-        total = a.dense_nseg;
-    } else {
+    {
         int run = 0;
         for (int p0 = 0; p0 < a.nprobe; p0 += 64) {
             int p = p0 + lane;
@@ -439,9 +437,7 @@ __global__ __launch_bounds__(256) void k_merge(MergeArgs a)
         int c = 0;
         size_t slot = 0;
         if (f < total) {
-            if (a.dense) {
-                slot = ((size_t)f * a.dense_nqt + (size_t)(q / a.cw)) * a.cw + (size_t)(q % a.cw);
-            } else {
+            {
                 int lo = 0, hi = a.nprobe;        // largest p with pref[p] <= f
                 while (hi - lo > 1) {
                     int mid = (lo + hi) >> 1;
@@ -516,14 +512,12 @@ __global__ __launch_bounds__(256) void k_merge(MergeArgs a)
             if (e[m].row & kCarried) score = ext_score[e[m].row & ~kCarried];     // (as it was reported)
             size_t o = (size_t)q * k + pos[m];
             if (a.out_ids) a.out_ids[o] = id[m];
-            if (a.out_ids32) a.out_ids32[o] = (int32_t)id[m];
             if (a.out_scores) a.out_scores[o] = score;
         }
     }
     for (int idx = n + lane; idx < k; idx += 64) {     // fewer than k candidates: pad
         size_t o = (size_t)q * k + idx;
         if (a.out_ids) a.out_ids[o] = -1;
-        if (a.out_ids32) a.out_ids32[o] = -1;
         if (a.out_scores) a.out_scores[o] = a.l2 ? __builtin_inff() : -__builtin_inff();
     }
 }

@@ -130,19 +130,15 @@ struct MergeArgs {
     int slot_stride;
     const int64_t* row_ids;     // nullptr: label = row number
     const float* qnorm;         // [nq] squared norm of the query operand (L2 only)
-    // bucket mode
     const int* probe;           // [nq, nprobe]
     const int* pair_entry;      // [nq, nprobe] position of the pair inside its list's bucket
     const int* list_off;        // [nlist+1]
     const int* bucket_off;      // [nlist+1]
     const int* item_base;       // [nlist+1]
     const int* dyn;
-    // dense mode
-    int dense, dense_nqt, dense_nseg;
     int nq, nprobe, nlist, k, cw, l2;
     int carried;                // out_ids / out_scores hold a previous result on entry: merged in (ids < 0: empty places)
     int64_t* out_ids;           // [nq, k] or nullptr
-    int32_t* out_ids32;         // [nq, k] (coarse) or nullptr
     float* out_scores;          // [nq, k] or nullptr
 };
 
