@@ -23,7 +23,7 @@ def test_every_declared_symbol_is_exported(hr):
     text = open(os.path.join(ROOT, "include", "hr_ivf.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = set(re.findall(r"\b(hr_[a-z0-9_]+)\s*\(", text))
-    assert {"hr_ivf_load", "hr_ivf_search", "hr_ivf_coarse", "hr_ivf_scan", "hr_ivf_free",
+    assert {"hr_ivf_load", "hr_ivf_search", "hr_ivf_coarse", "hr_ivf_scan", "hr_ivf_scan_step", "hr_ivf_free",
             "hr_ivf_workspace_bytes", "hr_last_error"} <= names
     for n in names:
         assert hasattr(hr.lib, n), n
@@ -68,5 +68,6 @@ def test_null_handle_is_rejected(hr):
     assert hr.lib.hr_ivf_search(None, None, 1, 1, 1, 0, None, None, None, 0, None) == -2
     assert hr.lib.hr_ivf_coarse(None, None, 1, 1, 0, None, None, None, 0, None) == -2
     assert hr.lib.hr_ivf_scan(None, None, 1, None, 1, 1, 0, None, None, None, 0, None) == -2
+    assert hr.lib.hr_ivf_scan_step(None, None, 1, None, 1, 1, 0, None, None, None, 0, None) == -2
     bogus = (ctypes.c_uint64 * 64)()                 # memory that is not an index
     assert hr.lib.hr_ivf_free(ctypes.cast(bogus, ctypes.c_void_p)) == -2
