@@ -139,6 +139,18 @@ int hr_ivf_scan_step(const hr_ivf_index* index, const float* queries, int64_t nq
                      void* stream);
 
 /*
+ * hr_ivf_list_hits — how often every list has been probed by hr_ivf_search / hr_ivf_scan /
+ * hr_ivf_scan_step calls on this index since it was loaded or since the last reset: the
+ * per-cluster access frequency that a cache of hot clusters is driven by (Section 4.4: the
+ * clusters accessed most often are the ones kept resident).  A by-product of the grouping of
+ * probes by list; counted on the device, in the order of the stream.
+ *   out_hits  DEV [nlist] int64.   reset != 0: the counters start again from zero.
+ * Enqueues one small kernel on the stream; calls that run concurrently on other streams are
+ * counted, but a reset concurrent with them may miss or keep some of their probes.
+ */
+int hr_ivf_list_hits(const hr_ivf_index* index, int64_t* out_hits, int32_t reset, void* stream);
+
+/*
  * hr_ivf_stats — host-side facts about the last hr_ivf_search / hr_ivf_scan enqueued with this
  * workspace, read back AFTER the caller has synchronised the stream (this call does a small
  * blocking device-to-host copy).  out[0] = work items of the list scan, out[1] = rows per

@@ -42,6 +42,7 @@ def _load_lib():
     L.hr_ivf_search.argtypes = [p, p, c.c_int64, c.c_int32, c.c_int32, c.c_int32, p, p, p, c.c_size_t, p]
     L.hr_ivf_coarse.argtypes = [p, p, c.c_int64, c.c_int32, c.c_int32, p, p, p, c.c_size_t, p]
     L.hr_ivf_scan.argtypes = [p, p, c.c_int64, p, c.c_int32, c.c_int32, c.c_int32, p, p, p, c.c_size_t, p]
+    L.hr_ivf_list_hits.argtypes = [p, p, c.c_int32, p]
     L.hr_ivf_scan_step.argtypes = [p, p, c.c_int64, p, c.c_int32, c.c_int32, c.c_int32, p, p, p, c.c_size_t, p]
     L.hr_ivf_stats.argtypes = [p, p, c.c_size_t, c.c_int64, c.c_int32, c.c_int32, c.POINTER(c.c_int64)]
     L.hr_ivf_profile_begin.argtypes = [p, c.c_int32]
@@ -124,6 +125,10 @@ def hr_ivf_scan_step(handle, queries, nq, probe_ids, nprobe, k, metric, io_ids, 
     _check(lib.hr_ivf_scan_step(handle, _addr(queries), nq, _addr(probe_ids), nprobe, k, metric,
                                 _addr(io_ids), _addr(io_scores), _addr(workspace), workspace_bytes,
                                 _stream(stream)))
+
+
+def hr_ivf_list_hits(handle, out_hits, reset=False, stream=None):
+    _check(lib.hr_ivf_list_hits(handle, _addr(out_hits), 1 if reset else 0, _stream(stream)))
 
 
 def hr_ivf_stats(handle, workspace, workspace_bytes, nq, nprobe, k):
@@ -223,6 +228,12 @@ class IvfIndex:
         ws = self.workspace(nq, nprobe, k)
         hr_ivf_scan_step(self.handle, q, nq, pr, nprobe, k, _METRIC[metric], ids, scores, ws, ws.numel())
         return ids, scores
+
+    def list_hits(self, reset=False):
+        """Probes per list since load / the last reset: int64 [nlist] on the device."""
+        out = torch.empty(self.nlist, dtype=torch.int64, device="cuda")
+        hr_ivf_list_hits(self.handle, out, reset)
+        return out
 
     def stats(self, nq, nprobe, k):
         ws = self.workspace(nq, nprobe, k)

@@ -123,6 +123,7 @@ struct hr_ivf_index {
     float* d_cent_norm;    // [nlist]
     void* d_cent_hi;       // [nlist, d] binary16: centroids rounded
     void* d_cent_lo;       // [nlist, d] binary16: (centroid - hi) * 2^11
+    unsigned long long* d_hits;   // [nlist] probes per list since load / last reset
     int num_cus;
     int lds_limit;
     // optional kernel timing (hr_ivf_profile_begin/end)
@@ -285,6 +286,8 @@ int hr_ivf_load(const float* centroids, const int64_t* list_offsets, const void*
     if (e == hipSuccess) e = hipMalloc(&ix->d_cent_norm, (size_t)nlist * 4);
     if (e == hipSuccess) e = hipMalloc(&ix->d_cent_hi, (size_t)nlist * d * 2);
     if (e == hipSuccess) e = hipMalloc(&ix->d_cent_lo, (size_t)nlist * d * 2);
+    if (e == hipSuccess) e = hipMalloc(&ix->d_hits, (size_t)nlist * 8);
+    if (e == hipSuccess) e = hipMemsetAsync(ix->d_hits, 0, (size_t)nlist * 8, s);
     if (e == hipSuccess) e = hipMemcpyAsync(ix->d_list_off, h_off, (size_t)(nlist + 1) * 4, hipMemcpyHostToDevice, s);
     if (e == hipSuccess) e = launch_row_norms(list_vectors, dtype, N, d, ix->d_row_norm, s);
     if (e == hipSuccess) e = launch_row_norms(centroids, HR_F32, nlist, d, ix->d_cent_norm, s);
@@ -297,6 +300,7 @@ int hr_ivf_load(const float* centroids, const int64_t* list_offsets, const void*
         if (ix->d_cent_norm) (void)hipFree(ix->d_cent_norm);
         if (ix->d_cent_hi) (void)hipFree(ix->d_cent_hi);
         if (ix->d_cent_lo) (void)hipFree(ix->d_cent_lo);
+        if (ix->d_hits) (void)hipFree(ix->d_hits);
         delete ix;
         return fail(HR_ERR_HIP, "hr_ivf_load: %s", hipGetErrorString(e));
     }
@@ -360,6 +364,7 @@ int hr_ivf_free(hr_ivf_index* ix)
     (void)hipFree(ix->d_cent_norm);
     (void)hipFree(ix->d_cent_hi);
     (void)hipFree(ix->d_cent_lo);
+    (void)hipFree(ix->d_hits);
     delete ix;
     return HR_OK;
 }
@@ -450,6 +455,7 @@ static int enqueue_scan(const hr_ivf_index* ix, const Plan& p, char* ws, int64_t
     b.probe = probe; b.nq = (int)nq; b.nprobe = nprobe; b.nlist = (int)ix->nlist; b.cw = p.cw_s;
     b.list_off = ix->d_list_off;
     b.list_w = zero;
+    b.hits = ix->d_hits;
     b.pair_entry = (int*)(ws + p.o_pair_entry);
     b.bucket_off = (int*)(ws + p.o_bucket_off);
     b.bucket_q = (int*)(ws + p.o_bucket_q);
@@ -607,6 +613,14 @@ int hr_ivf_scan_step(const hr_ivf_index* ix, const float* queries, int64_t nq, c
     HR_HIP(launch_prep_queries(queries, nq, ix->d, ix->dtype, f32 ? ws + p.o_qop_c : nullptr, nullptr,
                                f32 ? nullptr : ws + p.o_qop_s, (float*)(ws + p.o_qnorm_s), s));
     return enqueue_scan(ix, p, ws, nq, probe_ids, nprobe, k, metric, io_ids, io_scores, s, true);
+}
+
+int hr_ivf_list_hits(const hr_ivf_index* ix, int64_t* out_hits, int32_t reset, void* stream)
+{
+    if (int rc = check_index(ix)) return rc;
+    if (!out_hits) return fail(HR_ERR_ARG, "out_hits is null");
+    HR_HIP(launch_read_hits(ix->d_hits, ix->nlist, out_hits, reset != 0, (hipStream_t)stream));
+    return HR_OK;
 }
 
 int hr_ivf_stats(const hr_ivf_index* ix, const void* workspace, size_t workspace_bytes, int64_t nq,

@@ -36,6 +36,22 @@ hipError_t launch_split_f32(const float* x, int64_t n, void* hi, void* lo, hipSt
     return hipGetLastError();
 }
 
+// Per-list access counters (how often each list was probed: the frequency a cache of hot
+// clusters is driven by, Section 4.4 of the paper): copy out, optionally start again from zero.
+__global__ void k_read_hits(unsigned long long* hits, int64_t n, int64_t* out, int reset)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    out[i] = (int64_t)(reset ? atomicExch(&hits[i], 0ull) : hits[i]);
+}
+
+hipError_t launch_read_hits(unsigned long long* hits, int64_t n, int64_t* out, int reset, hipStream_t s)
+{
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_read_hits, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, hits, n, out, reset);
+    return hipGetLastError();
+}
+
 __device__ __forceinline__ float wave_sum(float v)
 {
 #pragma unroll
@@ -194,6 +210,7 @@ __global__ __launch_bounds__(1024) void k_bucket_scan(BucketArgs a)
     for (int l = l0; l < l1; l++) {
         int w = a.list_w[l];
         long long len = a.list_off[l + 1] - a.list_off[l];
+        if (a.hits != nullptr && w > 0) atomicAdd(&a.hits[l], (unsigned long long)w);     // access frequency of the list
         w_sum += w;
         cost += len * ((w + a.cw - 1) / a.cw);
         if (w > 0) rows += len;

@@ -153,6 +153,7 @@ hipError_t launch_row_norms(const void* rows, int dtype, int64_t nrows, int d, f
 hipError_t launch_prep_queries(const float* q, int64_t nq, int d, int dtype, void* qop_coarse,
                                float* qnorm_coarse, void* qop_scan, float* qnorm_scan, hipStream_t s);
 hipError_t launch_fill_i32(int* p, int64_t n, int v, hipStream_t s);
+hipError_t launch_read_hits(unsigned long long* hits, int64_t n, int64_t* out, int reset, hipStream_t s);
 hipError_t launch_state_thr(const int64_t* ids, const float* scores, const float* qnorm, int64_t nq, int k, int l2,
                             uint32_t* thr, hipStream_t s);
 hipError_t launch_split_f32(const float* x, int64_t n, void* hi, void* lo, hipStream_t s);
@@ -173,6 +174,7 @@ struct BucketArgs {
     int* round_cnt;             // [8][64] items per queue and round, then where each round starts (zeroed before launch)
     int* round_cur;             // [8][64] items placed so far per queue and round (zeroed before launch)
     int item_cap;
+    unsigned long long* hits;   // [nlist] probes per list since load or the last reset (index-owned), or nullptr
 };
 hipError_t launch_bucketing(const BucketArgs& a, hipStream_t s);
 

@@ -282,6 +282,33 @@ def test_scan_in_steps_with_carried_result(dtype, metric):
     ix.close()
 
 
+def test_list_access_counters():
+    """Per-list access frequency (what a cache of hot clusters is driven by): after some calls
+    the counters equal the histogram of all probe lists used, exactly; empty places are not
+    counted; a reset starts again from zero."""
+    print("case access counters", flush=True)
+    hr = _hr()
+    idx = _random_index(9000, 64, 40, "f16", seed=61)
+    g = torch.Generator(device="cpu").manual_seed(14)
+    ix = hr.IvfIndex(idx.centroids, idx.list_offsets, idx.list_vectors, idx.list_ids)
+    assert int(ix.list_hits().sum()) == 0
+    want = np.zeros(40, np.int64)
+    for nq, nprobe in ((50, 7), (130, 12)):
+        q = torch.randn(nq, 64, generator=g).cuda()
+        probe, _ = ix.coarse(q, nprobe, "ip")            # (the coarse step alone counts nothing)
+        ix.search(q, nprobe, 5, "ip")
+        want += np.bincount(probe.cpu().numpy().ravel(), minlength=40)
+    pr = torch.stack([torch.randperm(40, generator=g)[:6] for _ in range(33)]).to(torch.int32)
+    pr[4, 2:] = -1
+    q = torch.randn(33, 64, generator=g).cuda()
+    ix.scan(q, pr.cuda(), 3, "l2")
+    want += np.bincount(pr.numpy()[pr.numpy() >= 0], minlength=40)
+    got = ix.list_hits(reset=True).cpu().numpy()
+    assert np.array_equal(got, want), (got, want)
+    assert int(ix.list_hits().sum()) == 0
+    ix.close()
+
+
 def test_variable_length_probe_lists_and_empty_batch():
     print("case variable-length probes", flush=True)
     hr = _hr()
