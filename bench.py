@@ -161,7 +161,7 @@ def main():
         "metric": "queries/sec batched IVF top-k search", "value": nq / (ms_per_step * 1e-3),
         "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": {"f16": "f16", "bf16": "bf16", "f32": "f16x2"}[cfg.dtype] + " operands, f32 accumulate",
+        "dtype": {"f16": "f16", "bf16": "bf16", "f32": "f16x2"}[cfg.dtype],      # MFMA operand type; float32 accumulation
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}: N={cfg.N}, d={cfg.d}, nlist={cfg.nlist}, nq={nq}, "
                                f"nprobe={cfg.nprobe}, k={cfg.k}, {cfg.dtype} storage, {cfg.metric}",
