@@ -64,8 +64,8 @@ static constexpr int kLdsLimit = 160 * 1024;      // LDS per workgroup on gfx950
 // Workgroup shape, number of staging buffers and selection buffer capacity for a scan.
 // Shape: 8 waves (two per SIMD) when the selection buffers of that many query columns still
 // fit in LDS, else 4 waves with half the columns.  Buffers: float32 rows are staged through
-// registers into 2; 16-bit rows go straight to LDS, best into 4 (blocks in pairs, one barrier
-// per pair), for which the selection buffers may give up a little of their capacity, else
+// registers into 2; 16-bit rows go straight to LDS, best into 6 or 4 (blocks in pairs, one
+// barrier per pair; for 4 the selection buffers may give up a little of their capacity), else
 // into 3 or 2.  shape -1 = no fit.
 struct ScanPick { int shape, nbuf, cap; };
 static ScanPick pick_shape(int dtype, int d, int k)
@@ -83,6 +83,7 @@ static ScanPick pick_shape(int dtype, int d, int k)
             if (hr::scan_lds_bytes(dtype, d, cap, shape, 2) <= (size_t)kLdsLimit) return {shape, 2, cap};
             continue;
         }
+        if (hr::scan_lds_bytes(dtype, d, cap, shape, 6) <= (size_t)kLdsLimit) return {shape, 6, cap};   // (short rows: a third pair on its way)
         if (const int c = fit_cap(shape, 4)) return {shape, 4, c};
         for (int nbuf = 3; nbuf >= 2; nbuf--)
             if (hr::scan_lds_bytes(dtype, d, cap, shape, nbuf) <= (size_t)kLdsLimit) return {shape, nbuf, cap};

@@ -376,13 +376,13 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
     extern __shared__ __align__(16) char smem[];
     // staging buffers in LDS: a.nbuf of them (direct) or 2 (through registers); block blk of an
     // item uses buffer blk % NB, and the blocks up to blk + NB - 1 are on their way meanwhile
-    // With 4 buffers (direct) the blocks go in pairs: one barrier per two blocks, the next pair
+    // With 4 or 6 buffers (direct) the blocks go in pairs: one barrier per two blocks, the next pair
     // on its way meanwhile.  A barrier per block keeps the two waves of a SIMD in step (both
     // want the matrix pipeline, then both the vector ALU); between the barriers of a pair they
     // drift apart and overlap.
     const int NB = S::direct ? a.nbuf : 2;
-    const bool pairs = S::direct && NB == 4;
-    const int D = pairs ? 2 : NB - 1;              // blocks requested ahead of the one in use
+    const bool pairs = S::direct && (NB == 4 || NB == 6);
+    const int D = pairs ? NB - 2 : NB - 1;         // blocks requested ahead of the one in use
     // LDS: [NB staging buffers][selection buffers cw*cap][row norms NB x 16][item]
     char* stage = smem;
     Cand* sel = (Cand*)(smem + NB * S::buf_bytes);
@@ -735,7 +735,8 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
         // direct staging, 4 buffers: blocks blk and blk+1 between two barriers, blocks blk+2 and
         // blk+3 requested into the two buffers the previous pair leaves
         auto pair_direct = [&](int blk) __attribute__((always_inline)) {
-            wait_vmcnt<0>();
+            // (6 buffers: the requests of the pair after the next one may still be on their way)
+            if (NB == 6) wait_vmcnt<2 * S::lpf>(); else wait_vmcnt<0>();
             __builtin_amdgcn_s_barrier();
             HR_TOC(t_bar, tk);
             // (the requests of all waves at once keep the address unit busy for a while, and a
@@ -743,8 +744,9 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
             // now, the other half after their first block, when the first half multiplies)
             const bool early = NW != 8 || wave < 4 || nact == 0;
             auto requests = [&]() __attribute__((always_inline)) {
-                fill_direct(blk + 2, bi ^ 2);
-                fill_direct(blk + 3, (bi ^ 2) + 1);
+                const int fb = bi + D >= NB ? bi + D - NB : bi + D;     // the buffers the pair before this one used
+                fill_direct(blk + D, fb);
+                fill_direct(blk + D + 1, fb + 1);
                 HR_TOC(t_stage, tk);
             };
             if (early) requests();
@@ -764,7 +766,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
                 }
                 if (h == 0 && !early) requests();
             }
-            bi ^= 2;
+            bi = bi + 2 == NB ? 0 : bi + 2;
         };
         // through registers: (1) barrier: block blk is complete in LDS and nobody reads block
         // blk-1 any more, (2) block blk+1 from the ring into the buffer that one leaves, and
