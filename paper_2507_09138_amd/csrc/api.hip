@@ -67,10 +67,21 @@ static constexpr int kLdsLimit = 160 * 1024;      // LDS per workgroup on gfx950
 // registers into 2; 16-bit rows go straight to LDS, best into 6 or 4 (blocks in pairs, one
 // barrier per pair; for 4 the selection buffers may give up a little of their capacity), else
 // into 3 or 2.  shape -1 = no fit.
-struct ScanPick { int shape, nbuf, cap; };
+struct ScanPick { int shape, nbuf, cap, gsel; };
 static ScanPick pick_shape(int dtype, int d, int k)
 {
     const int cap = hr::sel_cap(k);
+    if (cap > 64) {
+        // large k: selection buffers of that size would take most of LDS; they live in global
+        // memory (the result slots themselves) and LDS is left to the row buffers
+        if (dtype == HR_F32) {
+            if (hr::scan_lds_bytes(dtype, d, 0, hr::SCAN_WIDE, 2) <= (size_t)kLdsLimit) return {hr::SCAN_WIDE, 2, cap, 1};
+            return {-1, 0, 0, 0};
+        }
+        for (int nbuf : {6, 4, 3, 2})
+            if (hr::scan_lds_bytes(dtype, d, 0, hr::SCAN_WIDE, nbuf) <= (size_t)kLdsLimit) return {hr::SCAN_WIDE, nbuf, cap, 1};
+        return {-1, 0, 0, 0};
+    }
     const int cap_min = k + hr::kAppendMax + 4 + 24 < cap ? k + hr::kAppendMax + 4 + 24 : cap;   // least worth having
     auto fit_cap = [&](int shape, int nbuf) {     // largest capacity (multiple of 4) that fits, or 0
         for (int c = cap; c >= cap_min; c -= 4)
@@ -80,15 +91,15 @@ static ScanPick pick_shape(int dtype, int d, int k)
     const int shapes[2] = {hr::SCAN_WIDE, hr::SCAN_NARROW};
     for (int shape : shapes) {
         if (dtype == HR_F32) {
-            if (hr::scan_lds_bytes(dtype, d, cap, shape, 2) <= (size_t)kLdsLimit) return {shape, 2, cap};
+            if (hr::scan_lds_bytes(dtype, d, cap, shape, 2) <= (size_t)kLdsLimit) return {shape, 2, cap, 0};
             continue;
         }
-        if (hr::scan_lds_bytes(dtype, d, cap, shape, 6) <= (size_t)kLdsLimit) return {shape, 6, cap};   // (short rows: a third pair on its way)
-        if (const int c = fit_cap(shape, 4)) return {shape, 4, c};
+        if (hr::scan_lds_bytes(dtype, d, cap, shape, 6) <= (size_t)kLdsLimit) return {shape, 6, cap, 0};   // (short rows: a third pair on its way)
+        if (const int c = fit_cap(shape, 4)) return {shape, 4, c, 0};
         for (int nbuf = 3; nbuf >= 2; nbuf--)
-            if (hr::scan_lds_bytes(dtype, d, cap, shape, nbuf) <= (size_t)kLdsLimit) return {shape, nbuf, cap};
+            if (hr::scan_lds_bytes(dtype, d, cap, shape, nbuf) <= (size_t)kLdsLimit) return {shape, nbuf, cap, 0};
     }
-    return {-1, 0, 0};
+    return {-1, 0, 0, 0};
 }
 
 using namespace hr;
@@ -144,7 +155,7 @@ struct Plan {
     // coarse step: centroid table scanned with all queries as one dense bucket
     int shape_c /* workgroup shape, -1 = no fit */, nbuf_c, cap_c, cw_c, nqt_c, seg_c, nseg_c, items_c;
     // list scan
-    int shape_s, nbuf_s, cap_s, cw_s, item_cap;
+    int shape_s, nbuf_s, cap_s, gsel_s, cw_s, item_cap;
     int slot_stride;                // entries per result slot of the list scan
     size_t o_zero, n_zero;          // ints cleared per call: list_w[nlist], dyn[DYN_COUNT], counters[8], ..., then
     size_t zoff_round, zoff_hist, zoff_hpar;   // (in ints from o_zero) round counters of the queues, per-query key histograms and their parameters
@@ -167,7 +178,7 @@ static Plan make_plan(const hr_ivf_index* ix, int64_t nq, int nprobe, int k)
     p.shape_c = -1; p.nbuf_c = 0; p.cap_c = 0;
     for (int nbuf = 3; nbuf >= 2 && p.shape_c < 0; nbuf--)
         if (scan_lds_bytes(HR_F16X2, ix->d, 0, SCAN_WIDE, nbuf) <= (size_t)kLdsLimit) { p.shape_c = SCAN_WIDE; p.nbuf_c = nbuf; }
-    p.shape_s = ps.shape; p.nbuf_s = ps.nbuf; p.cap_s = ps.cap;
+    p.shape_s = ps.shape; p.nbuf_s = ps.nbuf; p.cap_s = ps.cap; p.gsel_s = ps.gsel;
     p.cw_c = cols_per_set(HR_F32) * shape_sets(p.shape_c < 0 ? 0 : p.shape_c);
     // queries per coarse chunk: the [chunk, nlist] key table stays within 128 MiB
     p.cchunk = (int64_t)(128u << 20) / (nlist * 4) / p.cw_c * p.cw_c;
@@ -208,7 +219,7 @@ static Plan make_plan(const hr_ivf_index* ix, int64_t nq, int nprobe, int k)
     p.o_ckeys = take((size_t)p.cchunk * nlist * 4);
     const size_t slots = (size_t)p.item_cap * p.cw_s;
     p.o_slot_cnt = take(slots * 4);
-    p.slot_stride = p.cap_s <= 64 && p.cap_s > k ? p.cap_s : k;      // small k: whole selection buffers, nothing to cut
+    p.slot_stride = p.gsel_s || (p.cap_s <= 64 && p.cap_s > k) ? p.cap_s : k;   // whole selection buffers, nothing to cut (else: k)
     p.o_slot_ent = take(slots * (size_t)p.slot_stride * sizeof(Cand));
     p.total = o;
     return p;
@@ -450,7 +461,7 @@ static int enqueue_scan(const hr_ivf_index* ix, const Plan& p, char* ws, int64_t
 {
     if (p.shape_s < 0)
         return fail(HR_ERR_UNSUPPORTED, "list scan does not fit in LDS (d=%d, k=%d)", ix->d, k);
-    const size_t lds = scan_lds_bytes(ix->dtype, ix->d, p.cap_s, p.shape_s, p.nbuf_s);
+    const size_t lds = scan_lds_bytes(ix->dtype, ix->d, p.gsel_s ? 0 : p.cap_s, p.shape_s, p.nbuf_s);
     int* zero = (int*)(ws + p.o_zero);
     BucketArgs b{};
     b.probe = probe; b.nq = (int)nq; b.nprobe = nprobe; b.nlist = (int)ix->nlist; b.cw = p.cw_s;
@@ -510,6 +521,7 @@ static int enqueue_scan(const hr_ivf_index* ix, const Plan& p, char* ws, int64_t
     a.dense = 0;
     a.nq = (int)nq; a.k = k; a.cap = p.cap_s; a.l2 = metric == HR_METRIC_L2;
     a.nbuf = p.nbuf_s;
+    a.gsel = p.gsel_s;
     a.hist = zero + p.zoff_hist;
     a.hpar = (const float*)(zero + p.zoff_hpar);
     hr_ivf_index* mix = const_cast<hr_ivf_index*>(ix);

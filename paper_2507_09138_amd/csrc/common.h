@@ -104,6 +104,7 @@ struct ScanArgs {
     int dense, dense_items, dense_nqt, dense_seg_rows, dense_nrows;
     int nq, k, cap, l2;
     int nbuf;                   // staging buffers in LDS (16-bit storage; float32 always uses 2)
+    int gsel;                   // selection buffers = the item's slots in global memory (slot_stride = cap), none in LDS
     float* key_out;             // dense mode: [nq, dense_nrows] every key is written here and nothing is selected
     int* hist;                  // [nq][kHistBins] keys found so far per query, by key range (or nullptr)
     const float* hpar;          // [nq][2] lower edge of bin 0 and bin width (width 0: query has no histogram)

@@ -55,6 +55,13 @@ __device__ __forceinline__ void wave_sync()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// value of lane ^ 8 (the other half of a row of 16 lanes: rotation by 8 inside the row, a
+// data-parallel-primitive operand modifier, no LDS round trip)
+__device__ __forceinline__ float lane_xor8(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x128 /* row_ror:8 */, 0xf, 0xf, false));
+}
+
 __device__ __forceinline__ int lanes_below(unsigned long long mask)
 {
     return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0));
@@ -364,7 +371,7 @@ __device__ __forceinline__ uint32_t select_k(Cand* buf, int n, int k, int cap, c
     return wave_select<3>(buf, n, k, ids);
 }
 
-template <int DT, int KSTEPS, int NCS, int NW>
+template <int DT, int KSTEPS, int NCS, int NW, bool GS>   // GS = a.gsel
 __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
 {
     using S = ScanShape<DT, KSTEPS, NCS, NW>;
@@ -384,9 +391,12 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
     const bool pairs = S::direct && (NB == 4 || NB == 6);
     const int D = pairs ? NB - 2 : NB - 1;         // blocks requested ahead of the one in use
     // LDS: [NB staging buffers][selection buffers cw*cap][row norms NB x 16][item]
+    // (GS: the selection buffers are the item's result slots in global memory instead: a
+    // wave alone writes and reads the buffers of its columns, candidates are few, and LDS is
+    // left to the row buffers)
     char* stage = smem;
     Cand* sel = (Cand*)(smem + NB * S::buf_bytes);
-    float* nstage = (float*)(sel + S::cw * a.cap);
+    float* nstage = (float*)(sel + (GS ? 0 : S::cw * a.cap));
     int* s_item = (int*)(nstage + NB * kBlockRows);
 
     const int lane = lane_id();
@@ -475,6 +485,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
         }
         const int nrows = row_end - row0;
         const int nblk = (nrows + kBlockRows - 1) / kBlockRows;
+        Cand* const gsel = a.slot_ent + ((size_t)item * S::cw + wave * WC) * (size_t)a.slot_stride;   // (GS: slot_stride = cap)
         const char* src = (const char*)a.rows + (size_t)row0 * S::rowb;
         const char* src_lo = S::planes == 2 ? (const char*)a.rows_lo + (size_t)row0 * S::rowb : src;
 
@@ -631,12 +642,12 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
                 for (int r = 0; r < 4; r++) {
                     float dot;
                     if constexpr (T::planes == 2) {
-                        float t0 = __shfl_xor(acc[s][0][r], 8);       // hi rows x lo query
-                        float t1 = __shfl_xor(acc[s][1][r], 8);       // lo rows x lo query
+                        float t0 = lane_xor8(acc[s][0][r]);      // hi rows x lo query
+                        float t1 = lane_xor8(acc[s][1][r]);      // lo rows x lo query
                         dot = acc[s][0][r] + (t0 + acc[s][1][r]) * (1.0f / 2048.0f) + t1 * (1.0f / 4194304.0f);
                     } else if constexpr (DT == HR_BF16) {
                         float v = acc[s][0][r] + acc[s][1][r];
-                        dot = v + __shfl_xor(v, 8);
+                        dot = v + lane_xor8(v);
                     } else {
                         dot = acc[s][0][r] + acc[s][1][r];
                     }
@@ -663,6 +674,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
 #pragma unroll
                     for (int r = 0; r < 4; r++) pass[r] = key[r] >= thr[s] && (rbase + r < row_end);
                     Cand* ssel = mysel + (s * NC) * a.cap;
+                    Cand* gs = gsel + (s * NC) * a.cap;
                     // slot of each new candidate = column count + candidates of the same
                     // column in earlier row slots and in lower lanes of this row slot
                     int add = 0;
@@ -671,7 +683,9 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
                         const unsigned long long mine = __builtin_amdgcn_ballot_w64(pass[r]) & colmask;
                         if (pass[r]) {
                             const int pos = ccnt[s] + add + __builtin_popcountll(mine & below);
-                            ssel[jcol * a.cap + pos] = Cand{enc_key(key[r]), (uint32_t)(rbase + r)};
+                            const Cand cd{enc_key(key[r]), (uint32_t)(rbase + r)};
+                            if (GS) gs[jcol * a.cap + pos] = cd;
+                            else ssel[jcol * a.cap + pos] = cd;
                         }
                         add += __builtin_popcountll(mine);
                     }
@@ -682,7 +696,8 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
                         int col = __builtin_ctzll(full);
                         full &= full - 1;
                         int n = __builtin_amdgcn_readlane(ccnt[s], col);
-                        uint32_t kth = select_k(ssel + col * a.cap, n, a.k, a.cap, a.row_ids);
+                        uint32_t kth = GS ? select_k(gs + col * a.cap, n, a.k, a.cap, a.row_ids)
+                                              : select_k(ssel + col * a.cap, n, a.k, a.cap, a.row_ids);
 #ifdef HR_SCAN_TIMING
                         n_prunes++;
 #endif
@@ -823,7 +838,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
                 const int v = __shfl(ccnt[s], (lane - s * NC) & 63);
                 if (lane >= s * NC && lane < (s + 1) * NC) c = v;
             }
-            unsigned long long over = __builtin_amdgcn_ballot_w64(c > a.slot_stride);
+            unsigned long long over = __builtin_amdgcn_ballot_w64(!GS && c > a.slot_stride);
             while (over) {
                 const int wc = __builtin_ctzll(over);
                 over &= over - 1;
@@ -850,9 +865,11 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
             if (lane < WC && ok) {
                 const size_t slot = (size_t)item * S::cw + wave * WC + lane;
                 a.slot_cnt[slot] = n;
-                const Cand* cb = mysel + lane * a.cap;
-                Cand* out = a.slot_ent + slot * a.slot_stride;
-                for (int i = 0; i < n; i++) out[i] = cb[i];
+                if (!GS) {
+                    const Cand* cb = mysel + lane * a.cap;
+                    Cand* out = a.slot_ent + slot * a.slot_stride;
+                    for (int i = 0; i < n; i++) out[i] = cb[i];
+                }
             }
             // ---- what this item found tightens the lower bounds of its queries for the items
             // still to come.  Every query has a histogram of the keys reported so far over
@@ -877,7 +894,30 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
                     now = __hip_atomic_load(&a.thr[qcol], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
                 int added = 0;
-                if (have && wd > 0.f) {
+                if (GS) {
+                    // one column at a time, its entries spread over the lanes
+#pragma unroll 1
+                    for (int cl = 0; cl < WC; cl++) {
+                        const float cwd = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wd), cl));
+                        const int cn = __builtin_amdgcn_readlane(have ? n : 0, cl);
+                        if (cn == 0 || !(cwd > 0.f)) continue;
+                        const float cbase = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, base), cl));
+                        const uint32_t cnow = __builtin_amdgcn_readlane(now, cl);
+                        const int qc = __builtin_amdgcn_readlane(qcol, cl);
+                        const float inv = 1.0f / cwd;
+                        bool did = false;
+                        for (int i = lane; i < cn; i += 64) {
+                            const uint32_t ek = gsel[cl * a.cap + i].key;
+                            if (ek < cnow) continue;
+                            const float key = dec_key(ek);
+                            int b = (int)fminf(fmaxf((key - cbase) * inv, 0.f), (float)(kHistBins - 1));
+                            if (hist_edge(cbase, cwd, b) > key) b--;
+                            else if (b < kHistBins - 1 && hist_edge(cbase, cwd, b + 1) <= key) b++;
+                            if (b >= 0) did |= atomicAdd(&a.hist[(size_t)qc * kHistBins + b], 1) >= 0;
+                        }
+                        if (__builtin_amdgcn_ballot_w64(did) != 0 && lane == cl) added = 1;
+                    }
+                } else if (have && wd > 0.f) {
                     const Cand* cb = mysel + lane * a.cap;
                     const float inv = 1.0f / wd;
                     for (int i = 0; i < n; i++) {
@@ -933,12 +973,12 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
 #endif
 }
 
-template <int DT, int NCS, int NW>
+template <int DT, int NCS, int NW, bool GS>
 inline hipError_t launch_scan_shape(int d, const ScanArgs& a, int grid, size_t lds, hipStream_t s)
 {
 #define HR_SCAN_CASE(KS)                                                                           \
     case KS * 32: {                                                                                \
-        auto kern = k_scan<DT, KS, NCS, NW>;                                                       \
+        auto kern = k_scan<DT, KS, NCS, NW, GS>;                                                      \
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
         if (e != hipSuccess) return e;                                                             \
         hipLaunchKernelGGL(kern, dim3(grid), dim3(NW * 64), lds, s, a);                            \
@@ -960,10 +1000,11 @@ template <int DT>
 inline hipError_t launch_scan_dtype(int d, const ScanArgs& a, int shape, int grid, size_t lds, hipStream_t s)
 {
     if constexpr (DT == HR_F16X2) {
-        return launch_scan_shape<DT, 1, 8>(d, a, grid, lds, s);     // (coarse step only)
+        return launch_scan_shape<DT, 1, 8, false>(d, a, grid, lds, s);     // (coarse step only)
     } else {
-        return shape == SCAN_WIDE ? launch_scan_shape<DT, 1, 8>(d, a, grid, lds, s)
-                                  : launch_scan_shape<DT, 1, 4>(d, a, grid, lds, s);
+        if (a.gsel) return shape == SCAN_WIDE ? launch_scan_shape<DT, 1, 8, true>(d, a, grid, lds, s) : hipErrorInvalidValue;
+        return shape == SCAN_WIDE ? launch_scan_shape<DT, 1, 8, false>(d, a, grid, lds, s)
+                                  : launch_scan_shape<DT, 1, 4, false>(d, a, grid, lds, s);
     }
 }
 
@@ -1045,12 +1086,12 @@ __global__ __launch_bounds__(256) void k_seed(SeedArgs a)
         for (int r4 = 0; r4 < 4; r4++) {
             float dot;
             if constexpr (DT == HR_F32) {
-                float t0 = __shfl_xor(acc0[r4], 8);
-                float t1 = __shfl_xor(acc1[r4], 8);
+                float t0 = lane_xor8(acc0[r4]);
+                float t1 = lane_xor8(acc1[r4]);
                 dot = acc0[r4] + (t0 + acc1[r4]) * (1.0f / 2048.0f) + t1 * (1.0f / 4194304.0f);
             } else if constexpr (DT == HR_BF16) {
                 float v = acc0[r4] + acc1[r4];
-                dot = v + __shfl_xor(v, 8);
+                dot = v + lane_xor8(v);
             } else {
                 dot = acc0[r4] + acc1[r4];
             }
