@@ -1,6 +1,6 @@
 """Benchmark of the batched IVF search hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C3] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C3] [--nq N] [--nprobe P] [--no-cpu-baseline]
 
 One step = one hr_ivf_search call (coarse scoring, top-nprobe, grouping by list, cluster-major
 scan, per-query merge) over one batch of synthetic queries, index and queries resident in HBM.
@@ -104,6 +104,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="C3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--nq", type=int, default=0, help="batch size instead of the workload's own")
+    ap.add_argument("--nprobe", type=int, default=0, help="lists probed per query instead of the workload's own")
     ap.add_argument("--substages", type=int, default=0,
                     help="extra mode: one step = coarse + this many hr_ivf_scan_step calls over slices of the probe "
                          "lists, result carried along (the step-wise interface); prints its own JSON line")
@@ -116,6 +118,10 @@ def main():
     import synth
 
     cfg = synth.CONFIGS[args.workload]
+    if args.nq > 0:
+        cfg = synth.scaled(cfg, nq=args.nq)
+    if args.nprobe > 0:
+        cfg = synth.scaled(cfg, nprobe=args.nprobe)
     torch.cuda.set_device(0)
     idx = synth.make_index(cfg, "cuda")
     rounds = synth.make_queries(cfg, idx)

@@ -67,6 +67,10 @@ CONFIGS = {
                  32, 10, rounds=8, seed=BASE_SEED + 3, index_of="C3"),
     "C5": Config("C5", 16777216, 768, 16384, "zipf", 1.05, False, "bf16", "l2", 8192, "size",
                  0.0, 128, 100, seed=BASE_SEED + 5),
+    # the paper's own shape (Section 6.1): ~38 M passages, 1024-dimensional embeddings, IVF4096,
+    # nprobe 128..512, top-1, requests arriving in small batches.  77 GB of binary16 rows.
+    "P1": Config("P1", 37748736, 1024, 4096, "zipf", 0.5, True, "f16", "ip", 256, "size", 0.0,
+                 128, 1, seed=BASE_SEED + 6),
 }
 
 TORCH_DTYPE = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}

@@ -417,3 +417,15 @@ def test_config5_large_bf16_l2_scaled():
 @pytest.mark.skipif(os.environ.get("HR_SKIP_C5_FULL") == "1", reason="HR_SKIP_C5_FULL=1")
 def test_config5_large_bf16_l2_full_size_sampled():
     _run_config("C5", sample=48)
+
+
+def test_paper_shape_scaled():
+    """d = 1024, nprobe 128, top-1, a small batch (the paper's own parameters, Section 6.1) on a small index"""
+    (st_p, st_k, e2e), = _run_config("P1", N=1 << 20, nlist=512, nq=96)
+    assert st_k["exact_id_rows"] >= 0.98
+
+
+@pytest.mark.skipif(os.environ.get("HR_SKIP_P1_FULL") == "1", reason="HR_SKIP_P1_FULL=1 (77 GB index, 80 GB of host memory)")
+def test_paper_shape_full_size_sampled():
+    _run_config("P1", sample=16)
+
