@@ -132,6 +132,62 @@ def merge_topk(ids_a, scores_a, ids_b, scores_b, k, metric):
     return out_i, out_s
 
 
+def topk_of_rows(queries, vectors, dtype, ids, rows, k, metric):
+    """The k best of a given set of rows per query, in the order used everywhere (score best
+    first, then id ascending).  ``rows[q]`` is any sequence of row numbers; numbers < 0 or past
+    the end mean "no row" and a row named twice counts once.  This is what searching a local
+    cache of earlier results for a new query amounts to (Section 4.3 of the paper), and, over
+    the union of such rows and the rows of probed lists, what a retrieval started from that
+    cache must end with.  Returns (ids [nq,k] int64, scores [nq,k] float64, rows [nq,k] int64);
+    empty places: -1, -inf (inner product) or +inf (L2), -1."""
+    nq = len(rows)
+    n = np.asarray(vectors).shape[0]
+    out_i = np.full((nq, k), -1, np.int64)
+    out_s = np.full((nq, k), np.inf if metric == L2 else -np.inf, np.float64)
+    out_r = np.full((nq, k), -1, np.int64)
+    for q in range(nq):
+        r = np.unique(np.asarray(rows[q], np.int64))
+        r = r[(r >= 0) & (r < n)]
+        if r.size == 0:
+            continue
+        sc = pair_scores(queries, vectors, dtype, metric, np.full(r.size, q), r)
+        lab = np.asarray(ids)[r].astype(np.int64) if ids is not None else r
+        order = np.lexsort((lab, sc if metric == L2 else -sc))[:k]
+        out_i[q, :order.size] = lab[order]
+        out_s[q, :order.size] = sc[order]
+        out_r[q, :order.size] = r[order]
+    return out_i, out_s, out_r
+
+
+def lists_of_rows(rows, offsets):
+    """The list each row belongs to: the l with offsets[l] <= row < offsets[l+1]; -1 for rows
+    outside the index.  (H_v of Section 4.3: the clusters that held the results of v.)"""
+    rows = np.asarray(rows, np.int64)
+    off = np.asarray(offsets, np.int64)
+    out = np.searchsorted(off, rows, side="right") - 1
+    out[(rows < 0) | (rows >= off[-1])] = -1
+    return out.astype(np.int64)
+
+
+def reorder_probes(probe, prev, hot):
+    """Search order of the new probe lists C' (Section 4.3 of the paper): first the lists of C'
+    that are in H_v (``hot``), then those in (C - H_v) (``prev`` without ``hot``), then the
+    remaining ones; inside each group the given order stays.  Entries < 0 are "no list": they
+    go last, and are ignored in ``prev`` and ``hot``.  Plain Python, query by query."""
+    probe = np.asarray(probe)
+    out = np.empty_like(probe)
+    for q in range(probe.shape[0]):
+        h = set(int(x) for x in (hot[q] if hot is not None else []) if x >= 0)
+        c = set(int(x) for x in (prev[q] if prev is not None else []) if x >= 0)
+        row = [int(x) for x in probe[q]]
+        first = [l for l in row if l >= 0 and l in h]
+        second = [l for l in row if l >= 0 and l not in h and l in c]
+        rest = [l for l in row if l >= 0 and l not in h and l not in c]
+        absent = [l for l in row if l < 0]
+        out[q] = first + second + rest + absent
+    return out
+
+
 def ivf_search(queries, centroids, offsets, vectors, dtype, ids, nprobe, k, metric):
     """Whole search.  Returns (probe_ids, ids, scores)."""
     q = _as(queries, np.float32)

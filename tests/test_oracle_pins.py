@@ -309,3 +309,80 @@ def test_merge_of_two_partial_scans_is_the_scan_of_the_union():
             m_i, m_s = oracle.merge_topk(a_i, a_s, b_i, b_s, k, metric)
             assert np.array_equal(m_i, whole_i)
             assert np.array_equal(m_s, whole_s)
+
+
+# ---------------------------------------------------------------- reuse of the previous retrieval (Section 4.3)
+def test_topk_of_rows_reduces_to_scan_and_to_bruteforce():
+    """The k best of a set of rows: over the rows of the probed lists it is the scan, over all
+    rows the exhaustive search (both are the C routines pinned above); rows named twice, -1 and
+    rows past the end change nothing."""
+    rng = np.random.default_rng(5)
+    n, d, nlist, nq = 700, 20, 25, 30
+    x = rng.standard_normal((n, d)).astype(np.float32)
+    x[50:80] = x[10:40]                                      # equal scores, decided by id
+    off = np.sort(np.concatenate([[0, n], rng.integers(0, n + 1, nlist - 1)])).astype(np.int64)
+    ids = rng.permutation(n).astype(np.int64) * 3 + 1
+    q = rng.standard_normal((nq, d)).astype(np.float32)
+    probe = np.stack([rng.permutation(nlist)[:9] for _ in range(nq)]).astype(np.int32)
+    rows = [np.concatenate([np.arange(off[l], off[l + 1]) for l in probe[i]]) for i in range(nq)]
+    noisy = [np.concatenate([r, r[::3], [-1, -7, n, n + 5]]) for r in rows]
+    for metric in (oracle.IP, oracle.L2):
+        for k in (1, 10, 200):
+            s_i, s_s = oracle.scan(q, off, x, "f32", ids, probe, k, metric)
+            t_i, t_s, t_r = oracle.topk_of_rows(q, x, "f32", ids, rows, k, metric)
+            assert np.array_equal(t_i, s_i) and np.allclose(t_s, s_s, rtol=0, atol=1e-12)
+            assert np.array_equal(ids[t_r[t_r >= 0]], t_i[t_i >= 0])
+            u_i, u_s, _ = oracle.topk_of_rows(q, x, "f32", ids, noisy, k, metric)
+            assert np.array_equal(u_i, s_i) and np.array_equal(u_s, t_s)
+            b_i, b_s = oracle.bruteforce(q, x, "f32", ids, k, metric)
+            a_i, a_s, _ = oracle.topk_of_rows(q, x, "f32", ids, [np.arange(n)] * nq, k, metric)
+            assert np.array_equal(a_i, b_i) and np.allclose(a_s, b_s, rtol=0, atol=1e-12)
+    e_i, e_s, e_r = oracle.topk_of_rows(q[:1], x, "f32", ids, [[-1]], 3, oracle.L2)
+    assert (e_i == -1).all() and np.isinf(e_s).all() and (e_r == -1).all()
+
+
+def test_lists_of_rows_against_a_walk_over_the_lists():
+    off = np.array([0, 0, 4, 4, 4, 9, 10, 10], np.int64)      # empty lists at both ends and inside
+    want = {}
+    for l in range(len(off) - 1):
+        for r in range(off[l], off[l + 1]):
+            want[r] = l
+    rows = np.array([-3, -1] + list(range(0, 12)), np.int64)
+    got = oracle.lists_of_rows(rows, off)
+    assert got.tolist() == [want.get(int(r), -1) for r in rows]
+
+
+def test_reorder_probes_worked_example_and_invariants():
+    """The three groups of Section 4.3 on an example worked by hand (tests/golden), and on
+    random inputs: the output is the input rearranged, groups in order, given order kept inside
+    each group (checked with numpy set operations, not with the oracle's own loops)."""
+    path = os.path.join(os.path.dirname(__file__), "golden", "reorder_worked_example.txt")
+    vals = {}
+    for line in open(path):
+        line = line.split("#")[0].strip()
+        if line:
+            key, _, rest = line.partition(":")
+            vals[key.strip()] = np.array([int(t) for t in rest.split()], np.int32)
+    got = oracle.reorder_probes(vals["probe"][None], vals["prev"][None], vals["hot"][None])
+    assert got[0].tolist() == vals["order"].tolist()
+    # no history at all: nothing moves (except absent entries, which go last)
+    assert oracle.reorder_probes(vals["probe"][None], None, None)[0].tolist() == \
+        [int(x) for x in vals["probe"] if x >= 0] + [-1] * int((vals["probe"] < 0).sum())
+
+    rng = np.random.default_rng(8)
+    nq, nlist = 50, 90
+    probe = np.stack([rng.permutation(nlist)[:40] for _ in range(nq)]).astype(np.int32)
+    probe[rng.random(probe.shape) < 0.1] = -1
+    prev = np.stack([rng.permutation(nlist)[:30] for _ in range(nq)]).astype(np.int32)
+    prev[rng.random(prev.shape) < 0.1] = -1
+    hot = rng.integers(-1, nlist, (nq, 7)).astype(np.int32)    # with repeats
+    out = oracle.reorder_probes(probe, prev, hot)
+    for i in range(nq):
+        assert sorted(out[i].tolist()) == sorted(probe[i].tolist())
+        group = np.where(out[i] < 0, 3, np.where(np.isin(out[i], hot[i][hot[i] >= 0]), 0,
+                                                 np.where(np.isin(out[i], prev[i][prev[i] >= 0]), 1, 2)))
+        assert (np.diff(group) >= 0).all()
+        pos = {int(l): j for j, l in enumerate(probe[i]) if l >= 0}
+        for gno in range(3):
+            members = [pos[int(l)] for l in out[i][group == gno]]
+            assert members == sorted(members)
