@@ -97,6 +97,74 @@ def bench_substages(args, cfg, hr, ix, rounds, metric):
                                              f"{per} lists, k={cfg.k}", "rows_identical_to_one_call": same}}))
 
 
+def bench_reuse(args, cfg, hr, ix, rounds, metric):
+    """Consecutive retrievals of the same requests (the rounds of the workload: every query drifts a
+    little from round to round).  Each retrieval searches its probe lists in `reuse` sub-stages with a
+    carried top-20.  Two ways: lists in rank order from an empty result; or started from the 20 cached
+    rows of the previous round, lists in the order hot / probed before / rest.  Reported: after how
+    many sub-stages the final top-k is in place on average (the search could have stopped there), and
+    the time of a whole retrieval."""
+    import torch
+    nq, S, k, big = cfg.nq, args.reuse, cfg.k, max(20, cfg.k)
+    per = (cfg.nprobe + S - 1) // S
+    nst = (cfg.nprobe + per - 1) // per
+    R = len(rounds)
+
+    def retrieval(q, prev, use, record):
+        """prev = (probe, state) of the previous round or None; returns (probe, state, ids after every sub-stage)"""
+        probe, _ = ix.coarse(q, cfg.nprobe, cfg.metric)
+        if use and prev is not None:
+            hot = ix.lists_of_rows(prev[1][2][:, :k])
+            order = hr.reorder_probes(probe, prev[0], hot)
+            state = ix.rescore(q, prev[1][2], big, cfg.metric)
+        else:
+            order = probe
+            state = ix.new_state_rows(nq, big)
+        seen = [state[0][:, :k].clone()] if record else None          # (before any list: what the cache alone gives)
+        for j in range(nst):
+            ix.scan_step_rows(q, order[:, j * per:(j + 1) * per].contiguous(), state, cfg.metric)
+            if record:
+                seen.append(state[0][:, :k].clone())
+        return probe, state, seen
+
+    out = {}
+    for use in (False, True):
+        # how early the final result is in place (untimed pass)
+        prev, stages = None, []
+        for r in range(R):
+            probe, state, seen = retrieval(rounds[r], prev, use, True)
+            if r > 0:
+                final = seen[-1]
+                first = torch.full((nq,), nst, dtype=torch.int64, device="cuda")
+                for j in range(nst, -1, -1):
+                    first = torch.where((seen[j] == final).all(1), torch.full_like(first, j), first)
+                # (sub-stages are counted from 1; 0 = the cached rows already were the answer)
+                stages.append(first.float().mean().item())
+            prev = (probe, state)
+        # time of whole retrievals, rounds 1..R-1
+        def one_pass():
+            prev = None
+            for r in range(R):
+                probe, state, _ = retrieval(rounds[r], prev, use, False)
+                prev = (probe, state)
+        for _ in range(max(1, args.warmup // 2)):
+            one_pass()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            one_pass()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) / (args.steps * R) * 1e3
+        out["reuse" if use else "plain"] = {"substages_until_final_mean": sum(stages) / len(stages), "ms_per_retrieval": ms}
+    ix.close()
+    a, b = out["plain"]["substages_until_final_mean"], out["reuse"]["substages_until_final_mean"]
+    print(json.dumps({"metric": "sub-stages until the final top-k is in place (of %d)" % nst, "value": b, "unit": "sub-stages",
+                      "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "higher_is_better": False, "data": "synthetic",
+                      "config": {"workload": f"{cfg.name}: nq={nq}, nprobe={cfg.nprobe} in {nst} sub-stages of {per} lists, "
+                                             f"k={k}, top-{big} carried and cached, {R} rounds, noise {cfg.noise}, drift {cfg.drift}"},
+                      "plain_order": out["plain"], "cache_and_reordering": out["reuse"], "reduction": 1.0 - b / a if a > 0 else 0.0}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -109,6 +177,11 @@ def main():
     ap.add_argument("--substages", type=int, default=0,
                     help="extra mode: one step = coarse + this many hr_ivf_scan_step calls over slices of the probe "
                          "lists, result carried along (the step-wise interface); prints its own JSON line")
+    ap.add_argument("--reuse", type=int, default=0,
+                    help="extra mode (workloads with several rounds, e.g. C4): retrievals in this many sub-stages, with and "
+                         "without the cache of the previous round and the reordering of the probe lists; prints its own JSON line")
+    ap.add_argument("--noise", type=float, default=0.0, help="spread of vectors and queries around their centroid instead of the workload's own")
+    ap.add_argument("--drift", type=float, default=0.0, help="step of a query from round to round instead of the workload's own")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
@@ -122,6 +195,10 @@ def main():
         cfg = synth.scaled(cfg, nq=args.nq)
     if args.nprobe > 0:
         cfg = synth.scaled(cfg, nprobe=args.nprobe)
+    if args.noise > 0:
+        cfg = synth.scaled(cfg, noise=args.noise)
+    if args.drift > 0:
+        cfg = synth.scaled(cfg, drift=args.drift)
     torch.cuda.set_device(0)
     idx = synth.make_index(cfg, "cuda")
     rounds = synth.make_queries(cfg, idx)
@@ -134,6 +211,8 @@ def main():
 
     if args.substages > 0:
         return bench_substages(args, cfg, hr, ix, rounds, metric)
+    if args.reuse > 0:
+        return bench_reuse(args, cfg, hr, ix, rounds, metric)
 
     def step(i):
         q = rounds[i % len(rounds)]

@@ -139,6 +139,60 @@ int hr_ivf_scan_step(const hr_ivf_index* index, const float* queries, int64_t nq
                      void* stream);
 
 /*
+ * Reuse of a request's previous retrieval (Section 4.3: consecutive queries v, v' of a request are
+ * close; the results of v' tend to lie among a larger top-k of v, in the clusters H_v that held
+ * v's results, and in clusters probed for both).  Four calls; each only enqueues kernels.
+ *
+ * hr_ivf_scan_step_rows — hr_ivf_scan_step whose carried result also holds the row number of
+ * every entry:
+ *   io_rows  DEV [nq, k] int32: position of the entry's vector in list_vectors, -1 for an empty
+ *            place; updated in place with the ids and scores.
+ * Rows tell where a result lies (hr_ivf_lists_of_rows) and let it be scored again for another
+ * query (hr_ivf_rescore).  A vector of a probed list whose row the carried result already
+ * holds is not taken again, so a carried result may come from hr_ivf_rescore and its rows'
+ * lists may be probed afterwards.  (A list probed in two steps is still the caller's error.)
+ */
+int hr_ivf_scan_step_rows(const hr_ivf_index* index, const float* queries, int64_t nq,
+                          const int32_t* probe_ids, int32_t nprobe, int32_t k, int32_t metric,
+                          int64_t* io_ids, float* io_scores, int32_t* io_rows, void* workspace,
+                          size_t workspace_bytes, void* stream);
+
+/*
+ * hr_ivf_rescore — the local cache: the m rows a request kept from its previous retrieval (the
+ * paper keeps the 20 best) are scored for its new query and the k best of them become the
+ * starting result of the new retrieval.
+ *   rows        DEV [nq, m] int32 row numbers, 1 <= m <= HR_K_MAX; < 0 or >= N: no row; a row
+ *               listed twice counts once.
+ *   out_ids, out_scores, out_rows   DEV [nq, k]: the k best by (score, id), best first, empty
+ *               places last (-1, +-inf, -1): the form hr_ivf_scan_step_rows carries.
+ * Scores as in the search (query rounded as the list scan rounds it, float32 sums).
+ */
+int hr_ivf_rescore(const hr_ivf_index* index, const float* queries, int64_t nq, const int32_t* rows,
+                   int32_t m, int32_t k, int32_t metric, int64_t* out_ids, float* out_scores,
+                   int32_t* out_rows, void* stream);
+
+/*
+ * hr_ivf_lists_of_rows — the list every row belongs to (for H_v: the clusters that held the
+ * results of v).   rows DEV [n] int32;  out_lists DEV [n] int32, -1 for rows < 0 or >= N.
+ */
+int hr_ivf_lists_of_rows(const hr_ivf_index* index, const int32_t* rows, int64_t n, int32_t* out_lists,
+                         void* stream);
+
+/*
+ * hr_ivf_reorder_probes — search order of the new probe lists C' of every query: first the
+ * lists that are in hot (H_v), then those in prev (C, the lists probed for v) that are not in
+ * hot, then the others; inside each group the given order is kept; entries < 0 go last.
+ *   probe      DEV [nq, nprobe] int32, 1 <= nprobe <= HR_NPROBE_MAX
+ *   prev       DEV [nq, nprev] int32 or NULL, nprev <= HR_NPROBE_MAX   (entries < 0 ignored)
+ *   hot        DEV [nq, nhot] int32 or NULL, nhot <= HR_K_MAX          (entries < 0 ignored)
+ *   out_probe  DEV [nq, nprobe] int32, must not overlap probe
+ * Needs no index: list numbers are only compared.
+ */
+int hr_ivf_reorder_probes(const int32_t* probe, int64_t nq, int32_t nprobe, const int32_t* prev,
+                          int32_t nprev, const int32_t* hot, int32_t nhot, int32_t* out_probe,
+                          void* stream);
+
+/*
  * hr_ivf_list_hits — how often every list has been probed by hr_ivf_search / hr_ivf_scan /
  * hr_ivf_scan_step calls on this index since it was loaded or since the last reset: the
  * per-cluster access frequency that a cache of hot clusters is driven by (Section 4.4: the

@@ -44,6 +44,10 @@ def _load_lib():
     L.hr_ivf_scan.argtypes = [p, p, c.c_int64, p, c.c_int32, c.c_int32, c.c_int32, p, p, p, c.c_size_t, p]
     L.hr_ivf_list_hits.argtypes = [p, p, c.c_int32, p]
     L.hr_ivf_scan_step.argtypes = [p, p, c.c_int64, p, c.c_int32, c.c_int32, c.c_int32, p, p, p, c.c_size_t, p]
+    L.hr_ivf_scan_step_rows.argtypes = [p, p, c.c_int64, p, c.c_int32, c.c_int32, c.c_int32, p, p, p, p, c.c_size_t, p]
+    L.hr_ivf_rescore.argtypes = [p, p, c.c_int64, p, c.c_int32, c.c_int32, c.c_int32, p, p, p, p]
+    L.hr_ivf_lists_of_rows.argtypes = [p, p, c.c_int64, p, p]
+    L.hr_ivf_reorder_probes.argtypes = [p, c.c_int64, c.c_int32, p, c.c_int32, p, c.c_int32, p, p]
     L.hr_ivf_stats.argtypes = [p, p, c.c_size_t, c.c_int64, c.c_int32, c.c_int32, c.POINTER(c.c_int64)]
     L.hr_ivf_profile_begin.argtypes = [p, c.c_int32]
     L.hr_ivf_profile_end.argtypes = [p, c.POINTER(c.c_int32), c.POINTER(c.c_double)]
@@ -125,6 +129,28 @@ def hr_ivf_scan_step(handle, queries, nq, probe_ids, nprobe, k, metric, io_ids, 
     _check(lib.hr_ivf_scan_step(handle, _addr(queries), nq, _addr(probe_ids), nprobe, k, metric,
                                 _addr(io_ids), _addr(io_scores), _addr(workspace), workspace_bytes,
                                 _stream(stream)))
+
+
+def hr_ivf_scan_step_rows(handle, queries, nq, probe_ids, nprobe, k, metric, io_ids, io_scores, io_rows, workspace,
+                          workspace_bytes, stream=None):
+    _check(lib.hr_ivf_scan_step_rows(handle, _addr(queries), nq, _addr(probe_ids), nprobe, k, metric,
+                                     _addr(io_ids), _addr(io_scores), _addr(io_rows), _addr(workspace),
+                                     workspace_bytes, _stream(stream)))
+
+
+def hr_ivf_rescore(handle, queries, nq, rows, m, k, metric, out_ids, out_scores, out_rows, stream=None):
+    _check(lib.hr_ivf_rescore(handle, _addr(queries), nq, _addr(rows), m, k, metric, _addr(out_ids),
+                              _addr(out_scores), _addr(out_rows), _stream(stream)))
+
+
+def hr_ivf_lists_of_rows(handle, rows, n, out_lists, stream=None):
+    _check(lib.hr_ivf_lists_of_rows(handle, _addr(rows), n, _addr(out_lists), _stream(stream)))
+
+
+def hr_ivf_reorder_probes(probe, nq, nprobe, prev, nprev, hot, nhot, out_probe, stream=None):
+    _check(lib.hr_ivf_reorder_probes(_addr(probe), nq, nprobe, _addr(prev) if prev is not None else None, nprev,
+                                     _addr(hot) if hot is not None else None, nhot, _addr(out_probe),
+                                     _stream(stream)))
 
 
 def hr_ivf_list_hits(handle, out_hits, reset=False, stream=None):
@@ -218,6 +244,10 @@ class IvfIndex:
         return (torch.full((nq, k), -1, dtype=torch.int64, device=device),
                 torch.zeros(nq, k, dtype=torch.float32, device=device))
 
+    def new_state_rows(self, nq, k, device="cuda"):
+        """An empty carried result with row numbers, for scan_step_rows."""
+        return self.new_state(nq, k, device) + (torch.full((nq, k), -1, dtype=torch.int32, device=device),)
+
     def scan_step(self, queries, probe_ids, state, metric="ip"):
         """One sub-stage: merges the lists in probe_ids into the carried result (ids, scores), in place."""
         q = queries.contiguous()
@@ -229,6 +259,34 @@ class IvfIndex:
         hr_ivf_scan_step(self.handle, q, nq, pr, nprobe, k, _METRIC[metric], ids, scores, ws, ws.numel())
         return ids, scores
 
+    def scan_step_rows(self, queries, probe_ids, state, metric="ip"):
+        """scan_step on a carried result (ids, scores, rows) that also holds the row number of every entry."""
+        q = queries.contiguous()
+        pr = probe_ids.to(torch.int32).contiguous()
+        nq, nprobe = pr.shape
+        ids, scores, rows = state
+        k = ids.shape[1]
+        ws = self.workspace(nq, nprobe, k)
+        hr_ivf_scan_step_rows(self.handle, q, nq, pr, nprobe, k, _METRIC[metric], ids, scores, rows, ws, ws.numel())
+        return ids, scores, rows
+
+    def rescore(self, queries, rows, k, metric="ip"):
+        """The k best of the given rows [nq, m] for the queries: a carried result (ids, scores, rows)."""
+        q = queries.contiguous()
+        r = rows.to(torch.int32).contiguous()
+        nq, m = r.shape
+        ids = torch.empty(nq, k, dtype=torch.int64, device=q.device)
+        scores = torch.empty(nq, k, dtype=torch.float32, device=q.device)
+        out_rows = torch.empty(nq, k, dtype=torch.int32, device=q.device)
+        hr_ivf_rescore(self.handle, q, nq, r, m, k, _METRIC[metric], ids, scores, out_rows)
+        return ids, scores, out_rows
+
+    def lists_of_rows(self, rows):
+        r = rows.to(torch.int32).contiguous()
+        out = torch.empty_like(r)
+        hr_ivf_lists_of_rows(self.handle, r, r.numel(), out)
+        return out
+
     def list_hits(self, reset=False):
         """Probes per list since load / the last reset: int64 [nlist] on the device."""
         out = torch.empty(self.nlist, dtype=torch.int64, device="cuda")
@@ -238,3 +296,15 @@ class IvfIndex:
     def stats(self, nq, nprobe, k):
         ws = self.workspace(nq, nprobe, k)
         return hr_ivf_stats(self.handle, ws, ws.numel(), nq, nprobe, k)
+
+
+def reorder_probes(probe, prev=None, hot=None):
+    """Search order of the probe lists [nq, nprobe]: lists in hot first, then those in prev, then the rest."""
+    pr = probe.to(torch.int32).contiguous()
+    nq, nprobe = pr.shape
+    pv = prev.to(torch.int32).contiguous() if prev is not None else None
+    ht = hot.to(torch.int32).contiguous() if hot is not None else None
+    out = torch.empty_like(pr)
+    hr_ivf_reorder_probes(pr, nq, nprobe, pv, pv.shape[1] if pv is not None else 0, ht,
+                          ht.shape[1] if ht is not None else 0, out)
+    return out

@@ -457,7 +457,7 @@ static int enqueue_coarse(const hr_ivf_index* ix, const Plan& p, char* ws, int64
 // grouping by list + cluster-major scan + per-query merge
 static int enqueue_scan(const hr_ivf_index* ix, const Plan& p, char* ws, int64_t nq, const int32_t* probe,
                         int nprobe, int k, int metric, int64_t* out_ids, float* out_scores, hipStream_t s,
-                        bool carried = false)
+                        bool carried = false, int32_t* io_rows = nullptr)
 {
     if (p.shape_s < 0)
         return fail(HR_ERR_UNSUPPORTED, "list scan does not fit in LDS (d=%d, k=%d)", ix->d, k);
@@ -542,6 +542,7 @@ static int enqueue_scan(const hr_ivf_index* ix, const Plan& p, char* ws, int64_t
     m.nq = (int)nq; m.nprobe = nprobe; m.nlist = (int)ix->nlist; m.k = k; m.cw = p.cw_s; m.l2 = a.l2;
     m.out_ids = out_ids; m.out_scores = out_scores;
     m.carried = carried ? 1 : 0;
+    m.io_rows = io_rows;
     HR_HIP(launch_merge(m, s));
     return HR_OK;
 }
@@ -607,8 +608,8 @@ int hr_ivf_scan(const hr_ivf_index* ix, const float* queries, int64_t nq, const 
     return enqueue_scan(ix, p, ws, nq, probe_ids, nprobe, k, metric, out_ids, out_scores, s);
 }
 
-int hr_ivf_scan_step(const hr_ivf_index* ix, const float* queries, int64_t nq, const int32_t* probe_ids,
-                     int32_t nprobe, int32_t k, int32_t metric, int64_t* io_ids, float* io_scores,
+static int scan_step(const hr_ivf_index* ix, const float* queries, int64_t nq, const int32_t* probe_ids,
+                     int32_t nprobe, int32_t k, int32_t metric, int64_t* io_ids, float* io_scores, int32_t* io_rows,
                      void* workspace, size_t workspace_bytes, void* stream)
 {
     if (int rc = check_index(ix)) return rc;
@@ -625,7 +626,63 @@ int hr_ivf_scan_step(const hr_ivf_index* ix, const float* queries, int64_t nq, c
     const bool f32 = ix->dtype == HR_F32;
     HR_HIP(launch_prep_queries(queries, nq, ix->d, ix->dtype, f32 ? ws + p.o_qop_c : nullptr, nullptr,
                                f32 ? nullptr : ws + p.o_qop_s, (float*)(ws + p.o_qnorm_s), s));
-    return enqueue_scan(ix, p, ws, nq, probe_ids, nprobe, k, metric, io_ids, io_scores, s, true);
+    return enqueue_scan(ix, p, ws, nq, probe_ids, nprobe, k, metric, io_ids, io_scores, s, true, io_rows);
+}
+
+int hr_ivf_scan_step(const hr_ivf_index* ix, const float* queries, int64_t nq, const int32_t* probe_ids,
+                     int32_t nprobe, int32_t k, int32_t metric, int64_t* io_ids, float* io_scores,
+                     void* workspace, size_t workspace_bytes, void* stream)
+{
+    return scan_step(ix, queries, nq, probe_ids, nprobe, k, metric, io_ids, io_scores, nullptr, workspace, workspace_bytes, stream);
+}
+
+int hr_ivf_scan_step_rows(const hr_ivf_index* ix, const float* queries, int64_t nq, const int32_t* probe_ids,
+                          int32_t nprobe, int32_t k, int32_t metric, int64_t* io_ids, float* io_scores,
+                          int32_t* io_rows, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (int rc = check_index(ix)) return rc;
+    if (nq > 0 && !io_rows) return fail(HR_ERR_ARG, "io_rows is null");
+    return scan_step(ix, queries, nq, probe_ids, nprobe, k, metric, io_ids, io_scores, io_rows, workspace, workspace_bytes, stream);
+}
+
+int hr_ivf_rescore(const hr_ivf_index* ix, const float* queries, int64_t nq, const int32_t* rows, int32_t m,
+                   int32_t k, int32_t metric, int64_t* out_ids, float* out_scores, int32_t* out_rows, void* stream)
+{
+    if (int rc = check_index(ix)) return rc;
+    if (nq < 0 || nq > (1 << 24)) return fail(HR_ERR_ARG, "nq=%lld out of range", (long long)nq);
+    if (m < 1 || m > HR_K_MAX) return fail(HR_ERR_ARG, "m=%d must be in 1..%d", m, HR_K_MAX);
+    if (k < 1 || k > HR_K_MAX) return fail(HR_ERR_ARG, "k=%d must be in 1..%d", k, HR_K_MAX);
+    if (metric != HR_METRIC_IP && metric != HR_METRIC_L2) return fail(HR_ERR_ARG, "unknown metric %d", metric);
+    if (nq == 0) return HR_OK;
+    if (!queries || !rows || !out_ids || !out_scores || !out_rows) return fail(HR_ERR_ARG, "queries / rows / outputs null");
+    HR_HIP(launch_rescore(queries, nq, ix->d, ix->dtype, ix->vectors, ix->d_row_norm, ix->ids, ix->N, rows, m, k,
+                          metric == HR_METRIC_L2, out_ids, out_scores, out_rows, (hipStream_t)stream));
+    return HR_OK;
+}
+
+int hr_ivf_lists_of_rows(const hr_ivf_index* ix, const int32_t* rows, int64_t n, int32_t* out_lists, void* stream)
+{
+    if (int rc = check_index(ix)) return rc;
+    if (n < 0) return fail(HR_ERR_ARG, "n=%lld is negative", (long long)n);
+    if (n == 0) return HR_OK;
+    if (!rows || !out_lists) return fail(HR_ERR_ARG, "rows / out_lists null");
+    HR_HIP(launch_lists_of_rows(rows, n, ix->d_list_off, (int)ix->nlist, out_lists, (hipStream_t)stream));
+    return HR_OK;
+}
+
+int hr_ivf_reorder_probes(const int32_t* probe, int64_t nq, int32_t nprobe, const int32_t* prev, int32_t nprev,
+                          const int32_t* hot, int32_t nhot, int32_t* out_probe, void* stream)
+{
+    if (nq < 0 || nq > (1 << 24)) return fail(HR_ERR_ARG, "nq=%lld out of range", (long long)nq);
+    if (nprobe < 1 || nprobe > HR_NPROBE_MAX) return fail(HR_ERR_ARG, "nprobe=%d must be in 1..%d", nprobe, HR_NPROBE_MAX);
+    if (nprev < 0 || nprev > HR_NPROBE_MAX) return fail(HR_ERR_ARG, "nprev=%d must be in 0..%d", nprev, HR_NPROBE_MAX);
+    if (nhot < 0 || nhot > HR_K_MAX) return fail(HR_ERR_ARG, "nhot=%d must be in 0..%d", nhot, HR_K_MAX);
+    if (nq == 0) return HR_OK;
+    if (!probe || !out_probe) return fail(HR_ERR_ARG, "probe / out_probe null");
+    if (probe == out_probe) return fail(HR_ERR_ARG, "out_probe must not be probe");
+    HR_HIP(launch_reorder_probes(probe, nprobe, nprev > 0 ? prev : nullptr, nprev, nhot > 0 ? hot : nullptr, nhot, nq,
+                                 out_probe, (hipStream_t)stream));
+    return HR_OK;
 }
 
 int hr_ivf_list_hits(const hr_ivf_index* ix, int64_t* out_hits, int32_t reset, void* stream)

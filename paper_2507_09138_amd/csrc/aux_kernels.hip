@@ -388,10 +388,12 @@ __global__ __launch_bounds__(256) void k_merge(MergeArgs a)
     __shared__ int s_cnt[4];
     __shared__ int64_t s_ext_id[4][HR_K_MAX];
     __shared__ float s_ext_score[4][HR_K_MAX];
+    __shared__ int s_ext_row[4][HR_K_MAX];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int64_t q = (int64_t)blockIdx.x * 4 + wave;
     if (q >= a.nq) return;                       // whole wave leaves; no block barrier below
     int64_t* ext_id = s_ext_id[wave];
+    int* ext_row = s_ext_row[wave];              // rows of the carried entries (-1: empty place or rows not carried)
     float* ext_score = s_ext_score[wave];
     Cand* buf = s_buf[wave];
     int64_t* tie = s_tie[wave];
@@ -436,6 +438,7 @@ __global__ __launch_bounds__(256) void k_merge(MergeArgs a)
             const int64_t id = j < k ? a.out_ids[(size_t)q * k + j] : -1;
             const bool have = id >= 0;
             const unsigned long long m = __builtin_amdgcn_ballot_w64(have);
+            if (j < k) ext_row[j] = (have && a.io_rows) ? a.io_rows[(size_t)q * k + j] : -1;
             if (have) {
                 const float sc = a.out_scores[(size_t)q * k + j];
                 ext_id[j] = id;
@@ -477,7 +480,12 @@ __global__ __launch_bounds__(256) void k_merge(MergeArgs a)
         for (int j = 0; j < maxc; j++) {
             if (j < c) {
                 Cand cd = a.slot_ent[slot * a.slot_stride + j];
-                if (cd.key >= thr) {
+                bool take = cd.key >= thr;
+                // a row the carried result already holds (it came from a cache of earlier results
+                // and its list is scanned now) is not taken a second time
+                if (take && a.io_rows && a.carried)
+                    for (int t = 0; t < k; t++) take = take && ext_row[t] != (int)cd.row;
+                if (take) {
                     int pos = atomicAdd(&s_cnt[wave], 1);
                     buf[pos] = cd;
                 }
@@ -530,12 +538,14 @@ __global__ __launch_bounds__(256) void k_merge(MergeArgs a)
             size_t o = (size_t)q * k + pos[m];
             if (a.out_ids) a.out_ids[o] = id[m];
             if (a.out_scores) a.out_scores[o] = score;
+            if (a.io_rows) a.io_rows[o] = (e[m].row & kCarried) ? ext_row[e[m].row & ~kCarried] : (int)e[m].row;
         }
     }
     for (int idx = n + lane; idx < k; idx += 64) {     // fewer than k candidates: pad
         size_t o = (size_t)q * k + idx;
         if (a.out_ids) a.out_ids[o] = -1;
         if (a.out_scores) a.out_scores[o] = a.l2 ? __builtin_inff() : -__builtin_inff();
+        if (a.io_rows) a.io_rows[o] = -1;
     }
 }
 
@@ -662,6 +672,236 @@ hipError_t launch_topk_rows(const float* keys, const float* qnorm, int32_t* out_
     if (nq <= 0) return hipSuccess;
     TopkArgs a{keys, qnorm, out_ids, out_scores, (int)nq, n, k, l2};
     hipLaunchKernelGGL(k_topk_rows, dim3((unsigned)((nq + 3) / 4)), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// Reuse of the previous retrieval of a request (Section 4.3 of the paper: consecutive queries
+// v, v' of a request are close, so the results of v' tend to lie among a larger top-k of v, in
+// the clusters H_v that held v's results, and in clusters probed both times).
+
+// List of every given row (binary search in the row offsets); -1 for rows outside the index.
+__global__ void k_lists_of_rows(const int32_t* rows, int64_t n, const int* list_off, int nlist, int32_t* out)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const int r = rows[i];
+    int res = -1;
+    if (r >= 0 && r < list_off[nlist]) {
+        int lo = 0, hi = nlist;                 // largest l with list_off[l] <= r (lists may be empty)
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (list_off[mid] <= r) lo = mid; else hi = mid;
+        }
+        res = lo;
+    }
+    out[i] = res;
+}
+
+hipError_t launch_lists_of_rows(const int32_t* rows, int64_t n, const int* list_off, int nlist, int32_t* out, hipStream_t s)
+{
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_lists_of_rows, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, rows, n, list_off, nlist, out);
+    return hipGetLastError();
+}
+
+// Search order of the new probe lists C' of every query: first those in H_v, then those of
+// the previous probe lists C that are not in H_v, then the rest, each group in its given
+// (rank) order; absent entries (-1) last.  One wave per query.
+struct ReorderArgs {
+    const int32_t* probe;       // [nq, np]
+    const int32_t* prev;        // [nq, pp] or nullptr
+    const int32_t* hot;         // [nq, nh] or nullptr
+    int32_t* out;               // [nq, np]
+    int nq, np, pp, nh;
+};
+
+__global__ __launch_bounds__(256) void k_reorder_probes(ReorderArgs a)
+{
+    __shared__ int s_prev[4][HR_NPROBE_MAX];
+    __shared__ int s_hot[4][HR_K_MAX];
+    __shared__ unsigned char s_cls[4][HR_NPROBE_MAX];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int64_t q = (int64_t)blockIdx.x * 4 + wave;
+    if (q >= a.nq) return;
+    int* prev = s_prev[wave];
+    int* hot = s_hot[wave];
+    unsigned char* cls = s_cls[wave];
+    for (int i = lane; i < a.pp; i += 64) prev[i] = a.prev[q * a.pp + i];
+    for (int i = lane; i < a.nh; i += 64) hot[i] = a.hot[q * a.nh + i];
+    wave_sync();
+    int count[4] = {0, 0, 0, 0};                // entries per group (whole wave holds the same values)
+    for (int i0 = 0; i0 < a.np; i0 += 64) {
+        const int i = i0 + lane;
+        int c = 4;                              // (past the end)
+        if (i < a.np) {
+            const int l = a.probe[q * a.np + i];
+            c = 3;
+            if (l >= 0) {
+                c = 2;
+                for (int t = 0; t < a.pp; t++) if (prev[t] == l) { c = 1; break; }
+                for (int t = 0; t < a.nh; t++) if (hot[t] == l) { c = 0; break; }
+            }
+            cls[i] = (unsigned char)c;
+        }
+#pragma unroll
+        for (int g = 0; g < 4; g++) count[g] += __builtin_popcountll(__builtin_amdgcn_ballot_w64(c == g));
+    }
+    wave_sync();
+    int base[4] = {0, count[0], count[0] + count[1], count[0] + count[1] + count[2]};
+    for (int i0 = 0; i0 < a.np; i0 += 64) {
+        const int i = i0 + lane;
+        const int c = i < a.np ? cls[i] : 4;
+#pragma unroll
+        for (int g = 0; g < 4; g++) {
+            const unsigned long long m = __builtin_amdgcn_ballot_w64(c == g);
+            if (c == g) a.out[q * a.np + base[g] + lanes_below(m)] = a.probe[q * a.np + i];
+            base[g] += __builtin_popcountll(m);
+        }
+    }
+}
+
+hipError_t launch_reorder_probes(const int32_t* probe, int np, const int32_t* prev, int pp, const int32_t* hot, int nh,
+                                 int64_t nq, int32_t* out, hipStream_t s)
+{
+    if (nq <= 0) return hipSuccess;
+    ReorderArgs a{probe, prev, hot, out, (int)nq, np, prev ? pp : 0, hot ? nh : 0};
+    hipLaunchKernelGGL(k_reorder_probes, dim3((unsigned)((nq + 3) / 4)), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+// The local cache of a request: the rows a previous retrieval returned (a larger top-k of v)
+// are scored against the new query v' and the k best become the starting result of v's
+// successor.  One wave per query, 16 lanes per row (four rows at a time); the query is rounded
+// as the scan's operand is (binary16 for binary16 lists, bfloat16 hi + lo for bfloat16 lists),
+// products and sums in float32.  Rows listed twice count once; -1 = no row.
+struct RescoreArgs {
+    const float* q;             // [nq, d]
+    const void* rows;           // stored rows
+    const float* row_norm;      // [N]
+    const int64_t* row_ids;     // labels or nullptr
+    const int32_t* cand;        // [nq, m] row numbers
+    int64_t* out_ids;           // [nq, k]
+    float* out_scores;          // [nq, k]
+    int32_t* out_rows;          // [nq, k]
+    int64_t nrows;
+    int nq, m, k, d, dtype, l2;
+};
+
+__device__ __forceinline__ float rounded_like_operand(float x, int dtype)
+{
+    if (dtype == HR_F16) return (float)(_Float16)x;
+    if (dtype == HR_BF16) {
+        const uint16_t hi = bf16_rne(x);
+        return bf16_to_f32(hi) + bf16_to_f32(bf16_rne(x - bf16_to_f32(hi)));
+    }
+    return x;
+}
+
+__global__ __launch_bounds__(256) void k_rescore(RescoreArgs a)
+{
+    __shared__ float s_key[4][HR_K_MAX];
+    __shared__ int s_row[4][HR_K_MAX];
+    __shared__ int64_t s_lab[4][HR_K_MAX];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int64_t q = (int64_t)blockIdx.x * 4 + wave;
+    if (q >= a.nq) return;
+    float* key = s_key[wave];
+    int* row = s_row[wave];
+    int64_t* lab = s_lab[wave];
+    const float* qp = a.q + q * a.d;
+    const int sub = lane & 15, grp = lane >> 4;
+    float qn = 0.f;
+    for (int i = lane; i < a.d; i += 64) { const float x = rounded_like_operand(qp[i], a.dtype); qn += x * x; }
+    qn = wave_sum(qn);
+    for (int j0 = 0; j0 < a.m; j0 += 4) {
+        const int j = j0 + grp;
+        int r = j < a.m ? a.cand[q * a.m + j] : -1;
+        if (r < 0 || r >= a.nrows) r = -1;
+        float dot = 0.f;
+        if (r >= 0) {
+            // 8 elements per lane and step, the 16 lanes of a group side by side
+            for (int e = sub * 8; e < a.d; e += 128) {
+                float x[8];
+                if (a.dtype == HR_F32) {
+                    const float4* p = (const float4*)((const float*)a.rows + (size_t)r * a.d + e);
+                    const float4 u = p[0], v = p[1];
+                    x[0] = u.x; x[1] = u.y; x[2] = u.z; x[3] = u.w; x[4] = v.x; x[5] = v.y; x[6] = v.z; x[7] = v.w;
+                } else {
+                    const uint4 u = *(const uint4*)((const uint16_t*)a.rows + (size_t)r * a.d + e);
+                    const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+                    for (int t = 0; t < 4; t++) {
+                        if (a.dtype == HR_F16) {
+                            x[2 * t] = (float)__builtin_bit_cast(_Float16, (uint16_t)(w[t] & 0xffffu));
+                            x[2 * t + 1] = (float)__builtin_bit_cast(_Float16, (uint16_t)(w[t] >> 16));
+                        } else {
+                            x[2 * t] = bf16_to_f32((uint16_t)(w[t] & 0xffffu));
+                            x[2 * t + 1] = bf16_to_f32((uint16_t)(w[t] >> 16));
+                        }
+                    }
+                }
+#pragma unroll
+                for (int t = 0; t < 8; t++) dot = __builtin_fmaf(x[t], rounded_like_operand(qp[e + t], a.dtype), dot);
+            }
+        }
+#pragma unroll
+        for (int o = 8; o > 0; o >>= 1) dot += __shfl_xor(dot, o);
+        if (sub == 0 && j < a.m) {
+            row[j] = r;
+            key[j] = r < 0 ? 0.f : (a.l2 ? 2.0f * dot - a.row_norm[r] : dot);
+            lab[j] = r < 0 ? INT64_MAX : (a.row_ids ? a.row_ids[r] : (int64_t)r);
+        }
+    }
+    wave_sync();
+    // rows listed twice: the first copy counts, the others become "no row"
+    {
+        bool dup[(HR_K_MAX + 63) / 64];
+#pragma unroll
+        for (int c = 0; c < (HR_K_MAX + 63) / 64; c++) {
+            const int j = c * 64 + lane;
+            dup[c] = false;
+            if (j < a.m && row[j] >= 0)
+                for (int u = 0; u < j; u++) if (row[u] == row[j]) { dup[c] = true; break; }
+        }
+        wave_sync();
+#pragma unroll
+        for (int c = 0; c < (HR_K_MAX + 63) / 64; c++)
+            if (dup[c]) row[c * 64 + lane] = -1;
+        wave_sync();
+    }
+    // rank among the valid rows: better key first, equal keys by label
+    int nvalid = 0;
+    for (int j0 = 0; j0 < a.m; j0 += 64) {
+        const int j = j0 + lane;
+        const bool valid = j < a.m && row[j] >= 0;
+        nvalid += __builtin_popcountll(__builtin_amdgcn_ballot_w64(valid));
+        if (!valid) continue;
+        int rank = 0;
+        for (int t = 0; t < a.m; t++)
+            if (row[t] >= 0 && (key[t] > key[j] || (key[t] == key[j] && lab[t] < lab[j]))) rank++;
+        if (rank < a.k) {
+            const size_t o = (size_t)q * a.k + rank;
+            a.out_ids[o] = lab[j];
+            a.out_scores[o] = a.l2 ? fmaxf(qn - key[j], 0.f) : key[j];
+            a.out_rows[o] = row[j];
+        }
+    }
+    for (int i = nvalid + lane; i < a.k; i += 64) {      // fewer than k rows: the other places stay empty
+        const size_t o = (size_t)q * a.k + i;
+        a.out_ids[o] = -1;
+        a.out_scores[o] = a.l2 ? __builtin_inff() : -__builtin_inff();
+        a.out_rows[o] = -1;
+    }
+}
+
+hipError_t launch_rescore(const float* q, int64_t nq, int d, int dtype, const void* rows, const float* row_norm,
+                          const int64_t* row_ids, int64_t nrows, const int32_t* cand, int m, int k, int l2,
+                          int64_t* out_ids, float* out_scores, int32_t* out_rows, hipStream_t s)
+{
+    if (nq <= 0) return hipSuccess;
+    RescoreArgs a{q, rows, row_norm, row_ids, cand, out_ids, out_scores, out_rows, nrows, (int)nq, m, k, d, dtype, l2};
+    hipLaunchKernelGGL(k_rescore, dim3((unsigned)((nq + 3) / 4)), dim3(256), 0, s, a);
     return hipGetLastError();
 }
 

@@ -141,6 +141,7 @@ struct MergeArgs {
     int carried;                // out_ids / out_scores hold a previous result on entry: merged in (ids < 0: empty places)
     int64_t* out_ids;           // [nq, k] or nullptr
     float* out_scores;          // [nq, k] or nullptr
+    int32_t* io_rows;           // [nq, k] or nullptr: row numbers of the entries, carried along with them (-1: empty place)
 };
 
 // launchers implemented in the .hip files
@@ -157,6 +158,12 @@ hipError_t launch_fill_i32(int* p, int64_t n, int v, hipStream_t s);
 hipError_t launch_read_hits(unsigned long long* hits, int64_t n, int64_t* out, int reset, hipStream_t s);
 hipError_t launch_state_thr(const int64_t* ids, const float* scores, const float* qnorm, int64_t nq, int k, int l2,
                             uint32_t* thr, hipStream_t s);
+hipError_t launch_lists_of_rows(const int32_t* rows, int64_t n, const int* list_off, int nlist, int32_t* out, hipStream_t s);
+hipError_t launch_reorder_probes(const int32_t* probe, int np, const int32_t* prev, int pp, const int32_t* hot, int nh,
+                                 int64_t nq, int32_t* out, hipStream_t s);
+hipError_t launch_rescore(const float* q, int64_t nq, int d, int dtype, const void* rows, const float* row_norm,
+                          const int64_t* row_ids, int64_t nrows, const int32_t* cand, int m, int k, int l2,
+                          int64_t* out_ids, float* out_scores, int32_t* out_rows, hipStream_t s);
 hipError_t launch_split_f32(const float* x, int64_t n, void* hi, void* lo, hipStream_t s);
 
 struct BucketArgs {

@@ -69,5 +69,22 @@ def test_null_handle_is_rejected(hr):
     assert hr.lib.hr_ivf_coarse(None, None, 1, 1, 0, None, None, None, 0, None) == -2
     assert hr.lib.hr_ivf_scan(None, None, 1, None, 1, 1, 0, None, None, None, 0, None) == -2
     assert hr.lib.hr_ivf_scan_step(None, None, 1, None, 1, 1, 0, None, None, None, 0, None) == -2
+    assert hr.lib.hr_ivf_scan_step_rows(None, None, 1, None, 1, 1, 0, None, None, None, None, 0, None) == -2
+    assert hr.lib.hr_ivf_rescore(None, None, 1, None, 1, 1, 0, None, None, None, None) == -2
+    assert hr.lib.hr_ivf_lists_of_rows(None, None, 1, None, None) == -2
     bogus = (ctypes.c_uint64 * 64)()                 # memory that is not an index
     assert hr.lib.hr_ivf_free(ctypes.cast(bogus, ctypes.c_void_p)) == -2
+
+
+def test_reorder_argument_validation_on_host(hr):
+    P = ctypes.c_void_p
+    fake, other = P(4096), P(8192)                  # never dereferenced: validation fails first
+    f = hr.lib.hr_ivf_reorder_probes
+    assert f(fake, 4, 0, None, 0, None, 0, other, None) == -1
+    assert f(fake, 4, hr.HR_NPROBE_MAX + 1, None, 0, None, 0, other, None) == -1
+    assert f(fake, 4, 8, fake, hr.HR_NPROBE_MAX + 1, None, 0, other, None) == -1
+    assert f(fake, 4, 8, None, 0, fake, hr.HR_K_MAX + 1, other, None) == -1
+    assert f(None, 4, 8, None, 0, None, 0, other, None) == -1
+    assert f(fake, 4, 8, None, 0, None, 0, fake, None) == -1 and "must not be probe" in hr.hr_last_error()
+    assert f(fake, 0, 8, None, 0, None, 0, other, None) == 0      # empty batch: nothing to do
+

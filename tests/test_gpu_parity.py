@@ -429,3 +429,142 @@ def test_paper_shape_scaled():
 def test_paper_shape_full_size_sampled():
     _run_config("P1", sample=16)
 
+
+
+# ---------------------------------------------------------------- reuse of the previous retrieval (Section 4.3)
+def test_reorder_probes_exact():
+    """Integer work: identical to the oracle, at the size limits and with absent entries."""
+    hr = _hr()
+    rng = np.random.default_rng(31)
+    for nq, nlist, np_, pp, nh in [(70, 900, 512, 512, 128), (33, 40, 5, 0, 3), (9, 64, 64, 17, 0), (5, 10, 3, 0, 0),
+                                   (130, 200, 37, 64, 20)]:
+        print(f"case reorder nq={nq} nprobe={np_} nprev={pp} nhot={nh}", flush=True)
+        probe = np.stack([rng.permutation(nlist)[:np_] for _ in range(nq)]).astype(np.int32)
+        probe[rng.random(probe.shape) < 0.08] = -1
+        prev = np.stack([rng.permutation(nlist)[:pp] for _ in range(nq)]).astype(np.int32) if pp else None
+        if prev is not None:
+            prev[rng.random(prev.shape) < 0.08] = -1
+        hot = rng.integers(-1, nlist, (nq, nh)).astype(np.int32) if nh else None
+        got = hr.reorder_probes(torch.from_numpy(probe).cuda(),
+                                torch.from_numpy(prev).cuda() if prev is not None else None,
+                                torch.from_numpy(hot).cuda() if hot is not None else None).cpu().numpy()
+        assert np.array_equal(got, oracle.reorder_probes(probe, prev, hot))
+
+
+def test_lists_of_rows_exact():
+    hr = _hr()
+    idx = _random_index(5000, 64, 37, "f16", seed=3)          # (with empty lists)
+    ix = hr.IvfIndex(idx.centroids, idx.list_offsets, idx.list_vectors, idx.list_ids)
+    rows = np.concatenate([np.arange(-3, 5003), np.random.default_rng(1).integers(0, 5000, 999)]).astype(np.int32)
+    got = ix.lists_of_rows(torch.from_numpy(rows).cuda()).cpu().numpy()
+    assert np.array_equal(got, oracle.lists_of_rows(rows, synth.to_numpy(idx.list_offsets)))
+    ix.close()
+
+
+@pytest.mark.parametrize("dtype,metric", [("f16", "ip"), ("f16", "l2"), ("bf16", "l2"), ("f32", "ip"), ("f32", "l2")])
+def test_rescore_of_cached_rows(dtype, metric):
+    """The local cache: k best of m given rows per query against the oracle's top-k of those rows
+    (rows named twice, absent and out-of-range rows; fewer rows than k; m and k at their limits)."""
+    print(f"case rescore {dtype} {metric}", flush=True)
+    hr = _hr()
+    n, d = 9000, 256
+    idx = _random_index(n, d, 20, dtype, seed=17, dup=3)
+    host = Host(idx)
+    ix = hr.IvfIndex(idx.centroids, idx.list_offsets, idx.list_vectors, idx.list_ids)
+    rng = np.random.default_rng(23)
+    m_ = METRIC[metric]
+    for nq, m, k in [(101, 20, 10), (40, 5, 10), (37, 128, 128), (64, 64, 1)]:
+        q = torch.randn(nq, d, generator=torch.Generator().manual_seed(nq)).cuda()
+        rows = rng.integers(0, n, (nq, m)).astype(np.int32)
+        rows[rng.random(rows.shape) < 0.1] = -1
+        rows[0, :] = -1                                   # nothing cached for this query
+        if m > 3:
+            rows[1, 1] = rows[1, 0]; rows[1, 3] = rows[1, 0]; rows[2, 2] = n + 4
+        ids_g, sc_g, rows_g = [t.cpu().numpy() for t in ix.rescore(q, torch.from_numpy(rows).cuda(), k, metric)]
+        qn = synth.to_numpy(q)
+        ids_o, sc_o, rows_o = oracle.topk_of_rows(qn, host.vec, dtype, host.ids, list(rows), k, m_)
+        st = check_topk(ids_g, sc_g, ids_o, sc_o,
+                        lambda i, ids: oracle.pair_scores(qn, host.vec, dtype, m_, np.full(len(ids), i), host.rows_of(ids)),
+                        metric, TAU[dtype], _scale(qn, host.xnorm(), metric))
+        print(f"[parity rescore {dtype} {metric} m={m} k={k}] {st}", flush=True)
+        assert (ids_g[0] == -1).all() and (rows_g[0] == -1).all()
+        assert ((ids_g >= 0) == (ids_o >= 0)).all()        # same number of entries per query
+        have = ids_g >= 0
+        assert np.array_equal(host.ids[rows_g[have]], ids_g[have])      # rows and ids name the same vectors
+        for i in range(nq):                                # every row reported once
+            r = rows_g[i][rows_g[i] >= 0]
+            assert len(np.unique(r)) == len(r)
+    ix.close()
+
+
+def test_scan_step_rows_carries_rows():
+    """The carried result with row numbers: same ids and scores as without, rows name the vectors."""
+    hr = _hr()
+    idx = _random_index(20000, 128, 50, "f16", seed=29)
+    host = Host(idx)
+    ix = hr.IvfIndex(idx.centroids, idx.list_offsets, idx.list_vectors, idx.list_ids)
+    g = torch.Generator().manual_seed(4)
+    nq, nprobe, k = 90, 20, 30
+    q = torch.randn(nq, 128, generator=g).cuda()
+    probe = torch.stack([torch.randperm(50, generator=g)[:nprobe] for _ in range(nq)]).to(torch.int32)
+    probe[3, 2:] = -1
+    a = ix.new_state(nq, k)
+    b = ix.new_state_rows(nq, k)
+    for s0 in range(0, nprobe, 5):
+        ix.scan_step(q, probe[:, s0:s0 + 5].cuda(), a, "ip")
+        ix.scan_step_rows(q, probe[:, s0:s0 + 5].cuda(), b, "ip")
+    ids_a, sc_a = a[0].cpu().numpy(), a[1].cpu().numpy()
+    ids_b, sc_b, rows_b = b[0].cpu().numpy(), b[1].cpu().numpy(), b[2].cpu().numpy()
+    assert np.array_equal(ids_a, ids_b) and np.array_equal(sc_a, sc_b)
+    have = ids_b >= 0
+    assert ((rows_b >= 0) == have).all()
+    assert np.array_equal(host.ids[rows_b[have]], ids_b[have])
+    ix.close()
+
+
+@pytest.mark.parametrize("dtype,metric", [("f16", "ip"), ("bf16", "l2"), ("f32", "l2")])
+def test_retrieval_started_from_the_cache_of_the_previous_one(dtype, metric):
+    """Two consecutive retrievals of the same requests (the second query drifted a little): the
+    second starts from the 20 cached rows of the first, searches its lists in the order of
+    Section 4.3, in sub-stages; rows the cache already gave are found again by the scan and
+    must not be reported twice.  Expected: the oracle's k best over the union of the cached
+    rows and the rows of all probed lists."""
+    print(f"case cache {dtype} {metric}", flush=True)
+    hr = _hr()
+    cfg = synth.scaled(synth.CONFIGS["C4"], N=60000, nlist=96, nq=120, nprobe=16, k=10, rounds=2, dtype=dtype,
+                       metric=metric, d=128)
+    idx = synth.make_index(cfg, "cuda")
+    v, v2 = synth.make_queries(cfg, idx)
+    host = Host(idx)
+    ix = hr.IvfIndex(idx.centroids, idx.list_offsets, idx.list_vectors, idx.list_ids)
+    nq, k, big = cfg.nq, cfg.k, 20
+    # first retrieval, keeping the 20 best with their rows
+    probe1, _ = ix.coarse(v, cfg.nprobe, metric)
+    st1 = ix.new_state_rows(nq, big)
+    ix.scan_step_rows(v, probe1, st1, metric)
+    cache = st1[2].clone()
+    hot = ix.lists_of_rows(st1[2][:, :k])                      # H_v: where the k best of v were
+    # second retrieval
+    probe2, _ = ix.coarse(v2, cfg.nprobe, metric)
+    order = hr.reorder_probes(probe2, probe1, hot)
+    assert np.array_equal(order.cpu().numpy(),
+                          oracle.reorder_probes(probe2.cpu().numpy(), probe1.cpu().numpy(), hot.cpu().numpy()))
+    st2 = ix.rescore(v2, cache, k, metric)
+    for s0 in range(0, cfg.nprobe, 4):
+        ix.scan_step_rows(v2, order[:, s0:s0 + 4].contiguous(), st2, metric)
+    ids_g, sc_g, rows_g = [t.cpu().numpy() for t in st2]
+    qn = synth.to_numpy(v2)
+    p2 = probe2.cpu().numpy()
+    cache_h = cache.cpu().numpy()
+    union = [np.concatenate([cache_h[i]] + [np.arange(host.off[l], host.off[l + 1]) for l in p2[i]]) for i in range(nq)]
+    m_ = METRIC[metric]
+    ids_o, sc_o, _ = oracle.topk_of_rows(qn, host.vec, dtype, host.ids, union, k, m_)
+    st = check_topk(ids_g, sc_g, ids_o, sc_o,
+                    lambda i, ids: oracle.pair_scores(qn, host.vec, dtype, m_, np.full(len(ids), i), host.rows_of(ids)),
+                    metric, TAU[dtype], _scale(qn, host.xnorm(), metric))
+    inside = float(np.mean([np.isin(ids_o[i], st1[0][i].cpu().numpy()).all() for i in range(nq)]))
+    print(f"[parity cache {dtype} {metric}] {st}; results of v' all inside the 20 cached of v: {inside:.2f}", flush=True)
+    for i in range(nq):
+        assert len(np.unique(ids_g[i])) == k                # k distinct vectors
+    assert np.array_equal(host.ids[rows_g], ids_g)
+    ix.close()
