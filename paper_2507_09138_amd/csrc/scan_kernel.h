@@ -517,8 +517,9 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
                     }
                 }
             }
-            // (every wave writes the same 16 norms: the same number of loads per wave)
-            if (lane < kBlockRows)
+            // (every wave writes the same 16 norms: the same number of loads per wave; the inner
+            // product needs none)
+            if (a.l2 && lane < kBlockRows)
                 lds_dma4(a.row_norm + row0 + bl * kBlockRows, (uint32_t)min(lane, valid - 1) * 4u,
                          lds_addr(nstage) + buf * (kBlockRows * 4));
         };
@@ -722,11 +723,20 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
         // buffer that one leaves, (4) multiply, (5) select
         auto step_direct = [&](int blk) __attribute__((always_inline)) {
             // all but the D-1 youngest requests of this wave (S::lpf loads each) are done
-            switch (D) {
-            case 1: wait_vmcnt<0>(); break;
-            case 2: wait_vmcnt<S::lpf>(); break;
-            case 3: wait_vmcnt<2 * S::lpf>(); break;
-            default: wait_vmcnt<3 * S::lpf>(); break;
+            if (a.l2) {
+                switch (D) {
+                case 1: wait_vmcnt<0>(); break;
+                case 2: wait_vmcnt<S::lpf>(); break;
+                case 3: wait_vmcnt<2 * S::lpf>(); break;
+                default: wait_vmcnt<3 * S::lpf>(); break;
+                }
+            } else {
+                switch (D) {
+                case 1: wait_vmcnt<0>(); break;
+                case 2: wait_vmcnt<S::lpf - 1>(); break;
+                case 3: wait_vmcnt<2 * (S::lpf - 1)>(); break;
+                default: wait_vmcnt<3 * (S::lpf - 1)>(); break;
+                }
             }
             __builtin_amdgcn_s_barrier();
             HR_TOC(t_bar, tk);
@@ -751,7 +761,9 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
         // blk+3 requested into the two buffers the previous pair leaves
         auto pair_direct = [&](int blk) __attribute__((always_inline)) {
             // (6 buffers: the requests of the pair after the next one may still be on their way)
-            if (NB == 6) wait_vmcnt<2 * S::lpf>(); else wait_vmcnt<0>();
+            if (NB != 6) wait_vmcnt<0>();
+            else if (a.l2) wait_vmcnt<2 * S::lpf>();
+            else wait_vmcnt<2 * (S::lpf - 1)>();
             __builtin_amdgcn_s_barrier();
             HR_TOC(t_bar, tk);
             // (the requests of all waves at once keep the address unit busy for a while, and a
