@@ -568,3 +568,36 @@ def test_retrieval_started_from_the_cache_of_the_previous_one(dtype, metric):
         assert len(np.unique(ids_g[i])) == k                # k distinct vectors
     assert np.array_equal(host.ids[rows_g], ids_g)
     ix.close()
+
+
+def test_search_captured_in_a_hip_graph_replays_identically():
+    """The search only enqueues kernels (no allocation, no host synchronisation, no memset
+    nodes), so a caller can capture it in a HIP graph and replay it for launch-bound small
+    batches.  Replayed several times with new queries in the same buffers and eager work in
+    between; every replay must give the bits of the eager call."""
+    hr = _hr()
+    idx = _random_index(30000, 128, 64, "f16", seed=61)
+    ix = hr.IvfIndex(idx.centroids, idx.list_offsets, idx.list_vectors, idx.list_ids)
+    nq, nprobe, k = 48, 8, 10
+    gen = torch.Generator().manual_seed(9)
+    batches = [torch.randn(nq, 128, generator=gen).cuda() for _ in range(4)]
+    q = batches[0].clone()
+    ids = torch.empty(nq, k, dtype=torch.int64, device="cuda")
+    scores = torch.empty(nq, k, dtype=torch.float32, device="cuda")
+    ws = ix.workspace(nq, nprobe, k)
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        hr.hr_ivf_search(ix.handle, q, nq, nprobe, k, hr.HR_METRIC_IP, ids, scores, ws, ws.numel())    # warm-up, eager
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        hr.hr_ivf_search(ix.handle, q, nq, nprobe, k, hr.HR_METRIC_IP, ids, scores, ws, ws.numel())
+    for r, b in enumerate(batches):
+        want_ids, want_scores = ix.search(b, nprobe, k, "ip")              # eager, own buffers
+        torch.cuda.synchronize()
+        q.copy_(b)
+        ids.fill_(-7)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(ids, want_ids) and torch.equal(scores, want_scores), f"replay {r}"
+    ix.close()
