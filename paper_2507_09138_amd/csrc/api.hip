@@ -71,6 +71,13 @@ struct ScanPick { int shape, nbuf, cap, gsel; };
 static ScanPick pick_shape(int dtype, int d, int k)
 {
     const int cap = hr::sel_cap(k);
+    if (dtype == hr::HR_F16X2) {
+        // float32 lists split into two binary16 tables at load: 4 bytes per element to stage, so
+        // LDS goes to the row buffers (3 or 2 of them) and the selection buffers to global memory
+        for (int nbuf : {3, 2})
+            if (hr::scan_lds_bytes(dtype, d, 0, hr::SCAN_WIDE, nbuf) <= (size_t)kLdsLimit) return {hr::SCAN_WIDE, nbuf, cap, 1};
+        return {-1, 0, 0, 0};
+    }
     if (cap > 64) {
         // large k: selection buffers of that size would take most of LDS; they live in global
         // memory (the result slots themselves) and LDS is left to the row buffers
@@ -135,6 +142,8 @@ struct hr_ivf_index {
     float* d_cent_norm;    // [nlist]
     void* d_cent_hi;       // [nlist, d] binary16: centroids rounded
     void* d_cent_lo;       // [nlist, d] binary16: (centroid - hi) * 2^11
+    void* d_vec_hi;        // float32 lists only, when memory allows: [N, d] binary16 hi and scaled lo tables of the
+    void* d_vec_lo;        // rows (the split the scan would otherwise redo for every block it stages); else null
     unsigned long long* d_hits;   // [nlist] probes per list since load / last reset
     int num_cus;
     int lds_limit;
@@ -142,6 +151,9 @@ struct hr_ivf_index {
     hipEvent_t* prof_ev;   // 2 * prof_cap events
     int prof_cap, prof_n;
 };
+
+// storage type the list scan runs on
+static int scan_dtype(const hr_ivf_index* ix) { return ix->d_vec_hi ? (int)HR_F16X2 : ix->dtype; }
 
 static bool dim_supported(int d)
 {
@@ -174,7 +186,7 @@ static Plan make_plan(const hr_ivf_index* ix, int64_t nq, int nprobe, int k)
     Plan p{};
     const int64_t nlist = ix->nlist;
     // coarse step: dense scoring (no selection buffers in LDS) in the widest shape that fits
-    const ScanPick ps = pick_shape(ix->dtype, ix->d, k);
+    const ScanPick ps = pick_shape(scan_dtype(ix), ix->d, k);
     p.shape_c = -1; p.nbuf_c = 0; p.cap_c = 0;
     for (int nbuf = 3; nbuf >= 2 && p.shape_c < 0; nbuf--)
         if (scan_lds_bytes(HR_F16X2, ix->d, 0, SCAN_WIDE, nbuf) <= (size_t)kLdsLimit) { p.shape_c = SCAN_WIDE; p.nbuf_c = nbuf; }
@@ -192,7 +204,7 @@ static Plan make_plan(const hr_ivf_index* ix, int64_t nq, int nprobe, int k)
     p.seg_c = (int)seg;
     p.nseg_c = (int)((nlist + seg - 1) / seg);
     p.items_c = p.nseg_c * p.nqt_c;
-    p.cw_s = cols_per_set(ix->dtype) * shape_sets(p.shape_s < 0 ? 0 : p.shape_s);
+    p.cw_s = cols_per_set(scan_dtype(ix)) * shape_sets(p.shape_s < 0 ? 0 : p.shape_s);
     const int64_t pairs = nq * nprobe;
     p.item_cap = (int)(kItemTarget + pairs / p.cw_s + (pairs < nlist ? pairs : nlist) + 8);
 
@@ -304,6 +316,20 @@ int hr_ivf_load(const float* centroids, const int64_t* list_offsets, const void*
     if (e == hipSuccess) e = launch_row_norms(list_vectors, dtype, N, d, ix->d_row_norm, s);
     if (e == hipSuccess) e = launch_row_norms(centroids, HR_F32, nlist, d, ix->d_cent_norm, s);
     if (e == hipSuccess) e = launch_split_f32(centroids, nlist * d, ix->d_cent_hi, ix->d_cent_lo, s);
+    if (e == hipSuccess && dtype == HR_F32 && N > 0) {
+        // float32 lists: the scan multiplies binary16 hi and lo parts of the rows.  Made once here
+        // (same bytes again: 2 + 2 per element) they go straight from HBM to LDS like 16-bit lists;
+        // made on the fly they pass through registers for every block.  Only when that leaves at
+        // least half of the free device memory; otherwise the scan splits on the fly.
+        const size_t bytes = (size_t)N * d * 2;
+        size_t free_b = 0, total_b = 0;
+        if (hipMemGetInfo(&free_b, &total_b) == hipSuccess && 2 * bytes <= free_b / 2) {
+            if (hipMalloc(&ix->d_vec_hi, bytes) != hipSuccess) ix->d_vec_hi = nullptr;
+            if (ix->d_vec_hi && hipMalloc(&ix->d_vec_lo, bytes) != hipSuccess) { (void)hipFree(ix->d_vec_hi); ix->d_vec_hi = nullptr; ix->d_vec_lo = nullptr; }
+            if (!ix->d_vec_hi) (void)hipGetLastError();          // (not an error of the load: the other path is taken)
+            else e = launch_split_f32((const float*)list_vectors, N * d, ix->d_vec_hi, ix->d_vec_lo, s);
+        }
+    }
     if (e == hipSuccess) e = hipStreamSynchronize(s);
     delete[] h_off;
     if (e != hipSuccess) {
@@ -313,6 +339,8 @@ int hr_ivf_load(const float* centroids, const int64_t* list_offsets, const void*
         if (ix->d_cent_hi) (void)hipFree(ix->d_cent_hi);
         if (ix->d_cent_lo) (void)hipFree(ix->d_cent_lo);
         if (ix->d_hits) (void)hipFree(ix->d_hits);
+        if (ix->d_vec_hi) (void)hipFree(ix->d_vec_hi);
+        if (ix->d_vec_lo) (void)hipFree(ix->d_vec_lo);
         delete ix;
         return fail(HR_ERR_HIP, "hr_ivf_load: %s", hipGetErrorString(e));
     }
@@ -377,6 +405,8 @@ int hr_ivf_free(hr_ivf_index* ix)
     (void)hipFree(ix->d_cent_hi);
     (void)hipFree(ix->d_cent_lo);
     (void)hipFree(ix->d_hits);
+    if (ix->d_vec_hi) (void)hipFree(ix->d_vec_hi);
+    if (ix->d_vec_lo) (void)hipFree(ix->d_vec_lo);
     delete ix;
     return HR_OK;
 }
@@ -461,7 +491,7 @@ static int enqueue_scan(const hr_ivf_index* ix, const Plan& p, char* ws, int64_t
 {
     if (p.shape_s < 0)
         return fail(HR_ERR_UNSUPPORTED, "list scan does not fit in LDS (d=%d, k=%d)", ix->d, k);
-    const size_t lds = scan_lds_bytes(ix->dtype, ix->d, p.gsel_s ? 0 : p.cap_s, p.shape_s, p.nbuf_s);
+    const size_t lds = scan_lds_bytes(scan_dtype(ix), ix->d, p.gsel_s ? 0 : p.cap_s, p.shape_s, p.nbuf_s);
     int* zero = (int*)(ws + p.o_zero);
     BucketArgs b{};
     b.probe = probe; b.nq = (int)nq; b.nprobe = nprobe; b.nlist = (int)ix->nlist; b.cw = p.cw_s;
@@ -497,7 +527,8 @@ static int enqueue_scan(const hr_ivf_index* ix, const Plan& p, char* ws, int64_t
     HR_HIP(launch_seed(ix->dtype, ix->d, sd, s));
 
     ScanArgs a{};
-    a.rows = ix->vectors;
+    a.rows = ix->d_vec_hi ? ix->d_vec_hi : ix->vectors;
+    a.rows_lo = ix->d_vec_lo;
     a.row_norm = ix->d_row_norm;
     a.row_ids = ix->ids;
     a.qop = ws + p.o_qop_s;
@@ -527,7 +558,7 @@ static int enqueue_scan(const hr_ivf_index* ix, const Plan& p, char* ws, int64_t
     hr_ivf_index* mix = const_cast<hr_ivf_index*>(ix);
     const bool timed = mix->prof_ev && mix->prof_n < mix->prof_cap;
     if (timed) HR_HIP(hipEventRecord(mix->prof_ev[2 * mix->prof_n], s));
-    HR_HIP(launch_scan(ix->dtype, ix->d, a, p.shape_s, scan_grid(ix, lds, p.shape_s), lds, s));
+    HR_HIP(launch_scan(scan_dtype(ix), ix->d, a, p.shape_s, scan_grid(ix, lds, p.shape_s), lds, s));
     if (timed) {
         HR_HIP(hipEventRecord(mix->prof_ev[2 * mix->prof_n + 1], s));
         mix->prof_n++;

@@ -1012,7 +1012,8 @@ template <int DT>
 inline hipError_t launch_scan_dtype(int d, const ScanArgs& a, int shape, int grid, size_t lds, hipStream_t s)
 {
     if constexpr (DT == HR_F16X2) {
-        return launch_scan_shape<DT, 1, 8, false>(d, a, grid, lds, s);     // (coarse step only)
+        // (the centroid table in the coarse step, and float32 lists split at load)
+        return a.gsel ? launch_scan_shape<DT, 1, 8, true>(d, a, grid, lds, s) : launch_scan_shape<DT, 1, 8, false>(d, a, grid, lds, s);
     } else {
         if (a.gsel) return shape == SCAN_WIDE ? launch_scan_shape<DT, 1, 8, true>(d, a, grid, lds, s) : hipErrorInvalidValue;
         return shape == SCAN_WIDE ? launch_scan_shape<DT, 1, 8, false>(d, a, grid, lds, s)
