@@ -63,9 +63,12 @@ enum {
  *   magnitude below 65504 (they pass through binary16 pairs inside the kernels).
  *   stream        hipStream_t (as void*) on which the derived tables are computed.
  * centroids, list_vectors and list_ids are BORROWED: they must stay valid and unchanged until
- * hr_ivf_free.  The library allocates (hipMalloc) only small derived tables: device copies of
- * the offsets and 4 bytes per row / per centroid of squared norms.  The call synchronises
- * `stream` before returning.
+ * hr_ivf_free.  The library allocates (hipMalloc) derived tables: device copies of the offsets,
+ * 4 bytes per row / per centroid of squared norms, the centroids as two binary16 tables, 8 bytes
+ * per list of access counters; and, for HR_F32 storage only, the rows as two binary16 tables
+ * (hi and scaled lo part: N*d*4 bytes, as much as list_vectors itself) when that takes at most
+ * half of the device memory free at the time — without them the search gives the same results,
+ * more slowly.  The call synchronises `stream` before returning.
  */
 int hr_ivf_load(const float* centroids, const int64_t* list_offsets, const void* list_vectors,
                 const int64_t* list_ids, int64_t nlist, int64_t N, int32_t d, int32_t dtype,
