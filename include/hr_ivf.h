@@ -47,6 +47,7 @@ enum {
 #define HR_K_MAX 128          /* largest k */
 #define HR_NPROBE_MAX 512     /* largest nprobe (the paper probes 128 to 512 clusters: Section 6.1) */
 #define HR_WORKSPACE_ALIGN 256
+#define HR_LOAD_NO_ROW_TABLES 0x100   /* or-ed into hr_ivf_load's dtype: see there */
 
 /*
  * hr_ivf_load — wrap an IVF-Flat index that already lives in HBM (Section 2.2: vectors
@@ -67,8 +68,9 @@ enum {
  * 4 bytes per row / per centroid of squared norms, the centroids as two binary16 tables, 8 bytes
  * per list of access counters; and, for HR_F32 storage only, the rows as two binary16 tables
  * (hi and scaled lo part: N*d*4 bytes, as much as list_vectors itself) when that takes at most
- * half of the device memory free at the time — without them the search gives the same results,
- * more slowly.  The call synchronises `stream` before returning.
+ * half of the device memory free at the time, and dtype is not HR_F32 | HR_LOAD_NO_ROW_TABLES —
+ * without them the search gives the same results, more slowly.  The call synchronises `stream`
+ * before returning.
  */
 int hr_ivf_load(const float* centroids, const int64_t* list_offsets, const void* list_vectors,
                 const int64_t* list_ids, int64_t nlist, int64_t N, int32_t d, int32_t dtype,

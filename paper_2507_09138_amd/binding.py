@@ -15,6 +15,7 @@ import torch
 HR_METRIC_IP, HR_METRIC_L2 = 0, 1
 HR_F32, HR_F16, HR_BF16 = 0, 1, 2
 HR_K_MAX, HR_NPROBE_MAX = 128, 512
+HR_LOAD_NO_ROW_TABLES = 0x100
 _ERR = {-1: "HR_ERR_ARG", -2: "HR_ERR_HANDLE", -3: "HR_ERR_WORKSPACE", -4: "HR_ERR_HIP",
         -5: "HR_ERR_UNSUPPORTED"}
 _DTYPE = {torch.float32: HR_F32, torch.float16: HR_F16, torch.bfloat16: HR_BF16}
@@ -177,7 +178,7 @@ def hr_ivf_profile_end(handle):
 class IvfIndex:
     """Keeps the borrowed tensors alive, owns the handle and a growable workspace tensor."""
 
-    def __init__(self, centroids, list_offsets, list_vectors, list_ids):
+    def __init__(self, centroids, list_offsets, list_vectors, list_ids, row_tables=True):
         assert centroids.is_cuda and list_vectors.is_cuda and list_ids.is_cuda
         assert centroids.dtype == torch.float32 and list_ids.dtype == torch.int64
         self.centroids = centroids.contiguous()
@@ -188,7 +189,8 @@ class IvfIndex:
         self.N = self.list_vectors.shape[0]
         self.dtype = _DTYPE[self.list_vectors.dtype]
         self.handle = hr_ivf_load(self.centroids, self.list_offsets, self.list_vectors,
-                                  self.list_ids, self.nlist, self.N, self.d, self.dtype)
+                                  self.list_ids, self.nlist, self.N, self.d,
+                                  self.dtype | (0 if row_tables else HR_LOAD_NO_ROW_TABLES))
         self._ws = None
 
     def close(self):

@@ -277,6 +277,8 @@ int hr_ivf_load(const float* centroids, const int64_t* list_offsets, const void*
     if (nlist < 1 || nlist >= (1LL << 24)) return fail(HR_ERR_ARG, "nlist=%lld out of range", (long long)nlist);
     if (N < 0 || N >= (1LL << 31)) return fail(HR_ERR_ARG, "N=%lld out of range (< 2^31)", (long long)N);
     if (N > 0 && (!list_vectors || !list_ids)) return fail(HR_ERR_ARG, "list_vectors / list_ids is null");
+    const bool row_tables = !(dtype & HR_LOAD_NO_ROW_TABLES);
+    dtype &= ~HR_LOAD_NO_ROW_TABLES;
     if (dtype != HR_F32 && dtype != HR_F16 && dtype != HR_BF16) return fail(HR_ERR_ARG, "unknown dtype %d", dtype);
     if (d < 1) return fail(HR_ERR_ARG, "d=%d", d);
     if (!dim_supported(d)) return fail(HR_ERR_UNSUPPORTED, "d=%d not one of 64,128,256,512,768,1024", d);
@@ -316,7 +318,7 @@ int hr_ivf_load(const float* centroids, const int64_t* list_offsets, const void*
     if (e == hipSuccess) e = launch_row_norms(list_vectors, dtype, N, d, ix->d_row_norm, s);
     if (e == hipSuccess) e = launch_row_norms(centroids, HR_F32, nlist, d, ix->d_cent_norm, s);
     if (e == hipSuccess) e = launch_split_f32(centroids, nlist * d, ix->d_cent_hi, ix->d_cent_lo, s);
-    if (e == hipSuccess && dtype == HR_F32 && N > 0) {
+    if (e == hipSuccess && dtype == HR_F32 && N > 0 && row_tables) {
         // float32 lists: the scan multiplies binary16 hi and lo parts of the rows.  Made once here
         // (same bytes again: 2 + 2 per element) they go straight from HBM to LDS like 16-bit lists;
         // made on the fly they pass through registers for every block.  Only when that leaves at

@@ -34,6 +34,7 @@ def test_header_constants_match_binding(hr):
     text = open(os.path.join(ROOT, "include", "hr_ivf.h")).read()
     assert int(re.search(r"#define HR_K_MAX (\d+)", text).group(1)) == hr.HR_K_MAX
     assert int(re.search(r"#define HR_NPROBE_MAX (\d+)", text).group(1)) == hr.HR_NPROBE_MAX
+    assert int(re.search(r"#define HR_LOAD_NO_ROW_TABLES (0x[0-9a-f]+)", text).group(1), 16) == hr.HR_LOAD_NO_ROW_TABLES
 
 
 def test_load_argument_validation_on_host(hr):
@@ -54,6 +55,7 @@ def test_load_argument_validation_on_host(hr):
     assert load(N=-1) == -1
     assert load(N=1 << 31) == -1
     assert load(dtype=3) == -1
+    assert load(dtype=3 | hr.HR_LOAD_NO_ROW_TABLES) == -1
     assert load(d=0) == -1
     assert load(d=100) == -5 and "d=100" in hr.hr_last_error()
     assert load(offs=bad) == -1 and "decreases" in hr.hr_last_error()

@@ -601,3 +601,32 @@ def test_search_captured_in_a_hip_graph_replays_identically():
         torch.cuda.synchronize()
         assert torch.equal(ids, want_ids) and torch.equal(scores, want_scores), f"replay {r}"
     ix.close()
+
+
+@pytest.mark.parametrize("metric", ["ip", "l2"])
+def test_float32_lists_with_and_without_row_tables(metric):
+    """float32 lists are scanned from binary16 hi/lo tables made at load, or, without them, split
+    on the fly: the same products in the same order, so the results must be the same bits; the
+    on-the-fly path is checked against the oracle as well."""
+    print(f"case f32 row tables {metric}", flush=True)
+    hr = _hr()
+    idx = _random_index(40000, 256, 48, "f32", seed=71, dup=2)
+    host = Host(idx)
+    a = hr.IvfIndex(idx.centroids, idx.list_offsets, idx.list_vectors, idx.list_ids)
+    b = hr.IvfIndex(idx.centroids, idx.list_offsets, idx.list_vectors, idx.list_ids, row_tables=False)
+    q = torch.randn(300, 256, generator=torch.Generator().manual_seed(2)).cuda()
+    m = METRIC[metric]
+    for nprobe, k in [(12, 10), (7, 100)]:
+        ids_a, sc_a = a.search(q, nprobe, k, metric)
+        ids_b, sc_b = b.search(q, nprobe, k, metric)
+        assert torch.equal(ids_a, ids_b) and torch.equal(sc_a, sc_b)
+        probe, _ = b.coarse(q, nprobe, metric)
+        qn = synth.to_numpy(q)
+        ids_o, sc_o = oracle.scan(qn, host.off, host.vec, "f32", host.ids, probe.cpu().numpy(), k, m)
+        st = check_topk(ids_b.cpu().numpy(), sc_b.cpu().numpy(), ids_o, sc_o,
+                        lambda i, ids: oracle.pair_scores(qn, host.vec, "f32", m, np.full(len(ids), i), host.rows_of(ids)),
+                        metric, TAU["f32"], _scale(qn, host.xnorm(), metric))
+        print(f"[parity f32 on the fly {metric} nprobe={nprobe} k={k}] {st}", flush=True)
+    a.close()
+    b.close()
+
