@@ -73,8 +73,9 @@ static ScanPick pick_shape(int dtype, int d, int k)
     const int cap = hr::sel_cap(k);
     if (dtype == hr::HR_F16X2) {
         // float32 lists split into two binary16 tables at load: 4 bytes per element to stage, so
-        // LDS goes to the row buffers (3 or 2 of them) and the selection buffers to global memory
-        for (int nbuf : {3, 2})
+        // LDS goes to the row buffers (as many as fit; d = 768: 3, d = 1024: 2) and the selection
+        // buffers to global memory
+        for (int nbuf : {6, 4, 3, 2})
             if (hr::scan_lds_bytes(dtype, d, 0, hr::SCAN_WIDE, nbuf) <= (size_t)kLdsLimit) return {hr::SCAN_WIDE, nbuf, cap, 1};
         return {-1, 0, 0, 0};
     }
