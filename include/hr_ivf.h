@@ -144,6 +144,25 @@ int hr_ivf_scan_step(const hr_ivf_index* index, const float* queries, int64_t nq
                      void* stream);
 
 /*
+ * hr_ivf_hot_lists — the gc most frequently probed lists by the counters of hr_ivf_list_hits,
+ * most frequent first, equal counts by ascending list number: the clusters a partial index
+ * cache keeps resident (Section 4.4).   out_lists DEV [gc] int32, 1 <= gc <= nlist.
+ * Ranks by counting (nlist^2 compares): nlist <= 65536, else HR_ERR_UNSUPPORTED.  Meant to be
+ * called now and then (the paper updates its cache every 50 sub-stages), not per search.
+ */
+int hr_ivf_hot_lists(const hr_ivf_index* index, int32_t gc, int32_t* out_lists, void* stream);
+
+/*
+ * hr_ivf_refresh_rows — after the caller has replaced the vectors of rows row_begin ..
+ * row_end-1 in list_vectors (a cluster loaded asynchronously into the place of another one of
+ * the same length: the index loading interface of Section 5), recompute what the library
+ * derives from them (squared norms; for HR_F32 the binary16 row tables).  Enqueued on `stream`:
+ * put it behind the copy, and the next search behind it.  list_ids is read at search time and
+ * needs no refresh; list_offsets cannot change.
+ */
+int hr_ivf_refresh_rows(hr_ivf_index* index, int64_t row_begin, int64_t row_end, void* stream);
+
+/*
  * Reuse of a request's previous retrieval (Section 4.3: consecutive queries v, v' of a request are
  * close; the results of v' tend to lie among a larger top-k of v, in the clusters H_v that held
  * v's results, and in clusters probed for both).  Four calls; each only enqueues kernels.

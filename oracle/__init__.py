@@ -188,6 +188,14 @@ def reorder_probes(probe, prev, hot):
     return out
 
 
+def hot_lists(hits, gc):
+    """The gc most frequently probed lists (Section 4.4 of the paper: the clusters accessed most
+    often are the ones a partial index cache keeps), most frequent first, equal counts by
+    ascending list number."""
+    hits = np.asarray(hits, np.int64)
+    return np.lexsort((np.arange(hits.size), -hits))[:gc].astype(np.int64)
+
+
 def ivf_search(queries, centroids, offsets, vectors, dtype, ids, nprobe, k, metric):
     """Whole search.  Returns (probe_ids, ids, scores)."""
     q = _as(queries, np.float32)

@@ -44,6 +44,8 @@ def _load_lib():
     L.hr_ivf_coarse.argtypes = [p, p, c.c_int64, c.c_int32, c.c_int32, p, p, p, c.c_size_t, p]
     L.hr_ivf_scan.argtypes = [p, p, c.c_int64, p, c.c_int32, c.c_int32, c.c_int32, p, p, p, c.c_size_t, p]
     L.hr_ivf_list_hits.argtypes = [p, p, c.c_int32, p]
+    L.hr_ivf_hot_lists.argtypes = [p, c.c_int32, p, p]
+    L.hr_ivf_refresh_rows.argtypes = [p, c.c_int64, c.c_int64, p]
     L.hr_ivf_scan_step.argtypes = [p, p, c.c_int64, p, c.c_int32, c.c_int32, c.c_int32, p, p, p, c.c_size_t, p]
     L.hr_ivf_scan_step_rows.argtypes = [p, p, c.c_int64, p, c.c_int32, c.c_int32, c.c_int32, p, p, p, p, c.c_size_t, p]
     L.hr_ivf_rescore.argtypes = [p, p, c.c_int64, p, c.c_int32, c.c_int32, c.c_int32, p, p, p, p]
@@ -156,6 +158,14 @@ def hr_ivf_reorder_probes(probe, nq, nprobe, prev, nprev, hot, nhot, out_probe, 
 
 def hr_ivf_list_hits(handle, out_hits, reset=False, stream=None):
     _check(lib.hr_ivf_list_hits(handle, _addr(out_hits), 1 if reset else 0, _stream(stream)))
+
+
+def hr_ivf_hot_lists(handle, gc, out_lists, stream=None):
+    _check(lib.hr_ivf_hot_lists(handle, gc, _addr(out_lists), _stream(stream)))
+
+
+def hr_ivf_refresh_rows(handle, row_begin, row_end, stream=None):
+    _check(lib.hr_ivf_refresh_rows(handle, row_begin, row_end, _stream(stream)))
 
 
 def hr_ivf_stats(handle, workspace, workspace_bytes, nq, nprobe, k):
@@ -294,6 +304,16 @@ class IvfIndex:
         out = torch.empty(self.nlist, dtype=torch.int64, device="cuda")
         hr_ivf_list_hits(self.handle, out, reset)
         return out
+
+    def hot_lists(self, gc):
+        """The gc most frequently probed lists, most frequent first: int32 [gc] on the device."""
+        out = torch.empty(gc, dtype=torch.int32, device="cuda")
+        hr_ivf_hot_lists(self.handle, gc, out)
+        return out
+
+    def refresh_rows(self, row_begin, row_end):
+        """After the vectors of these rows were replaced in place: recompute what is derived from them."""
+        hr_ivf_refresh_rows(self.handle, row_begin, row_end)
 
     def stats(self, nq, nprobe, k):
         ws = self.workspace(nq, nprobe, k)

@@ -727,6 +727,33 @@ int hr_ivf_list_hits(const hr_ivf_index* ix, int64_t* out_hits, int32_t reset, v
     return HR_OK;
 }
 
+int hr_ivf_hot_lists(const hr_ivf_index* ix, int32_t gc, int32_t* out_lists, void* stream)
+{
+    if (int rc = check_index(ix)) return rc;
+    if (gc < 1 || gc > ix->nlist) return fail(HR_ERR_ARG, "gc=%d must be in 1..nlist=%lld", gc, (long long)ix->nlist);
+    if (ix->nlist > 65536) return fail(HR_ERR_UNSUPPORTED, "hr_ivf_hot_lists ranks by counting: nlist=%lld > 65536", (long long)ix->nlist);
+    if (!out_lists) return fail(HR_ERR_ARG, "out_lists is null");
+    HR_HIP(launch_hot_lists(ix->d_hits, (int)ix->nlist, gc, out_lists, (hipStream_t)stream));
+    return HR_OK;
+}
+
+int hr_ivf_refresh_rows(hr_ivf_index* ix, int64_t row_begin, int64_t row_end, void* stream)
+{
+    if (int rc = check_index(ix)) return rc;
+    if (row_begin < 0 || row_end < row_begin || row_end > ix->N)
+        return fail(HR_ERR_ARG, "rows %lld..%lld outside 0..N=%lld", (long long)row_begin, (long long)row_end, (long long)ix->N);
+    const int64_t n = row_end - row_begin;
+    if (n == 0) return HR_OK;
+    hipStream_t s = (hipStream_t)stream;
+    const size_t esize = ix->dtype == HR_F32 ? 4 : 2;
+    const char* rows = (const char*)ix->vectors + (size_t)row_begin * ix->d * esize;
+    HR_HIP(launch_row_norms(rows, ix->dtype, n, ix->d, ix->d_row_norm + row_begin, s));
+    if (ix->d_vec_hi)
+        HR_HIP(launch_split_f32((const float*)rows, n * ix->d, (char*)ix->d_vec_hi + (size_t)row_begin * ix->d * 2,
+                                (char*)ix->d_vec_lo + (size_t)row_begin * ix->d * 2, s));
+    return HR_OK;
+}
+
 int hr_ivf_stats(const hr_ivf_index* ix, const void* workspace, size_t workspace_bytes, int64_t nq,
                  int32_t nprobe, int32_t k, int64_t out[4])
 {

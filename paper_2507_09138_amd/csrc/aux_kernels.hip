@@ -52,6 +52,34 @@ hipError_t launch_read_hits(unsigned long long* hits, int64_t n, int64_t* out, i
     return hipGetLastError();
 }
 
+// The gc most frequently probed lists, most frequent first, equal counts by list number: the
+// lists a cache of hot clusters would keep (Section 4.4).  Every list counts the lists that
+// come before it (tiles of the counters pass through LDS); its rank is its place in the output.
+__global__ __launch_bounds__(256) void k_hot_lists(const unsigned long long* hits, int nlist, int gc, int32_t* out)
+{
+    __shared__ unsigned long long s_h[256];
+    const int l = blockIdx.x * 256 + threadIdx.x;
+    const unsigned long long mine = l < nlist ? hits[l] : 0ull;
+    int rank = 0;
+    for (int j0 = 0; j0 < nlist; j0 += 256) {
+        __syncthreads();
+        s_h[threadIdx.x] = j0 + (int)threadIdx.x < nlist ? hits[j0 + threadIdx.x] : 0ull;
+        __syncthreads();
+        const int n = min(256, nlist - j0);
+        for (int t = 0; t < n; t++) {
+            const unsigned long long h = s_h[t];
+            rank += (h > mine || (h == mine && j0 + t < l)) ? 1 : 0;
+        }
+    }
+    if (l < nlist && rank < gc) out[rank] = l;
+}
+
+hipError_t launch_hot_lists(const unsigned long long* hits, int nlist, int gc, int32_t* out, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_hot_lists, dim3((unsigned)((nlist + 255) / 256)), dim3(256), 0, s, hits, nlist, gc, out);
+    return hipGetLastError();
+}
+
 __device__ __forceinline__ float wave_sum(float v)
 {
 #pragma unroll

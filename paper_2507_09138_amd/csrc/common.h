@@ -155,6 +155,7 @@ hipError_t launch_row_norms(const void* rows, int dtype, int64_t nrows, int d, f
 hipError_t launch_prep_queries(const float* q, int64_t nq, int d, int dtype, void* qop_coarse,
                                float* qnorm_coarse, void* qop_scan, float* qnorm_scan, hipStream_t s);
 hipError_t launch_fill_i32(int* p, int64_t n, int v, hipStream_t s);
+hipError_t launch_hot_lists(const unsigned long long* hits, int nlist, int gc, int32_t* out, hipStream_t s);
 hipError_t launch_read_hits(unsigned long long* hits, int64_t n, int64_t* out, int reset, hipStream_t s);
 hipError_t launch_state_thr(const int64_t* ids, const float* scores, const float* qnorm, int64_t nq, int k, int l2,
                             uint32_t* thr, hipStream_t s);

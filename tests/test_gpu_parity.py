@@ -630,3 +630,49 @@ def test_float32_lists_with_and_without_row_tables(metric):
     a.close()
     b.close()
 
+
+def test_hot_lists_by_access_counters():
+    """The most frequently probed lists, exactly as the oracle orders the counters (many lists
+    tie at zero and at small counts)."""
+    hr = _hr()
+    idx = _random_index(20000, 64, 700, "f16", seed=5)
+    ix = hr.IvfIndex(idx.centroids, idx.list_offsets, idx.list_vectors, idx.list_ids)
+    g = torch.Generator().manual_seed(3)
+    for nq, nprobe in ((40, 9), (111, 5)):
+        ix.search(torch.randn(nq, 64, generator=g).cuda(), nprobe, 4, "ip")
+    hits = ix.list_hits().cpu().numpy()
+    assert (hits == 0).sum() > 50 and hits.max() > 1
+    for gc in (1, 10, 256, 257, 700):
+        assert np.array_equal(ix.hot_lists(gc).cpu().numpy(), oracle.hot_lists(hits, gc))
+    with pytest.raises(hr.HrError):
+        ix.hot_lists(701)
+    ix.close()
+
+
+@pytest.mark.parametrize("dtype,metric", [("f32", "l2"), ("f16", "l2"), ("bf16", "ip")])
+def test_refresh_rows_after_vectors_replaced_in_place(dtype, metric):
+    """A cluster's vectors replaced in place (what an asynchronous load of another cluster into its
+    slot does): after hr_ivf_refresh_rows the index answers like one loaded from the new data, bit
+    for bit (squared norms, and for float32 the row tables, are derived again)."""
+    hr = _hr()
+    idx = _random_index(16000, 128, 30, dtype, seed=9)
+    ix = hr.IvfIndex(idx.centroids, idx.list_offsets, idx.list_vectors, idx.list_ids)
+    q = torch.randn(64, 128, generator=torch.Generator().manual_seed(1)).cuda()
+    before = ix.search(q, 30, 10, metric)
+    off = idx.list_offsets
+    lst = int(torch.argmax(off[1:] - off[:-1]))
+    r0, r1 = int(off[lst]), int(off[lst + 1])
+    new = (torch.randn(r1 - r0, 128, generator=torch.Generator().manual_seed(2)) * 3.0).to(idx.list_vectors.dtype)
+    idx.list_vectors[r0:r1] = new.cuda()
+    ix.refresh_rows(r0, r1)
+    ix.refresh_rows(r0, r0)                                   # empty range: nothing to do
+    got = ix.search(q, 30, 10, metric)
+    fresh = hr.IvfIndex(idx.centroids, idx.list_offsets, idx.list_vectors, idx.list_ids)
+    want = fresh.search(q, 30, 10, metric)
+    assert torch.equal(got[0], want[0]) and torch.equal(got[1], want[1])
+    assert not torch.equal(before[0], want[0])                # (the replaced rows do matter)
+    with pytest.raises(hr.HrError):
+        ix.refresh_rows(5, idx.list_vectors.shape[0] + 1)
+    ix.close()
+    fresh.close()
+

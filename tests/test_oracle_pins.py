@@ -386,3 +386,12 @@ def test_reorder_probes_worked_example_and_invariants():
         for gno in range(3):
             members = [pos[int(l)] for l in out[i][group == gno]]
             assert members == sorted(members)
+
+
+def test_hot_lists_worked_example():
+    """Counts 5 0 9 5 0 9 1: the two lists with 9 first (lower number first), then the two with
+    5, then 1, then the never-probed ones in list order (worked by hand)."""
+    hits = [5, 0, 9, 5, 0, 9, 1]
+    assert oracle.hot_lists(hits, 7).tolist() == [2, 5, 0, 3, 6, 1, 4]
+    assert oracle.hot_lists(hits, 3).tolist() == [2, 5, 0]
+
