@@ -676,3 +676,24 @@ def test_refresh_rows_after_vectors_replaced_in_place(dtype, metric):
     ix.close()
     fresh.close()
 
+
+
+def test_seeded_sweep_of_small_configurations():
+    """Forty seeded draws of (N, d, lists, storage, metric, batch, nprobe, k) from the corners of
+    the supported ranges (one row, one list, one query, k at the buffer-size boundaries 24/25,
+    64/65 and at its maximum, nprobe up to 300), each through coarse, scan and search against
+    the oracle."""
+    rng = np.random.default_rng(1)
+    for c in range(40):
+        d = int(rng.choice([64, 128, 256, 512, 768, 1024]))
+        dtype = str(rng.choice(["f32", "f16", "bf16"]))
+        metric = str(rng.choice(["ip", "l2"]))
+        nlist = int(rng.choice([1, 2, 7, 33, 150, 600]))
+        n = int(rng.choice([1, 15, 17, 300, 5000, 40000]))
+        nq = int(rng.choice([1, 2, 17, 129, 700]))
+        nprobe = int(min(nlist, rng.choice([1, 2, 9, 64, 300])))
+        k = int(rng.choice([1, 2, 10, 24, 25, 64, 65, 100, 128]))
+        print(f"case sweep {c}: n={n} d={d} nlist={nlist} {dtype} {metric} nq={nq} nprobe={nprobe} k={k}", flush=True)
+        idx = _random_index(n, d, nlist, dtype, seed=1000 + c)
+        q = torch.randn(nq, d, generator=torch.Generator().manual_seed(c)).cuda()
+        compare_all(idx, q, nprobe=nprobe, k=k, metric=metric)
