@@ -69,8 +69,13 @@ enum {
  * per list of access counters; and, for HR_F32 storage only, the rows as two binary16 tables
  * (hi and scaled lo part: N*d*4 bytes, as much as list_vectors itself) when that takes at most
  * half of the device memory free at the time, and dtype is not HR_F32 | HR_LOAD_NO_ROW_TABLES —
- * without them the search gives the same results, more slowly.  The call synchronises `stream`
- * before returning.
+ * without them the search gives the same results, more slowly.  For HR_BF16 storage likewise
+ * the rows as one binary16 table (N*d*2 bytes; every bfloat16 value of magnitude 2^-14 .. 65504
+ * is a binary16 value, smaller ones are rounded to a multiple of 2^-24), unless a value exceeds
+ * 65504 or HR_LOAD_NO_ROW_TABLES is given: the lists are then multiplied with the query rounded
+ * to binary16 (as HR_F16 lists are) and twice as many queries share one pass over a list; without
+ * the table the query goes in as bfloat16 hi + lo parts, results equal within the tolerance of
+ * 16-bit storage, not bit for bit.  The call synchronises `stream` before returning.
  */
 int hr_ivf_load(const float* centroids, const int64_t* list_offsets, const void* list_vectors,
                 const int64_t* list_ids, int64_t nlist, int64_t N, int32_t d, int32_t dtype,

@@ -145,6 +145,8 @@ struct hr_ivf_index {
     void* d_cent_lo;       // [nlist, d] binary16: (centroid - hi) * 2^11
     void* d_vec_hi;        // float32 lists only, when memory allows: [N, d] binary16 hi and scaled lo tables of the
     void* d_vec_lo;        // rows (the split the scan would otherwise redo for every block it stages); else null
+    void* d_vec16;         // bfloat16 lists only, when memory and the value range allow: [N, d] the rows as binary16
+    int* d_flag;           // device int: a bfloat16 value did not fit binary16
     unsigned long long* d_hits;   // [nlist] probes per list since load / last reset
     int num_cus;
     int lds_limit;
@@ -154,7 +156,12 @@ struct hr_ivf_index {
 };
 
 // storage type the list scan runs on
-static int scan_dtype(const hr_ivf_index* ix) { return ix->d_vec_hi ? (int)HR_F16X2 : ix->dtype; }
+static int scan_dtype(const hr_ivf_index* ix) { return ix->d_vec_hi ? (int)HR_F16X2 : (ix->d_vec16 ? (int)HR_F16 : ix->dtype); }
+// form of the query operand the list scan multiplies (what k_prep_queries is asked for)
+static int operand_dtype(const hr_ivf_index* ix) { const int s = scan_dtype(ix); return s == HR_F16X2 ? (int)HR_F32 : s; }
+// rows and their type for the kernels that read single rows (threshold seeding, rescoring)
+static int row_dtype(const hr_ivf_index* ix) { return ix->d_vec16 ? (int)HR_F16 : ix->dtype; }
+static const void* row_table(const hr_ivf_index* ix) { return ix->d_vec16 ? ix->d_vec16 : ix->vectors; }
 
 static bool dim_supported(int d)
 {
@@ -219,8 +226,8 @@ static Plan make_plan(const hr_ivf_index* ix, int64_t nq, int nprobe, int k)
     p.o_thr = take((size_t)nq * 2 * 4);
     p.o_qop_c = take((size_t)nq * 2 * ix->d * 2);
     p.o_qnorm_c = take((size_t)nq * 4);
-    p.o_qop_s = ix->dtype == HR_F32 ? p.o_qop_c
-                                    : take((size_t)nq * (ix->dtype == HR_BF16 ? 2 : 1) * ix->d * 2);
+    p.o_qop_s = operand_dtype(ix) == HR_F32 ? p.o_qop_c
+                                            : take((size_t)nq * (operand_dtype(ix) == HR_BF16 ? 2 : 1) * ix->d * 2);
     p.o_qnorm_s = take((size_t)nq * 4);
     p.o_probe = take((size_t)pairs * 4);
     p.o_pair_entry = take((size_t)pairs * 4);
@@ -333,7 +340,32 @@ int hr_ivf_load(const float* centroids, const int64_t* list_offsets, const void*
             else e = launch_split_f32((const float*)list_vectors, N * d, ix->d_vec_hi, ix->d_vec_lo, s);
         }
     }
+    if (e == hipSuccess && dtype == HR_BF16 && N > 0 && row_tables) {
+        // bfloat16 lists: as binary16 (same bytes again) every value keeps its 8 significant bits,
+        // and the scan can multiply them with the query rounded to binary16 in one MFMA column
+        // per query instead of two (bfloat16 hi and lo parts): twice the queries per work item.
+        // Only when that leaves at least half of the free device memory and no value overflows.
+        const size_t bytes = (size_t)N * d * 2;
+        size_t free_b = 0, total_b = 0;
+        if (hipMemGetInfo(&free_b, &total_b) == hipSuccess && bytes <= free_b / 2) {
+            if (hipMalloc(&ix->d_vec16, bytes) != hipSuccess) ix->d_vec16 = nullptr;
+            if (ix->d_vec16 && hipMalloc(&ix->d_flag, sizeof(int)) != hipSuccess) { (void)hipFree(ix->d_vec16); ix->d_vec16 = nullptr; ix->d_flag = nullptr; }
+            if (!ix->d_vec16) (void)hipGetLastError();
+            else {
+                e = hipMemsetAsync(ix->d_flag, 0, sizeof(int), s);
+                if (e == hipSuccess) e = launch_bf16_to_f16(list_vectors, N * d, ix->d_vec16, ix->d_flag, s);
+            }
+        }
+    }
     if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e == hipSuccess && ix->d_vec16) {
+        int over = 0;
+        e = hipMemcpy(&over, ix->d_flag, sizeof(int), hipMemcpyDeviceToHost);
+        if (e == hipSuccess && over) {          // values beyond binary16: the lists are scanned as bfloat16
+            (void)hipFree(ix->d_vec16); (void)hipFree(ix->d_flag);
+            ix->d_vec16 = nullptr; ix->d_flag = nullptr;
+        }
+    }
     delete[] h_off;
     if (e != hipSuccess) {
         if (ix->d_list_off) (void)hipFree(ix->d_list_off);
@@ -344,6 +376,8 @@ int hr_ivf_load(const float* centroids, const int64_t* list_offsets, const void*
         if (ix->d_hits) (void)hipFree(ix->d_hits);
         if (ix->d_vec_hi) (void)hipFree(ix->d_vec_hi);
         if (ix->d_vec_lo) (void)hipFree(ix->d_vec_lo);
+        if (ix->d_vec16) (void)hipFree(ix->d_vec16);
+        if (ix->d_flag) (void)hipFree(ix->d_flag);
         delete ix;
         return fail(HR_ERR_HIP, "hr_ivf_load: %s", hipGetErrorString(e));
     }
@@ -410,6 +444,8 @@ int hr_ivf_free(hr_ivf_index* ix)
     (void)hipFree(ix->d_hits);
     if (ix->d_vec_hi) (void)hipFree(ix->d_vec_hi);
     if (ix->d_vec_lo) (void)hipFree(ix->d_vec_lo);
+    if (ix->d_vec16) (void)hipFree(ix->d_vec16);
+    if (ix->d_flag) (void)hipFree(ix->d_flag);
     delete ix;
     return HR_OK;
 }
@@ -519,7 +555,7 @@ static int enqueue_scan(const hr_ivf_index* ix, const Plan& p, char* ws, int64_t
         HR_HIP(launch_state_thr(out_ids, out_scores, (const float*)(ws + p.o_qnorm_s), nq, k, metric == HR_METRIC_L2,
                                 (uint32_t*)(ws + p.o_thr) + nq, s));
     SeedArgs sd{};
-    sd.rows = ix->vectors; sd.row_norm = ix->d_row_norm; sd.qop = ws + p.o_qop_s;
+    sd.rows = row_table(ix); sd.row_norm = ix->d_row_norm; sd.qop = ws + p.o_qop_s;
     sd.probe = probe; sd.list_off = ix->d_list_off;
     sd.thr = (uint32_t*)(ws + p.o_thr) + nq;
     sd.hpar = (float*)(zero + p.zoff_hpar);
@@ -527,10 +563,10 @@ static int enqueue_scan(const hr_ivf_index* ix, const Plan& p, char* ws, int64_t
     sd.seed_rows = k + 28 < 64 ? 64 : ((k + 28 + 15) & ~15);
     if (sd.seed_rows > 192) sd.seed_rows = 192;
     sd.l2 = metric == HR_METRIC_L2;
-    HR_HIP(launch_seed(ix->dtype, ix->d, sd, s));
+    HR_HIP(launch_seed(row_dtype(ix), ix->d, sd, s));
 
     ScanArgs a{};
-    a.rows = ix->d_vec_hi ? ix->d_vec_hi : ix->vectors;
+    a.rows = ix->d_vec_hi ? ix->d_vec_hi : row_table(ix);
     a.rows_lo = ix->d_vec_lo;
     a.row_norm = ix->d_row_norm;
     a.row_ids = ix->ids;
@@ -596,8 +632,8 @@ int hr_ivf_search(const hr_ivf_index* ix, const float* queries, int64_t nq, int3
     char* ws = (char*)workspace;
     hipStream_t s = (hipStream_t)stream;
     if (int rc = enqueue_clear(p, ws, nq, s)) return rc;
-    HR_HIP(launch_prep_queries(queries, nq, ix->d, ix->dtype, ws + p.o_qop_c, (float*)(ws + p.o_qnorm_c),
-                               ix->dtype == HR_F32 ? nullptr : ws + p.o_qop_s, (float*)(ws + p.o_qnorm_s), s));
+    HR_HIP(launch_prep_queries(queries, nq, ix->d, operand_dtype(ix), ws + p.o_qop_c, (float*)(ws + p.o_qnorm_c),
+                               operand_dtype(ix) == HR_F32 ? nullptr : ws + p.o_qop_s, (float*)(ws + p.o_qnorm_s), s));
     int32_t* probe = (int32_t*)(ws + p.o_probe);
     if (int rc = enqueue_coarse(ix, p, ws, nq, nprobe, metric, probe, nullptr, s)) return rc;
     return enqueue_scan(ix, p, ws, nq, probe, nprobe, k, metric, out_ids, out_scores, s);
@@ -636,8 +672,8 @@ int hr_ivf_scan(const hr_ivf_index* ix, const float* queries, int64_t nq, const 
     char* ws = (char*)workspace;
     hipStream_t s = (hipStream_t)stream;
     if (int rc = enqueue_clear(p, ws, nq, s)) return rc;
-    const bool f32 = ix->dtype == HR_F32;
-    HR_HIP(launch_prep_queries(queries, nq, ix->d, ix->dtype, f32 ? ws + p.o_qop_c : nullptr, nullptr,
+    const bool f32 = operand_dtype(ix) == HR_F32;
+    HR_HIP(launch_prep_queries(queries, nq, ix->d, operand_dtype(ix), f32 ? ws + p.o_qop_c : nullptr, nullptr,
                                f32 ? nullptr : ws + p.o_qop_s, (float*)(ws + p.o_qnorm_s), s));
     return enqueue_scan(ix, p, ws, nq, probe_ids, nprobe, k, metric, out_ids, out_scores, s);
 }
@@ -657,8 +693,8 @@ static int scan_step(const hr_ivf_index* ix, const float* queries, int64_t nq, c
     char* ws = (char*)workspace;
     hipStream_t s = (hipStream_t)stream;
     if (int rc = enqueue_clear(p, ws, nq, s)) return rc;
-    const bool f32 = ix->dtype == HR_F32;
-    HR_HIP(launch_prep_queries(queries, nq, ix->d, ix->dtype, f32 ? ws + p.o_qop_c : nullptr, nullptr,
+    const bool f32 = operand_dtype(ix) == HR_F32;
+    HR_HIP(launch_prep_queries(queries, nq, ix->d, operand_dtype(ix), f32 ? ws + p.o_qop_c : nullptr, nullptr,
                                f32 ? nullptr : ws + p.o_qop_s, (float*)(ws + p.o_qnorm_s), s));
     return enqueue_scan(ix, p, ws, nq, probe_ids, nprobe, k, metric, io_ids, io_scores, s, true, io_rows);
 }
@@ -689,7 +725,7 @@ int hr_ivf_rescore(const hr_ivf_index* ix, const float* queries, int64_t nq, con
     if (metric != HR_METRIC_IP && metric != HR_METRIC_L2) return fail(HR_ERR_ARG, "unknown metric %d", metric);
     if (nq == 0) return HR_OK;
     if (!queries || !rows || !out_ids || !out_scores || !out_rows) return fail(HR_ERR_ARG, "queries / rows / outputs null");
-    HR_HIP(launch_rescore(queries, nq, ix->d, ix->dtype, ix->vectors, ix->d_row_norm, ix->ids, ix->N, rows, m, k,
+    HR_HIP(launch_rescore(queries, nq, ix->d, row_dtype(ix), row_table(ix), ix->d_row_norm, ix->ids, ix->N, rows, m, k,
                           metric == HR_METRIC_L2, out_ids, out_scores, out_rows, (hipStream_t)stream));
     return HR_OK;
 }
@@ -748,6 +784,8 @@ int hr_ivf_refresh_rows(hr_ivf_index* ix, int64_t row_begin, int64_t row_end, vo
     const size_t esize = ix->dtype == HR_F32 ? 4 : 2;
     const char* rows = (const char*)ix->vectors + (size_t)row_begin * ix->d * esize;
     HR_HIP(launch_row_norms(rows, ix->dtype, n, ix->d, ix->d_row_norm + row_begin, s));
+    if (ix->d_vec16)
+        HR_HIP(launch_bf16_to_f16(rows, n * ix->d, (char*)ix->d_vec16 + (size_t)row_begin * ix->d * 2, ix->d_flag, s));
     if (ix->d_vec_hi)
         HR_HIP(launch_split_f32((const float*)rows, n * ix->d, (char*)ix->d_vec_hi + (size_t)row_begin * ix->d * 2,
                                 (char*)ix->d_vec_lo + (size_t)row_begin * ix->d * 2, s));

@@ -1,5 +1,7 @@
 // Small kernels around the list scan: query operand preparation, row norms, grouping of
 // (query, list) probes by list, and the per-query merge of the scan's partial results.
+#include <algorithm>
+
 #include "scan_kernel.h"
 
 namespace hr {
@@ -21,18 +23,39 @@ hipError_t launch_fill_i32(int* p, int64_t n, int v, hipStream_t s)
 // float32 -> binary16 hi + 2^11-scaled binary16 lo (the split the scan applies to float32 rows)
 __global__ void k_split_f32(const float* x, int64_t n, _Float16* hi, _Float16* lo)
 {
-    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n) return;
-    const float v = x[i];
-    const _Float16 h = (_Float16)v;
-    hi[i] = h;
-    lo[i] = (_Float16)((v - (float)h) * 2048.0f);
+    // (grid-stride: a launch may not have 2^32 threads or more)
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+        const float v = x[i];
+        const _Float16 h = (_Float16)v;
+        hi[i] = h;
+        lo[i] = (_Float16)((v - (float)h) * 2048.0f);
+    }
+}
+
+// bfloat16 -> binary16 (exact for magnitudes from 2^-14 to 65504: 8 significant bits fit in 11;
+// below that the result is rounded to a multiple of 2^-24; above, the flag is raised)
+__global__ void k_bf16_to_f16(const uint16_t* x, int64_t n, _Float16* out, int* overflow)
+{
+    bool over = false;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+        const float v = __builtin_bit_cast(float, ((uint32_t)x[i]) << 16);
+        over |= !(fabsf(v) <= 65504.0f);                       // (also for NaN)
+        out[i] = (_Float16)v;
+    }
+    if (over) atomicOr(overflow, 1);
+}
+
+hipError_t launch_bf16_to_f16(const void* x, int64_t n, void* out, int* overflow, hipStream_t s)
+{
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_bf16_to_f16, dim3((unsigned)std::min<int64_t>((n + 255) / 256, 1 << 20)), dim3(256), 0, s, (const uint16_t*)x, n, (_Float16*)out, overflow);
+    return hipGetLastError();
 }
 
 hipError_t launch_split_f32(const float* x, int64_t n, void* hi, void* lo, hipStream_t s)
 {
     if (n <= 0) return hipSuccess;
-    hipLaunchKernelGGL(k_split_f32, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, x, n, (_Float16*)hi, (_Float16*)lo);
+    hipLaunchKernelGGL(k_split_f32, dim3((unsigned)std::min<int64_t>((n + 255) / 256, 1 << 20)), dim3(256), 0, s, x, n, (_Float16*)hi, (_Float16*)lo);
     return hipGetLastError();
 }
 

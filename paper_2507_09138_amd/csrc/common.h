@@ -165,6 +165,7 @@ hipError_t launch_reorder_probes(const int32_t* probe, int np, const int32_t* pr
 hipError_t launch_rescore(const float* q, int64_t nq, int d, int dtype, const void* rows, const float* row_norm,
                           const int64_t* row_ids, int64_t nrows, const int32_t* cand, int m, int k, int l2,
                           int64_t* out_ids, float* out_scores, int32_t* out_rows, hipStream_t s);
+hipError_t launch_bf16_to_f16(const void* x, int64_t n, void* out, int* overflow, hipStream_t s);
 hipError_t launch_split_f32(const float* x, int64_t n, void* hi, void* lo, hipStream_t s);
 
 struct BucketArgs {

@@ -58,13 +58,13 @@ def _scale(q, xn, metric):
     return floor_for(q.shape[1]) * (qn * xn if metric == "ip" else qn ** 2 + xn ** 2)
 
 
-def compare_all(index, queries, nprobe, k, metric, sample=None, label=""):
+def compare_all(index, queries, nprobe, k, metric, sample=None, label="", row_tables=True):
     """coarse vs oracle; scan (with the GPU's probe lists) vs oracle; search == coarse + scan."""
     hr = _hr()
     cfg = index.cfg
     tau = TAU[cfg.dtype]
     host = Host(index)
-    ix = hr.IvfIndex(index.centroids, index.list_offsets, index.list_vectors, index.list_ids)
+    ix = hr.IvfIndex(index.centroids, index.list_offsets, index.list_vectors, index.list_ids, row_tables=row_tables)
     q_dev = queries
     t0 = time.time()
     probe_g, pscore_g = ix.coarse(q_dev, nprobe, metric)
@@ -697,3 +697,31 @@ def test_seeded_sweep_of_small_configurations():
         idx = _random_index(n, d, nlist, dtype, seed=1000 + c)
         q = torch.randn(nq, d, generator=torch.Generator().manual_seed(c)).cuda()
         compare_all(idx, q, nprobe=nprobe, k=k, metric=metric)
+
+
+@pytest.mark.parametrize("metric", ["ip", "l2"])
+def test_bfloat16_lists_without_the_binary16_table(metric):
+    """bfloat16 lists are scanned from a binary16 copy made at load (query rounded to binary16, one
+    MFMA column per query); without it, as bfloat16 with the query in bfloat16 hi and lo parts.
+    The second way is checked here (the first is what every other bfloat16 test runs), on random
+    data with k on both sides of the buffer-size boundary and on the scaled large workload."""
+    print(f"case bf16 without table {metric}", flush=True)
+    idx = _random_index(30000, 256, 40, "bf16", seed=83, dup=2)
+    q = torch.randn(200, 256, generator=torch.Generator().manual_seed(5)).cuda()
+    compare_all(idx, q, nprobe=9, k=10, metric=metric, row_tables=False)
+    compare_all(idx, q, nprobe=9, k=100, metric=metric, row_tables=False)
+    if metric == "l2":
+        cfg = synth.scaled(synth.CONFIGS["C5"], N=262144, nlist=256, nq=256, nprobe=32)
+        ci = synth.make_index(cfg, "cuda")
+        compare_all(ci, synth.make_queries(cfg, ci)[0], cfg.nprobe, cfg.k, cfg.metric, row_tables=False, label="C5 scaled, no table")
+
+
+def test_bfloat16_values_beyond_binary16_keep_the_bfloat16_scan():
+    """A value above 65504 cannot go into the binary16 table: the load notices and the lists are
+    scanned as bfloat16 (results against the oracle as usual)."""
+    idx = _random_index(6000, 64, 12, "bf16", seed=19)
+    idx.list_vectors[1234, 7] = 1.0e6
+    idx.list_vectors[77, 0] = -3.0e5
+    q = torch.randn(50, 64, generator=torch.Generator().manual_seed(8)).cuda()
+    compare_all(idx, q, nprobe=12, k=5, metric="ip")
+
