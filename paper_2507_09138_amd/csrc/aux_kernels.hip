@@ -640,7 +640,17 @@ __global__ __launch_bounds__(256) void k_topk_rows(TopkArgs a)
 #pragma unroll
             for (int j = 0; j < 8; j++) {
                 const uint32_t u = enc_key(v[j]);
-                if (i0 + j * 64 + lane < a.n && (u & mask) == prefix) atomicAdd(&hist[(u >> shift) & 255], 1);
+                const bool in = i0 + j * 64 + lane < a.n && (u & mask) == prefix;
+                const int dg = (u >> shift) & 255;
+                // keys of one row mostly share their leading digits: the lanes whose digit is
+                // that of the first counted lane are added in one go, only the others one by
+                // one (64 atomic additions to one LDS word would go one after the other)
+                const unsigned long long min_ = __builtin_amdgcn_ballot_w64(in);
+                if (min_ == 0) continue;
+                const int d0 = __builtin_amdgcn_readlane(dg, __builtin_ctzll(min_));
+                const unsigned long long same = __builtin_amdgcn_ballot_w64(in && dg == d0);
+                if (lane == 0) atomicAdd(&hist[d0], (int)__builtin_popcountll(same));
+                if (in && dg != d0) atomicAdd(&hist[dg], 1);
             }
         }
         wave_sync();
