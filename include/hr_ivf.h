@@ -102,6 +102,8 @@ size_t hr_ivf_workspace_bytes(const hr_ivf_index* index, int64_t nq, int32_t npr
  *               are scratch.  Two calls that overlap in time must not share a workspace.
  *   stream      hipStream_t (as void*).  The call only enqueues kernels on it: no allocation,
  *               no host synchronisation; outputs are valid once the stream reaches that point.
+ *               (Kernels only, no memset or copy nodes: the call can be captured in a HIP
+ *               graph and replayed with new contents in the same buffers.)
  */
 int hr_ivf_search(const hr_ivf_index* index, const float* queries, int64_t nq, int32_t nprobe,
                   int32_t k, int32_t metric, int64_t* out_ids, float* out_scores,
