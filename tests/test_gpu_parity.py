@@ -725,3 +725,33 @@ def test_bfloat16_values_beyond_binary16_keep_the_bfloat16_scan():
     q = torch.randn(50, 64, generator=torch.Generator().manual_seed(8)).cuda()
     compare_all(idx, q, nprobe=12, k=5, metric="ip")
 
+
+
+def test_two_searches_in_flight_on_two_streams():
+    """Two calls on the same index, each with its own stream, workspace and outputs, enqueued
+    back to back so that they overlap on the device: both must give what they give alone."""
+    hr = _hr()
+    idx = _random_index(60000, 128, 64, "f16", seed=41)
+    ix = hr.IvfIndex(idx.centroids, idx.list_offsets, idx.list_vectors, idx.list_ids)
+    gen = torch.Generator().manual_seed(6)
+    qa, qb = torch.randn(700, 128, generator=gen).cuda(), torch.randn(500, 128, generator=gen).cuda()
+    want_a = ix.search(qa, 16, 10, "ip")
+    want_b = ix.search(qb, 24, 20, "l2")
+    torch.cuda.synchronize()
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    out = []
+    for q, nprobe, k in ((qa, 16, 10), (qb, 24, 20)):
+        nbytes = hr.hr_ivf_workspace_bytes(ix.handle, q.shape[0], nprobe, k)
+        out.append((torch.empty(q.shape[0], k, dtype=torch.int64, device="cuda"),
+                    torch.empty(q.shape[0], k, dtype=torch.float32, device="cuda"),
+                    torch.empty(nbytes, dtype=torch.uint8, device="cuda")))
+    for _ in range(3):
+        for t in out:
+            t[0].fill_(-9)
+        torch.cuda.synchronize()
+        hr.hr_ivf_search(ix.handle, qa, 700, 16, 10, hr.HR_METRIC_IP, out[0][0], out[0][1], out[0][2], out[0][2].numel(), stream=sa)
+        hr.hr_ivf_search(ix.handle, qb, 500, 24, 20, hr.HR_METRIC_L2, out[1][0], out[1][1], out[1][2], out[1][2].numel(), stream=sb)
+        torch.cuda.synchronize()
+        assert torch.equal(out[0][0], want_a[0]) and torch.equal(out[0][1], want_a[1])
+        assert torch.equal(out[1][0], want_b[0]) and torch.equal(out[1][1], want_b[1])
+    ix.close()
