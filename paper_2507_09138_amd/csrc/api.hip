@@ -61,52 +61,32 @@ size_t scan_lds_bytes(int dtype, int d, int cap, int shape, int nbuf)
 
 static constexpr int kLdsLimit = 160 * 1024;      // LDS per workgroup on gfx950
 
-// Workgroup shape, number of staging buffers and selection buffer capacity for a scan.
-// Shape: 8 waves (two per SIMD) when the selection buffers of that many query columns still
-// fit in LDS, else 4 waves with half the columns.  Buffers: float32 rows are staged through
-// registers into 2; 16-bit rows go straight to LDS, best into 6 or 4 (blocks in pairs, one
-// barrier per pair; for 4 the selection buffers may give up a little of their capacity), else
-// into 3 or 2.  shape -1 = no fit.
+// Workgroup shape, number of staging buffers and selection buffers of a list scan.
+// Rows that go straight from HBM to LDS (16-bit storage, and float32 lists split into two
+// binary16 tables at load): 8 waves, the selection buffers in global memory (they are the
+// item's result slots; a wave alone uses those of its columns and candidates are few), and
+// LDS left to as many 16-row buffers as fit: 6 or 4 (blocks in pairs, one barrier per pair),
+// else 3 or 2.  More rows on their way is what counts when few queries share a list and the
+// scan is bound by HBM (measured with the buffers in LDS and 4 row buffers instead: C4 +2 %,
+// the 38 M x 1024 index +2.5 %, C3 +1 %).
+// float32 rows split on the fly are staged through registers into 2 padded buffers: selection
+// buffers in LDS for small k when they fit (8 waves, else 4 with half the columns), in global
+// memory for large k.  shape -1 = no fit.
 struct ScanPick { int shape, nbuf, cap, gsel; };
 static ScanPick pick_shape(int dtype, int d, int k)
 {
     const int cap = hr::sel_cap(k);
-    if (dtype == hr::HR_F16X2) {
-        // float32 lists split into two binary16 tables at load: 4 bytes per element to stage, so
-        // LDS goes to the row buffers (as many as fit; d = 768: 3, d = 1024: 2) and the selection
-        // buffers to global memory
+    if (dtype != HR_F32) {
         for (int nbuf : {6, 4, 3, 2})
             if (hr::scan_lds_bytes(dtype, d, 0, hr::SCAN_WIDE, nbuf) <= (size_t)kLdsLimit) return {hr::SCAN_WIDE, nbuf, cap, 1};
         return {-1, 0, 0, 0};
     }
     if (cap > 64) {
-        // large k: selection buffers of that size would take most of LDS; they live in global
-        // memory (the result slots themselves) and LDS is left to the row buffers
-        if (dtype == HR_F32) {
-            if (hr::scan_lds_bytes(dtype, d, 0, hr::SCAN_WIDE, 2) <= (size_t)kLdsLimit) return {hr::SCAN_WIDE, 2, cap, 1};
-            return {-1, 0, 0, 0};
-        }
-        for (int nbuf : {6, 4, 3, 2})
-            if (hr::scan_lds_bytes(dtype, d, 0, hr::SCAN_WIDE, nbuf) <= (size_t)kLdsLimit) return {hr::SCAN_WIDE, nbuf, cap, 1};
+        if (hr::scan_lds_bytes(dtype, d, 0, hr::SCAN_WIDE, 2) <= (size_t)kLdsLimit) return {hr::SCAN_WIDE, 2, cap, 1};
         return {-1, 0, 0, 0};
     }
-    const int cap_min = k + hr::kAppendMax + 4 + 24 < cap ? k + hr::kAppendMax + 4 + 24 : cap;   // least worth having
-    auto fit_cap = [&](int shape, int nbuf) {     // largest capacity (multiple of 4) that fits, or 0
-        for (int c = cap; c >= cap_min; c -= 4)
-            if (hr::scan_lds_bytes(dtype, d, c, shape, nbuf) <= (size_t)kLdsLimit) return c;
-        return 0;
-    };
-    const int shapes[2] = {hr::SCAN_WIDE, hr::SCAN_NARROW};
-    for (int shape : shapes) {
-        if (dtype == HR_F32) {
-            if (hr::scan_lds_bytes(dtype, d, cap, shape, 2) <= (size_t)kLdsLimit) return {shape, 2, cap, 0};
-            continue;
-        }
-        if (hr::scan_lds_bytes(dtype, d, cap, shape, 6) <= (size_t)kLdsLimit) return {shape, 6, cap, 0};   // (short rows: a third pair on its way)
-        if (const int c = fit_cap(shape, 4)) return {shape, 4, c, 0};
-        for (int nbuf = 3; nbuf >= 2; nbuf--)
-            if (hr::scan_lds_bytes(dtype, d, cap, shape, nbuf) <= (size_t)kLdsLimit) return {shape, nbuf, cap, 0};
-    }
+    for (int shape : {hr::SCAN_WIDE, hr::SCAN_NARROW})
+        if (hr::scan_lds_bytes(dtype, d, cap, shape, 2) <= (size_t)kLdsLimit) return {shape, 2, cap, 0};
     return {-1, 0, 0, 0};
 }
 

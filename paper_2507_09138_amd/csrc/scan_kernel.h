@@ -1016,8 +1016,12 @@ inline hipError_t launch_scan_dtype(int d, const ScanArgs& a, int shape, int gri
         return a.gsel ? launch_scan_shape<DT, 1, 8, true>(d, a, grid, lds, s) : launch_scan_shape<DT, 1, 8, false>(d, a, grid, lds, s);
     } else {
         if (a.gsel) return shape == SCAN_WIDE ? launch_scan_shape<DT, 1, 8, true>(d, a, grid, lds, s) : hipErrorInvalidValue;
-        return shape == SCAN_WIDE ? launch_scan_shape<DT, 1, 8, false>(d, a, grid, lds, s)
-                                  : launch_scan_shape<DT, 1, 4, false>(d, a, grid, lds, s);
+        if constexpr (DT == HR_F32) {
+            return shape == SCAN_WIDE ? launch_scan_shape<DT, 1, 8, false>(d, a, grid, lds, s)
+                                      : launch_scan_shape<DT, 1, 4, false>(d, a, grid, lds, s);
+        } else {
+            return hipErrorInvalidValue;       // (16-bit lists always keep their selection buffers in global memory)
+        }
     }
 }
 
