@@ -616,8 +616,9 @@ struct TopkArgs {
 
 __global__ __launch_bounds__(256) void k_topk_rows(TopkArgs a)
 {
+    constexpr int kCollect = 1024;                  // entries one wave can collect in LDS (>= HR_NPROBE_MAX)
     __shared__ int s_hist[4][256];
-    __shared__ Cand s_ent[4][HR_NPROBE_MAX];
+    __shared__ Cand s_ent[4][kCollect];
     const int lane = lane_id(), wave = threadIdx.x >> 6;
     const int64_t q = (int64_t)blockIdx.x * 4 + wave;
     if (q >= a.nq) return;
@@ -625,9 +626,91 @@ __global__ __launch_bounds__(256) void k_topk_rows(TopkArgs a)
     int* hist = s_hist[wave];
     Cand* ent = s_ent[wave];
     const int k = min(a.k, a.n);
+
+    // ---- the quick way, one pass over the row: a lower bound t0 from 512 keys spread over the
+    // row (their m-th largest, m chosen so that about 3k keys of the row are expected above
+    // it), every key >= t0 collected in LDS, the k best of those selected there.  It is exact
+    // whenever at least k and at most kCollect keys were collected (all keys >= the k-th best
+    // are then among them); otherwise the radix passes below do the work.
+    bool done = false;
+    {
+        uint32_t t0 = 0;                            // (below every encoded key: short rows are collected whole)
+        if (a.n > kCollect) {
+            constexpr int S = 512;
+            uint32_t sv[S / 64];
+#pragma unroll
+            for (int j = 0; j < S / 64; j++) sv[j] = enc_key(row[(int)(((long long)(j * 64 + lane) * a.n) / S)]);
+            int want = (int)((3LL * k * S + a.n - 1) / a.n);
+            want = max(2, min(S, want));
+            unsigned long long alive[S / 64];
+#pragma unroll
+            for (int j = 0; j < S / 64; j++) alive[j] = ~0ull;
+            for (int b = 31; b >= 0; b--) {
+                unsigned long long ones[S / 64];
+                int c1 = 0;
+#pragma unroll
+                for (int j = 0; j < S / 64; j++) {
+                    ones[j] = alive[j] & __builtin_amdgcn_ballot_w64((sv[j] >> b) & 1u);
+                    c1 += __builtin_popcountll(ones[j]);
+                }
+                if (c1 >= want) {
+                    t0 |= 1u << b;
+#pragma unroll
+                    for (int j = 0; j < S / 64; j++) alive[j] = ones[j];
+                } else {
+                    want -= c1;
+#pragma unroll
+                    for (int j = 0; j < S / 64; j++) alive[j] &= ~ones[j];
+                }
+            }
+        }
+        int cnt = 0;
+        auto collect = [&](float key, int i, bool valid) __attribute__((always_inline)) {
+            const uint32_t u = enc_key(key);
+            const bool take = valid && u >= t0;
+            const unsigned long long m = __builtin_amdgcn_ballot_w64(take);
+            if (m == 0) return;
+            const int pos = cnt + lanes_below(m);
+            if (take && pos < kCollect) ent[pos] = Cand{u, (uint32_t)i};
+            cnt += __builtin_popcountll(m);
+        };
+        // (what hides the latency of the loads is how many are in flight: 8 of 16 bytes per
+        // lane when the rows allow it; the order of collection does not matter)
+        if ((a.n & 3) == 0) {
+            const float4* row4 = (const float4*)row;
+            const int n4 = a.n >> 2;
+            for (int i0 = 0; i0 < n4; i0 += 64 * 8) {
+                float4 v[8];
+#pragma unroll
+                for (int j = 0; j < 8; j++) v[j] = row4[min(i0 + j * 64 + lane, n4 - 1)];
+#pragma unroll
+                for (int j = 0; j < 8; j++) {
+                    const int i4 = i0 + j * 64 + lane;
+                    collect(v[j].x, i4 * 4, i4 < n4);
+                    collect(v[j].y, i4 * 4 + 1, i4 < n4);
+                    collect(v[j].z, i4 * 4 + 2, i4 < n4);
+                    collect(v[j].w, i4 * 4 + 3, i4 < n4);
+                }
+            }
+        } else {
+            for (int i0 = 0; i0 < a.n; i0 += 64 * 8) {
+                float v[8];
+#pragma unroll
+                for (int j = 0; j < 8; j++) { const int i = i0 + j * 64 + lane; v[j] = row[min(i, a.n - 1)]; }
+#pragma unroll
+                for (int j = 0; j < 8; j++) collect(v[j], i0 + j * 64 + lane, i0 + j * 64 + lane < a.n);
+            }
+        }
+        wave_sync();
+        if (cnt >= k && cnt <= kCollect) {
+            if (cnt > k) wave_select<kCollect / 64>(ent, cnt, k, nullptr);      // (equal keys: lower index first)
+            done = true;
+        }
+    }
+
     uint32_t prefix = 0, mask = 0;
     int need = k;                                   // entries still to take among those matching the prefix
-    for (int shift = 24; shift >= 0; shift -= 8) {
+    for (int shift = 24; shift >= 0 && !done; shift -= 8) {
 #pragma unroll
         for (int j = 0; j < 4; j++) hist[lane * 4 + j] = 0;
         wave_sync();
@@ -679,7 +762,7 @@ __global__ __launch_bounds__(256) void k_topk_rows(TopkArgs a)
     }
     // prefix = k-th best key; `need` of the entries equal to it are taken, lowest index first
     int n_gt = 0, n_eq = 0;
-    for (int i0 = 0; i0 < a.n; i0 += 64 * 8) {
+    for (int i0 = 0; i0 < a.n && !done; i0 += 64 * 8) {
         float v[8];
 #pragma unroll
         for (int j = 0; j < 8; j++) { const int i = i0 + j * 64 + lane; v[j] = row[min(i, a.n - 1)]; }

@@ -217,12 +217,12 @@ def test_coarse_duplicate_centroids_lower_index_first():
 
 
 def test_coarse_in_chunks_of_queries():
-    """More queries than one chunk of the coarse key table holds (128 MiB / (4 nlist) = 8192 at
+    """More queries than one chunk of the coarse key table holds (512 MiB / (4 nlist) = 32768 at
     nlist = 4096): every chunk, and the ragged last one, against the oracle."""
     print("case coarse chunks", flush=True)
     hr = _hr()
     g = torch.Generator(device="cpu").manual_seed(43)
-    nlist, d, nq = 4096, 64, 8192 + 8192 + 333
+    nlist, d, nq = 4096, 64, 32768 + 32768 + 333
     cent = torch.randn(nlist, d, generator=g)
     x = torch.randn(nlist, d, generator=g).to(torch.float16)
     off = torch.arange(0, nlist + 1, dtype=torch.int64)
@@ -231,7 +231,7 @@ def test_coarse_in_chunks_of_queries():
     ix = hr.IvfIndex(cent.cuda(), off, x.cuda(), ids.cuda())
     probe, score = ix.coarse(q.cuda(), 16, "ip")
     probe, score = probe.cpu().numpy(), score.cpu().numpy()
-    sel = np.concatenate([np.arange(0, 40), np.arange(8170, 8230), np.arange(16370, 16420), np.arange(nq - 40, nq)])
+    sel = np.concatenate([np.arange(0, 40), np.arange(32740, 32800), np.arange(65510, 65560), np.arange(nq - 40, nq)])
     qs = np.ascontiguousarray(q.numpy()[sel])
     probe_o, score_o = oracle.coarse(qs, cent.numpy(), 16, oracle.IP)
     cn = float(np.sqrt((cent.numpy().astype(np.float64) ** 2).sum(1)).mean())
