@@ -755,3 +755,47 @@ def test_two_searches_in_flight_on_two_streams():
         assert torch.equal(out[0][0], want_a[0]) and torch.equal(out[0][1], want_a[1])
         assert torch.equal(out[1][0], want_b[0]) and torch.equal(out[1][1], want_b[1])
     ix.close()
+
+
+def test_coarse_selection_when_the_one_pass_way_does_not_apply():
+    """The nprobe best centroids are normally found in one pass from a sampled lower bound; two
+    rows built so that this cannot work (more keys at the bound than the collection holds; a
+    bound above the nprobe-th key) must come out of the full radix select, exact as ever."""
+    hr = _hr()
+    g = torch.Generator(device="cpu").manual_seed(77)
+    d = 64
+    v = torch.randn(d, generator=g)
+    v = v / v.norm()
+
+    def run(cent, nprobe):
+        nlist = cent.shape[0]
+        off = torch.arange(0, nlist + 1, dtype=torch.int64)
+        x = torch.randn(nlist, d, generator=g).to(torch.float16)
+        ix = hr.IvfIndex(cent.cuda(), off, x.cuda(), torch.arange(nlist, dtype=torch.int64).cuda())
+        q = (v[None, :] + 0.01 * torch.randn(40, d, generator=g)).contiguous()
+        probe, score = ix.coarse(q.cuda(), nprobe, "ip")
+        probe, score = probe.cpu().numpy(), score.cpu().numpy()
+        probe_o, score_o = oracle.coarse(q.numpy(), cent.numpy(), nprobe, oracle.IP)
+        cn = float(np.sqrt((cent.numpy().astype(np.float64) ** 2).sum(1)).mean())
+        st = check_probes(probe, score, probe_o, score_o,
+                          lambda i, c: oracle.pair_scores(q.numpy(), cent.numpy(), "f32", oracle.IP, np.full(len(c), i), c),
+                          "ip", TAU["f32"], _scale(q.numpy(), cn, "ip"))
+        ix.close()
+        return probe, probe_o, st
+
+    # 2000 copies of the best centroid among 3000: far more equal keys at the top than the 1024 collected
+    cent = 0.05 * torch.randn(3000, d, generator=g)
+    copies = torch.randperm(3000, generator=g)[:2000]
+    cent[copies] = v * 2.0
+    probe, probe_o, st = run(cent, 100)
+    lowest = np.sort(copies.numpy())[:100]
+    assert (probe == lowest[None, :]).all() and np.array_equal(probe, probe_o)       # equal keys: lower index first
+    # 50 outstanding centroids, all on sampled positions (every 4th of 2048): the sampled bound lands among them,
+    # fewer than nprobe = 64 keys reach it
+    cent = 0.05 * torch.randn(2048, d, generator=g)
+    top = torch.arange(0, 200, 4)
+    cent[top] = v[None, :] * (2.0 + 0.01 * torch.arange(50, dtype=torch.float32)[:, None])
+    probe, probe_o, st = run(cent, 64)
+    assert np.array_equal(np.sort(probe[:, :50], axis=1), np.broadcast_to(top.numpy(), (40, 50)))
+    assert np.array_equal(probe[:, :50], probe_o[:, :50])
+    print(f"[parity coarse fallback] {st}", flush=True)
