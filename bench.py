@@ -23,7 +23,7 @@ MFMA_PEAK_TFLOPS = {"f16": 2500.0, "bf16": 2500.0, "f32": 2500.0}   # f32 rows r
 ESIZE = {"f32": 4, "f16": 2, "bf16": 2}
 # HBM bytes per list-scan launch (read + written) from the rocprofv3 FETCH_SIZE / WRITE_SIZE counter runs
 # summarised under profiles/ (counters cannot be read from inside this process); other workloads: null
-MEASURED_TRAFFIC = {"C3": 8.89e9 + 0.04e9}
+MEASURED_TRAFFIC = {"C3": 8.94e9 + 0.04e9}
 
 
 def cpu_baseline(cfg, idx, q, target_s=30.0):
