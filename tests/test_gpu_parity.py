@@ -799,3 +799,52 @@ def test_coarse_selection_when_the_one_pass_way_does_not_apply():
     assert np.array_equal(np.sort(probe[:, :50], axis=1), np.broadcast_to(top.numpy(), (40, 50)))
     assert np.array_equal(probe[:, :50], probe_o[:, :50])
     print(f"[parity coarse fallback] {st}", flush=True)
+
+
+def test_seeded_sweep_of_stepwise_retrievals_started_from_cached_rows():
+    """Twenty-four seeded draws of storage type, metric, sizes, k, cache size and sub-stage width:
+    a carried result started from random cached rows (absent, repeated, inside and outside the
+    probed lists), then the probe lists (with holes) searched a few at a time; expected: the
+    oracle's k best over the union of the cached rows and the rows of the probed lists, every
+    vector once, rows and ids naming the same vectors.  Half of the draws load without row tables."""
+    hr = _hr()
+    rng = np.random.default_rng(3)
+    for c in range(24):
+        d = int(rng.choice([64, 128, 256]))
+        dtype = str(rng.choice(["f32", "f16", "bf16"]))
+        metric = str(rng.choice(["ip", "l2"]))
+        nlist = int(rng.choice([5, 33, 150]))
+        n = int(rng.choice([300, 5000, 30000]))
+        nq = int(rng.choice([1, 17, 200]))
+        nprobe = int(min(nlist, rng.choice([2, 9, 40])))
+        k = int(rng.choice([1, 10, 25, 100]))
+        m = int(rng.choice([1, 20, 128]))
+        step = int(rng.choice([1, 3, 8]))
+        print(f"case steps sweep {c}: n={n} d={d} nlist={nlist} {dtype} {metric} nq={nq} nprobe={nprobe} k={k} m={m} step={step}", flush=True)
+        idx = _random_index(n, d, nlist, dtype, seed=2000 + c)
+        host = Host(idx)
+        ix = hr.IvfIndex(idx.centroids, idx.list_offsets, idx.list_vectors, idx.list_ids, row_tables=bool(rng.integers(0, 2)))
+        q = torch.randn(nq, d, generator=torch.Generator().manual_seed(c)).cuda()
+        cache = rng.integers(-1, idx.list_vectors.shape[0], (nq, m)).astype(np.int32)
+        probe = np.stack([rng.permutation(nlist)[:nprobe] for _ in range(nq)]).astype(np.int32)
+        probe[rng.random(probe.shape) < 0.1] = -1
+        state = ix.rescore(q, torch.from_numpy(cache).cuda(), k, metric)
+        pd = torch.from_numpy(probe).cuda()
+        for s0 in range(0, nprobe, step):
+            ix.scan_step_rows(q, pd[:, s0:s0 + step].contiguous(), state, metric)
+        ids_g, sc_g, rows_g = [t.cpu().numpy() for t in state]
+        qn = synth.to_numpy(q)
+        union = [np.concatenate([cache[i]] + [np.arange(host.off[l], host.off[l + 1]) for l in probe[i] if l >= 0])
+                 for i in range(nq)]
+        mm = METRIC[metric]
+        ids_o, sc_o, _ = oracle.topk_of_rows(qn, host.vec, dtype, host.ids, union, k, mm)
+        check_topk(ids_g, sc_g, ids_o, sc_o,
+                   lambda i, ids: oracle.pair_scores(qn, host.vec, dtype, mm, np.full(len(ids), i), host.rows_of(ids)),
+                   metric, TAU[dtype], _scale(qn, host.xnorm(), metric))
+        have = ids_g >= 0
+        assert np.array_equal(host.ids[rows_g[have]], ids_g[have])
+        assert ((ids_g >= 0) == (ids_o >= 0)).all()
+        for i in range(nq):
+            r = rows_g[i][rows_g[i] >= 0]
+            assert len(np.unique(r)) == len(r)
+        ix.close()
