@@ -47,7 +47,7 @@ enum {
 #define HR_K_MAX 128          /* largest k */
 #define HR_NPROBE_MAX 512     /* largest nprobe (the paper probes 128 to 512 clusters: Section 6.1) */
 #define HR_WORKSPACE_ALIGN 256
-#define HR_LOAD_NO_ROW_TABLES 0x100   /* or-ed into hr_ivf_load's dtype: see there */
+#define HR_LOAD_ROW_TABLES 0x100      /* or-ed into hr_ivf_load's dtype: see there */
 
 /*
  * hr_ivf_load — wrap an IVF-Flat index that already lives in HBM (Section 2.2: vectors
@@ -57,8 +57,9 @@ enum {
  *                 list_offsets[0] = 0, list_offsets[nlist] = N, non-decreasing (empty lists allowed).
  *                 Copied during the call.
  *   list_vectors  DEV  [N, d] row-major in `dtype` (HR_F32 / HR_F16 / HR_BF16), list-major.
- *   list_ids      DEV  [N] int64, the label reported for each row (any values; ties between equal
- *                 scores are broken by ascending label).
+ *   list_ids      DEV  [N] int64 >= 0, the label reported for each row (ties between equal scores
+ *                 are broken by ascending label; a negative id marks an empty place in results and
+ *                 carried results, so a negative label is refused: HR_ERR_ARG).
  *   d             supported: 64, 128, 256, 512, 768, 1024 (else HR_ERR_UNSUPPORTED).
  *   N < 2^31.  Values must be finite and, for HR_F32 storage and for centroids/queries, of
  *   magnitude below 65504 (they pass through binary16 pairs inside the kernels).
@@ -66,16 +67,18 @@ enum {
  * centroids, list_vectors and list_ids are BORROWED: they must stay valid and unchanged until
  * hr_ivf_free.  The library allocates (hipMalloc) derived tables: device copies of the offsets,
  * 4 bytes per row / per centroid of squared norms, the centroids as two binary16 tables, 8 bytes
- * per list of access counters; and, for HR_F32 storage only, the rows as two binary16 tables
- * (hi and scaled lo part: N*d*4 bytes, as much as list_vectors itself) when that takes at most
- * half of the device memory free at the time, and dtype is not HR_F32 | HR_LOAD_NO_ROW_TABLES —
- * without them the search gives the same results, more slowly.  For HR_BF16 storage likewise
- * the rows as one binary16 table (N*d*2 bytes; every bfloat16 value of magnitude 2^-14 .. 65504
- * is a binary16 value, smaller ones are rounded to a multiple of 2^-24), unless a value exceeds
- * 65504 or HR_LOAD_NO_ROW_TABLES is given: the lists are then multiplied with the query rounded
- * to binary16 (as HR_F16 lists are) and twice as many queries share one pass over a list; without
- * the table the query goes in as bfloat16 hi + lo parts, results equal within the tolerance of
- * 16-bit storage, not bit for bit.  The call synchronises `stream` before returning.
+ * per list of access counters.  Nothing the size of list_vectors, unless the caller asks for it:
+ * with dtype = HR_F32 | HR_LOAD_ROW_TABLES the rows are also kept as two binary16 tables (hi and
+ * scaled lo part: N*d*4 bytes, as much as list_vectors itself) which the scan then reads instead of
+ * splitting every row block on the fly: same products in the same order, the same bits, faster.
+ * With HR_BF16 | HR_LOAD_ROW_TABLES the rows are also kept as one binary16 table (N*d*2 bytes; every
+ * bfloat16 value of magnitude 2^-14 .. 65504 is a binary16 value, smaller ones are rounded to a
+ * multiple of 2^-24): the lists are then multiplied with the query rounded to binary16 (as HR_F16
+ * lists are) and twice as many queries share one pass over a list; without the table the query goes
+ * in as bfloat16 hi + lo parts; the two ways agree within the tolerance of 16-bit storage, not bit
+ * for bit.  The tables are made only when they take at most half of the device memory free at the
+ * time and, for bfloat16, no value exceeds 65504; otherwise the flag has no effect.  HR_F16 ignores
+ * it.  The call synchronises `stream` before returning.
  */
 int hr_ivf_load(const float* centroids, const int64_t* list_offsets, const void* list_vectors,
                 const int64_t* list_ids, int64_t nlist, int64_t N, int32_t d, int32_t dtype,
@@ -85,8 +88,10 @@ int hr_ivf_load(const float* centroids, const int64_t* list_offsets, const void*
 int hr_ivf_free(hr_ivf_index* index);
 
 /*
- * Bytes of DEV scratch that hr_ivf_search / hr_ivf_coarse / hr_ivf_scan need for this batch
- * shape; 0 on invalid arguments.  Depends only on (index, nq, nprobe, k), never on the data.
+ * Bytes of DEV scratch that hr_ivf_search / hr_ivf_coarse / hr_ivf_scan and the step-wise calls
+ * need for this batch shape; 0 on invalid arguments (nprobe 1 .. HR_NPROBE_MAX: hr_ivf_scan takes
+ * rows of that many places whatever the number of lists).  Depends only on (index, nq, nprobe, k),
+ * never on the data.
  */
 size_t hr_ivf_workspace_bytes(const hr_ivf_index* index, int64_t nq, int32_t nprobe, int32_t k);
 
@@ -110,7 +115,7 @@ int hr_ivf_search(const hr_ivf_index* index, const float* queries, int64_t nq, i
                   void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * hr_ivf_coarse — first half only (Section 2.2: "the nprobe closest clusters are selected").
+ * hr_ivf_coarse — first half only: the choice of the clusters a query is searched in (Section 2.2).
  *   out_probe_ids     DEV [nq, nprobe] int32, best-first (ties: lower list number first).
  *   out_probe_scores  DEV [nq, nprobe] float32 or NULL.
  */
@@ -163,9 +168,11 @@ int hr_ivf_hot_lists(const hr_ivf_index* index, int32_t gc, int32_t* out_lists, 
  * hr_ivf_refresh_rows — after the caller has replaced the vectors of rows row_begin ..
  * row_end-1 in list_vectors (a cluster loaded asynchronously into the place of another one of
  * the same length: the index loading interface of Section 5), recompute what the library
- * derives from them (squared norms; for HR_F32 the binary16 row tables).  Enqueued on `stream`:
- * put it behind the copy, and the next search behind it.  list_ids is read at search time and
- * needs no refresh; list_offsets cannot change.
+ * derives from them (squared norms; the binary16 row tables of HR_LOAD_ROW_TABLES).  Enqueued on
+ * `stream`: put it behind the copy, and the next search behind it.  list_ids is read at search time
+ * and needs no refresh; list_offsets cannot change.  Only with a binary16 table of bfloat16 rows the
+ * call also waits for the stream, to learn whether a new value exceeds 65504: HR_ERR_UNSUPPORTED
+ * then (the table holds an infinity there until the rows are replaced again).
  */
 int hr_ivf_refresh_rows(hr_ivf_index* index, int64_t row_begin, int64_t row_end, void* stream);
 

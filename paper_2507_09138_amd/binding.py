@@ -15,7 +15,7 @@ import torch
 HR_METRIC_IP, HR_METRIC_L2 = 0, 1
 HR_F32, HR_F16, HR_BF16 = 0, 1, 2
 HR_K_MAX, HR_NPROBE_MAX = 128, 512
-HR_LOAD_NO_ROW_TABLES = 0x100
+HR_LOAD_ROW_TABLES = 0x100
 _ERR = {-1: "HR_ERR_ARG", -2: "HR_ERR_HANDLE", -3: "HR_ERR_WORKSPACE", -4: "HR_ERR_HIP",
         -5: "HR_ERR_UNSUPPORTED"}
 _DTYPE = {torch.float32: HR_F32, torch.float16: HR_F16, torch.bfloat16: HR_BF16}
@@ -185,12 +185,50 @@ def hr_ivf_profile_end(handle):
     return n.value, ms.value
 
 
+def _want(t, name, dtype, shape, device):
+    """The kernels read raw addresses: a tensor of another type, shape or device would be read out of bounds.
+    shape entries that are None are free.  Raises HrError(HR_ERR_ARG) before anything reaches the library."""
+    if not isinstance(t, torch.Tensor):
+        raise HrError(-1, f"{name} must be a torch tensor")
+    if t.device != device:
+        raise HrError(-1, f"{name} is on {t.device}, the index is on {device}")
+    if t.dtype != dtype:
+        raise HrError(-1, f"{name} has dtype {t.dtype}, want {dtype}")
+    if t.dim() != len(shape) or any(w is not None and int(g) != int(w) for g, w in zip(t.shape, shape)):
+        raise HrError(-1, f"{name} has shape {tuple(t.shape)}, want {tuple('*' if w is None else w for w in shape)}")
+    return t.contiguous()
+
+
+def _want_int(t, name, shape, device):
+    """Integer tensors of list or row numbers: any integer type is converted to int32 on the way."""
+    if not isinstance(t, torch.Tensor) or t.dtype not in (torch.int32, torch.int64, torch.int16, torch.int8, torch.uint8):
+        raise HrError(-1, f"{name} must be an integer tensor")
+    return _want(t.to(torch.int32), name, torch.int32, shape, device)
+
+
+def _want_range(v, name, lo, hi):
+    if not (lo <= int(v) <= hi):
+        raise HrError(-1, f"{name}={int(v)} must be in {lo}..{hi}")
+    return int(v)
+
+
 class IvfIndex:
     """Keeps the borrowed tensors alive, owns the handle and a growable workspace tensor."""
 
-    def __init__(self, centroids, list_offsets, list_vectors, list_ids, row_tables=True):
-        assert centroids.is_cuda and list_vectors.is_cuda and list_ids.is_cuda
-        assert centroids.dtype == torch.float32 and list_ids.dtype == torch.int64
+    def __init__(self, centroids, list_offsets, list_vectors, list_ids, row_tables=False):
+        """row_tables: also keep float32 / bfloat16 rows as binary16 tables (as many bytes again) that the scan
+        reads instead: HR_LOAD_ROW_TABLES of hr_ivf_load."""
+        for t, name in ((centroids, "centroids"), (list_vectors, "list_vectors"), (list_ids, "list_ids")):
+            if not isinstance(t, torch.Tensor) or not t.is_cuda:
+                raise HrError(-1, f"{name} must be a device tensor")
+        if list_vectors.dtype not in _DTYPE:
+            raise HrError(-1, f"list_vectors has dtype {list_vectors.dtype}, want float32, float16 or bfloat16")
+        self.device = centroids.device
+        _want(centroids, "centroids", torch.float32, (None, None), self.device)
+        _want(list_vectors, "list_vectors", list_vectors.dtype, (None, centroids.shape[1]), self.device)
+        _want(list_ids, "list_ids", torch.int64, (list_vectors.shape[0],), self.device)
+        if not isinstance(list_offsets, torch.Tensor) or list_offsets.dim() != 1 or list_offsets.numel() != centroids.shape[0] + 1:
+            raise HrError(-1, "list_offsets must be a tensor of nlist + 1 entries")
         self.centroids = centroids.contiguous()
         self.list_offsets = list_offsets.to("cpu", torch.int64).contiguous()
         self.list_vectors = list_vectors.contiguous()
@@ -200,7 +238,7 @@ class IvfIndex:
         self.dtype = _DTYPE[self.list_vectors.dtype]
         self.handle = hr_ivf_load(self.centroids, self.list_offsets, self.list_vectors,
                                   self.list_ids, self.nlist, self.N, self.d,
-                                  self.dtype | (0 if row_tables else HR_LOAD_NO_ROW_TABLES))
+                                  self.dtype | (HR_LOAD_ROW_TABLES if row_tables else 0))
         self._ws = None
 
     def close(self):
@@ -223,8 +261,25 @@ class IvfIndex:
             self._ws = torch.empty(max(need, 256), dtype=torch.uint8, device=self.centroids.device)
         return self._ws
 
+    def _queries(self, queries, nq=None):
+        return _want(queries, "queries", torch.float32, (nq, self.d), self.device)
+
+    def _state(self, state, nq, rows):
+        """A carried result (ids, scores[, rows]) of nq queries; returns it with k."""
+        if len(state) != (3 if rows else 2):
+            raise HrError(-1, "state must be (ids, scores, rows)" if rows else "state must be (ids, scores)")
+        ids = state[0]
+        if not isinstance(ids, torch.Tensor) or ids.dim() != 2:
+            raise HrError(-1, "state ids must be a [nq, k] tensor")
+        k = _want_range(ids.shape[1], "k", 1, HR_K_MAX)
+        for t, name, dt in zip(state, ("state ids", "state scores", "state rows"), (torch.int64, torch.float32, torch.int32)):
+            _want(t, name, dt, (nq, k), self.device)
+            if not t.is_contiguous():
+                raise HrError(-1, f"{name} must be contiguous (it is updated in place)")
+        return k
+
     def search(self, queries, nprobe, k, metric="ip"):
-        q = queries.contiguous()
+        q = self._queries(queries)
         nq = q.shape[0]
         ids = torch.empty(nq, k, dtype=torch.int64, device=q.device)
         scores = torch.empty(nq, k, dtype=torch.float32, device=q.device)
@@ -233,7 +288,7 @@ class IvfIndex:
         return ids, scores
 
     def coarse(self, queries, nprobe, metric="ip"):
-        q = queries.contiguous()
+        q = self._queries(queries)
         nq = q.shape[0]
         probe = torch.empty(nq, nprobe, dtype=torch.int32, device=q.device)
         scores = torch.empty(nq, nprobe, dtype=torch.float32, device=q.device)
@@ -242,8 +297,8 @@ class IvfIndex:
         return probe, scores
 
     def scan(self, queries, probe_ids, k, metric="ip"):
-        q = queries.contiguous()
-        pr = probe_ids.to(torch.int32).contiguous()
+        q = self._queries(queries)
+        pr = _want_int(probe_ids, "probe_ids", (q.shape[0], None), self.device)
         nq, nprobe = pr.shape
         ids = torch.empty(nq, k, dtype=torch.int64, device=q.device)
         scores = torch.empty(nq, k, dtype=torch.float32, device=q.device)
@@ -251,42 +306,44 @@ class IvfIndex:
         hr_ivf_scan(self.handle, q, nq, pr, nprobe, k, _METRIC[metric], ids, scores, ws, ws.numel())
         return ids, scores
 
-    def new_state(self, nq, k, device="cuda"):
+    def new_state(self, nq, k):
         """An empty carried result for scan_step: ids -1."""
-        return (torch.full((nq, k), -1, dtype=torch.int64, device=device),
-                torch.zeros(nq, k, dtype=torch.float32, device=device))
+        return (torch.full((nq, k), -1, dtype=torch.int64, device=self.device),
+                torch.zeros(nq, k, dtype=torch.float32, device=self.device))
 
-    def new_state_rows(self, nq, k, device="cuda"):
+    def new_state_rows(self, nq, k):
         """An empty carried result with row numbers, for scan_step_rows."""
-        return self.new_state(nq, k, device) + (torch.full((nq, k), -1, dtype=torch.int32, device=device),)
+        return self.new_state(nq, k) + (torch.full((nq, k), -1, dtype=torch.int32, device=self.device),)
 
     def scan_step(self, queries, probe_ids, state, metric="ip"):
         """One sub-stage: merges the lists in probe_ids into the carried result (ids, scores), in place."""
-        q = queries.contiguous()
-        pr = probe_ids.to(torch.int32).contiguous()
+        q = self._queries(queries)
+        pr = _want_int(probe_ids, "probe_ids", (q.shape[0], None), self.device)
         nq, nprobe = pr.shape
+        k = self._state(state, nq, False)
         ids, scores = state
-        k = ids.shape[1]
         ws = self.workspace(nq, nprobe, k)
         hr_ivf_scan_step(self.handle, q, nq, pr, nprobe, k, _METRIC[metric], ids, scores, ws, ws.numel())
         return ids, scores
 
     def scan_step_rows(self, queries, probe_ids, state, metric="ip"):
         """scan_step on a carried result (ids, scores, rows) that also holds the row number of every entry."""
-        q = queries.contiguous()
-        pr = probe_ids.to(torch.int32).contiguous()
+        q = self._queries(queries)
+        pr = _want_int(probe_ids, "probe_ids", (q.shape[0], None), self.device)
         nq, nprobe = pr.shape
+        k = self._state(state, nq, True)
         ids, scores, rows = state
-        k = ids.shape[1]
         ws = self.workspace(nq, nprobe, k)
         hr_ivf_scan_step_rows(self.handle, q, nq, pr, nprobe, k, _METRIC[metric], ids, scores, rows, ws, ws.numel())
         return ids, scores, rows
 
     def rescore(self, queries, rows, k, metric="ip"):
         """The k best of the given rows [nq, m] for the queries: a carried result (ids, scores, rows)."""
-        q = queries.contiguous()
-        r = rows.to(torch.int32).contiguous()
+        q = self._queries(queries)
+        r = _want_int(rows, "rows", (q.shape[0], None), self.device)
         nq, m = r.shape
+        _want_range(m, "m", 1, HR_K_MAX)
+        _want_range(k, "k", 1, HR_K_MAX)
         ids = torch.empty(nq, k, dtype=torch.int64, device=q.device)
         scores = torch.empty(nq, k, dtype=torch.float32, device=q.device)
         out_rows = torch.empty(nq, k, dtype=torch.int32, device=q.device)
@@ -294,20 +351,22 @@ class IvfIndex:
         return ids, scores, out_rows
 
     def lists_of_rows(self, rows):
-        r = rows.to(torch.int32).contiguous()
+        if not isinstance(rows, torch.Tensor):
+            raise HrError(-1, "rows must be a torch tensor")
+        r = _want_int(rows, "rows", tuple(rows.shape), self.device)
         out = torch.empty_like(r)
         hr_ivf_lists_of_rows(self.handle, r, r.numel(), out)
         return out
 
     def list_hits(self, reset=False):
         """Probes per list since load / the last reset: int64 [nlist] on the device."""
-        out = torch.empty(self.nlist, dtype=torch.int64, device="cuda")
+        out = torch.empty(self.nlist, dtype=torch.int64, device=self.device)
         hr_ivf_list_hits(self.handle, out, reset)
         return out
 
     def hot_lists(self, gc):
         """The gc most frequently probed lists, most frequent first: int32 [gc] on the device."""
-        out = torch.empty(gc, dtype=torch.int32, device="cuda")
+        out = torch.empty(_want_range(gc, "gc", 1, self.nlist), dtype=torch.int32, device=self.device)
         hr_ivf_hot_lists(self.handle, gc, out)
         return out
 
@@ -322,10 +381,17 @@ class IvfIndex:
 
 def reorder_probes(probe, prev=None, hot=None):
     """Search order of the probe lists [nq, nprobe]: lists in hot first, then those in prev, then the rest."""
-    pr = probe.to(torch.int32).contiguous()
+    if not isinstance(probe, torch.Tensor) or not probe.is_cuda:
+        raise HrError(-1, "probe must be a device tensor")
+    pr = _want_int(probe, "probe", (None, None), probe.device)
     nq, nprobe = pr.shape
-    pv = prev.to(torch.int32).contiguous() if prev is not None else None
-    ht = hot.to(torch.int32).contiguous() if hot is not None else None
+    _want_range(nprobe, "nprobe", 1, HR_NPROBE_MAX)
+    pv = _want_int(prev, "prev", (nq, None), probe.device) if prev is not None else None
+    ht = _want_int(hot, "hot", (nq, None), probe.device) if hot is not None else None
+    if pv is not None:
+        _want_range(pv.shape[1], "nprev", 0, HR_NPROBE_MAX)
+    if ht is not None:
+        _want_range(ht.shape[1], "nhot", 0, HR_K_MAX)
     out = torch.empty_like(pr)
     hr_ivf_reorder_probes(pr, nq, nprobe, pv, pv.shape[1] if pv is not None else 0, ht,
                           ht.shape[1] if ht is not None else 0, out)

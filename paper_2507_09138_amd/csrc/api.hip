@@ -126,7 +126,7 @@ struct hr_ivf_index {
     void* d_vec_hi;        // float32 lists only, when memory allows: [N, d] binary16 hi and scaled lo tables of the
     void* d_vec_lo;        // rows (the split the scan would otherwise redo for every block it stages); else null
     void* d_vec16;         // bfloat16 lists only, when memory and the value range allow: [N, d] the rows as binary16
-    int* d_flag;           // device int: a bfloat16 value did not fit binary16
+    int* d_flag;           // two device ints: [0] a bfloat16 value did not fit binary16, [1] a negative label
     unsigned long long* d_hits;   // [nlist] probes per list since load / last reset
     int num_cus;
     int lds_limit;
@@ -155,21 +155,28 @@ struct Plan {
     // coarse step: centroid table scanned with all queries as one dense bucket
     int shape_c /* workgroup shape, -1 = no fit */, nbuf_c, cap_c, cw_c, nqt_c, seg_c, nseg_c, items_c;
     // list scan
-    int shape_s, nbuf_s, cap_s, gsel_s, cw_s, item_cap;
+    int shape_s, nbuf_s, cap_s, gsel_s, cw_s, item_cap, item_target;
     int slot_stride;                // entries per result slot of the list scan
+    int slot_cap;                   // result slots: one per (list segment, query of the list's bucket)
     size_t o_zero, n_zero;          // ints cleared per call: list_w[nlist], dyn[DYN_COUNT], counters[8], ..., then
     size_t zoff_round, zoff_hist, zoff_hpar;   // (in ints from o_zero) round counters of the queues, per-query key histograms and their parameters
     size_t o_thr;                   // 2*nq ints set to "-inf"
     size_t o_qop_c, o_qnorm_c, o_qop_s, o_qnorm_s;
     size_t o_probe;
-    size_t o_pair_entry, o_bucket_off, o_bucket_q, o_item_base, o_item_tab, o_xq;
+    size_t o_pair_entry, o_bucket_off, o_bucket_q, o_item_base, o_slot_base, o_item_tab, o_xq;
     size_t o_ckeys;                 // coarse step: [cchunk, nlist] keys of one chunk of queries
     int64_t cchunk;                 // queries per coarse chunk
     size_t o_slot_cnt, o_slot_ent;
     size_t total;
 };
 
-static Plan make_plan(const hr_ivf_index* ix, int64_t nq, int nprobe, int k)
+// What bounds the size of a plan: the aimed number of work items of the list scan (segments are sized so that
+// about that many items result: fewer, larger items need fewer result slots) and the bytes of the coarse key table
+// (queries are scored in chunks that fit it).
+struct PlanLimits { int item_target; size_t ckeys_bytes; };
+static constexpr PlanLimits kDefaultLimits = {kItemTarget, (size_t)512 << 20};
+
+static Plan make_plan(const hr_ivf_index* ix, int64_t nq, int nprobe, int k, const PlanLimits& lim = kDefaultLimits)
 {
     Plan p{};
     const int64_t nlist = ix->nlist;
@@ -180,9 +187,10 @@ static Plan make_plan(const hr_ivf_index* ix, int64_t nq, int nprobe, int k)
         if (scan_lds_bytes(HR_F16X2, ix->d, 0, SCAN_WIDE, nbuf) <= (size_t)kLdsLimit) { p.shape_c = SCAN_WIDE; p.nbuf_c = nbuf; }
     p.shape_s = ps.shape; p.nbuf_s = ps.nbuf; p.cap_s = ps.cap; p.gsel_s = ps.gsel;
     p.cw_c = cols_per_set(HR_F32) * shape_sets(p.shape_c < 0 ? 0 : p.shape_c);
-    // queries per coarse chunk: the [chunk, nlist] key table stays within 512 MiB (the more queries per launch the
-    // better both kernels fill the device: C5 four chunks of 2048 queries 1.88 ms, one of 8192 1.45 ms)
-    p.cchunk = (int64_t)(512u << 20) / (nlist * 4) / p.cw_c * p.cw_c;
+    // queries per coarse chunk: the [chunk, nlist] key table stays within its limit, 512 MiB by default (the more
+    // queries per launch the better both kernels fill the device: 16384 lists, four chunks of 2048 queries 1.88 ms,
+    // one of 8192 1.45 ms)
+    p.cchunk = (int64_t)lim.ckeys_bytes / (nlist * 4) / p.cw_c * p.cw_c;
     if (p.cchunk < p.cw_c) p.cchunk = p.cw_c;
     if (p.cchunk > nq) p.cchunk = nq > 0 ? nq : 1;
     p.nqt_c = (int)((p.cchunk + p.cw_c - 1) / p.cw_c);
@@ -195,7 +203,12 @@ static Plan make_plan(const hr_ivf_index* ix, int64_t nq, int nprobe, int k)
     p.items_c = p.nseg_c * p.nqt_c;
     p.cw_s = cols_per_set(scan_dtype(ix)) * shape_sets(p.shape_s < 0 ? 0 : p.shape_s);
     const int64_t pairs = nq * nprobe;
-    p.item_cap = (int)(kItemTarget + pairs / p.cw_s + (pairs < nlist ? pairs : nlist) + 8);
+    // Work items: sum over probed lists of segments x query tiles.  Segments have at least C / item_target rows, C =
+    // sum of rows x tiles, so there are at most item_target items plus one per (list, tile) for the ragged ends.
+    // Result slots: sum of segments x bucket width <= cw x item_target, plus one per pair for the ragged ends.
+    p.item_target = lim.item_target;
+    p.item_cap = (int)(lim.item_target + pairs / p.cw_s + (pairs < nlist ? pairs : nlist) + 8);
+    p.slot_cap = (int)((int64_t)p.cw_s * lim.item_target + pairs);
 
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
@@ -215,10 +228,11 @@ static Plan make_plan(const hr_ivf_index* ix, int64_t nq, int nprobe, int k)
     p.o_bucket_off = take((size_t)(nlist + 1) * 4);
     p.o_bucket_q = take((size_t)pairs * 4);
     p.o_item_base = take((size_t)(nlist + 1) * 4);
+    p.o_slot_base = take((size_t)(nlist + 1) * 4);
     p.o_item_tab = take((size_t)p.item_cap * sizeof(int4));
     p.o_xq = take((size_t)p.item_cap * 8 * 4);
     p.o_ckeys = take((size_t)p.cchunk * nlist * 4);
-    const size_t slots = (size_t)p.item_cap * p.cw_s;
+    const size_t slots = (size_t)p.slot_cap;
     p.o_slot_cnt = take(slots * 4);
     p.slot_stride = p.gsel_s || (p.cap_s <= 64 && p.cap_s > k) ? p.cap_s : k;   // whole selection buffers, nothing to cut (else: k)
     p.o_slot_ent = take(slots * (size_t)p.slot_stride * sizeof(Cand));
@@ -266,8 +280,8 @@ int hr_ivf_load(const float* centroids, const int64_t* list_offsets, const void*
     if (nlist < 1 || nlist >= (1LL << 24)) return fail(HR_ERR_ARG, "nlist=%lld out of range", (long long)nlist);
     if (N < 0 || N >= (1LL << 31)) return fail(HR_ERR_ARG, "N=%lld out of range (< 2^31)", (long long)N);
     if (N > 0 && (!list_vectors || !list_ids)) return fail(HR_ERR_ARG, "list_vectors / list_ids is null");
-    const bool row_tables = !(dtype & HR_LOAD_NO_ROW_TABLES);
-    dtype &= ~HR_LOAD_NO_ROW_TABLES;
+    const bool row_tables = (dtype & HR_LOAD_ROW_TABLES) != 0;
+    dtype &= ~HR_LOAD_ROW_TABLES;
     if (dtype != HR_F32 && dtype != HR_F16 && dtype != HR_BF16) return fail(HR_ERR_ARG, "unknown dtype %d", dtype);
     if (d < 1) return fail(HR_ERR_ARG, "d=%d", d);
     if (!dim_supported(d)) return fail(HR_ERR_UNSUPPORTED, "d=%d not one of 64,128,256,512,768,1024", d);
@@ -302,16 +316,19 @@ int hr_ivf_load(const float* centroids, const int64_t* list_offsets, const void*
     if (e == hipSuccess) e = hipMalloc(&ix->d_cent_hi, (size_t)nlist * d * 2);
     if (e == hipSuccess) e = hipMalloc(&ix->d_cent_lo, (size_t)nlist * d * 2);
     if (e == hipSuccess) e = hipMalloc(&ix->d_hits, (size_t)nlist * 8);
+    if (e == hipSuccess) e = hipMalloc(&ix->d_flag, 2 * sizeof(int));
     if (e == hipSuccess) e = hipMemsetAsync(ix->d_hits, 0, (size_t)nlist * 8, s);
+    if (e == hipSuccess) e = hipMemsetAsync(ix->d_flag, 0, 2 * sizeof(int), s);
+    if (e == hipSuccess) e = launch_check_labels(list_ids, N, ix->d_flag + 1, s);
     if (e == hipSuccess) e = hipMemcpyAsync(ix->d_list_off, h_off, (size_t)(nlist + 1) * 4, hipMemcpyHostToDevice, s);
     if (e == hipSuccess) e = launch_row_norms(list_vectors, dtype, N, d, ix->d_row_norm, s);
     if (e == hipSuccess) e = launch_row_norms(centroids, HR_F32, nlist, d, ix->d_cent_norm, s);
     if (e == hipSuccess) e = launch_split_f32(centroids, nlist * d, ix->d_cent_hi, ix->d_cent_lo, s);
     if (e == hipSuccess && dtype == HR_F32 && N > 0 && row_tables) {
-        // float32 lists: the scan multiplies binary16 hi and lo parts of the rows.  Made once here
-        // (same bytes again: 2 + 2 per element) they go straight from HBM to LDS like 16-bit lists;
-        // made on the fly they pass through registers for every block.  Only when that leaves at
-        // least half of the free device memory; otherwise the scan splits on the fly.
+        // float32 lists, when the caller asks for row tables: the scan multiplies binary16 hi and lo parts
+        // of the rows.  Made once here (same bytes again: 2 + 2 per element) they go straight from HBM to
+        // LDS like 16-bit lists; made on the fly they pass through registers for every block.  Only when
+        // that leaves at least half of the free device memory; otherwise the scan splits on the fly.
         const size_t bytes = (size_t)N * d * 2;
         size_t free_b = 0, total_b = 0;
         if (hipMemGetInfo(&free_b, &total_b) == hipSuccess && 2 * bytes <= free_b / 2) {
@@ -322,33 +339,27 @@ int hr_ivf_load(const float* centroids, const int64_t* list_offsets, const void*
         }
     }
     if (e == hipSuccess && dtype == HR_BF16 && N > 0 && row_tables) {
-        // bfloat16 lists: as binary16 (same bytes again) every value keeps its 8 significant bits,
-        // and the scan can multiply them with the query rounded to binary16 in one MFMA column
-        // per query instead of two (bfloat16 hi and lo parts): twice the queries per work item.
-        // Only when that leaves at least half of the free device memory and no value overflows.
+        // bfloat16 lists, when the caller asks for row tables: as binary16 (same bytes again) every value
+        // keeps its 8 significant bits, and the scan can multiply them with the query rounded to binary16
+        // in one MFMA column per query instead of two (bfloat16 hi and lo parts): twice the queries per
+        // work item.  Only when that leaves at least half of the free device memory and no value overflows.
         const size_t bytes = (size_t)N * d * 2;
         size_t free_b = 0, total_b = 0;
         if (hipMemGetInfo(&free_b, &total_b) == hipSuccess && bytes <= free_b / 2) {
             if (hipMalloc(&ix->d_vec16, bytes) != hipSuccess) ix->d_vec16 = nullptr;
-            if (ix->d_vec16 && hipMalloc(&ix->d_flag, sizeof(int)) != hipSuccess) { (void)hipFree(ix->d_vec16); ix->d_vec16 = nullptr; ix->d_flag = nullptr; }
             if (!ix->d_vec16) (void)hipGetLastError();
-            else {
-                e = hipMemsetAsync(ix->d_flag, 0, sizeof(int), s);
-                if (e == hipSuccess) e = launch_bf16_to_f16(list_vectors, N * d, ix->d_vec16, ix->d_flag, s);
-            }
+            else e = launch_bf16_to_f16(list_vectors, N * d, ix->d_vec16, ix->d_flag, s);
         }
     }
     if (e == hipSuccess) e = hipStreamSynchronize(s);
-    if (e == hipSuccess && ix->d_vec16) {
-        int over = 0;
-        e = hipMemcpy(&over, ix->d_flag, sizeof(int), hipMemcpyDeviceToHost);
-        if (e == hipSuccess && over) {          // values beyond binary16: the lists are scanned as bfloat16
-            (void)hipFree(ix->d_vec16); (void)hipFree(ix->d_flag);
-            ix->d_vec16 = nullptr; ix->d_flag = nullptr;
-        }
+    int flags[2] = {0, 0};                      // [0] a bfloat16 value beyond binary16, [1] a negative label
+    if (e == hipSuccess) e = hipMemcpy(flags, ix->d_flag, sizeof flags, hipMemcpyDeviceToHost);
+    if (e == hipSuccess && ix->d_vec16 && flags[0]) {      // the lists are scanned as bfloat16
+        (void)hipFree(ix->d_vec16);
+        ix->d_vec16 = nullptr;
     }
     delete[] h_off;
-    if (e != hipSuccess) {
+    if (e != hipSuccess || flags[1]) {
         if (ix->d_list_off) (void)hipFree(ix->d_list_off);
         if (ix->d_row_norm) (void)hipFree(ix->d_row_norm);
         if (ix->d_cent_norm) (void)hipFree(ix->d_cent_norm);
@@ -360,6 +371,7 @@ int hr_ivf_load(const float* centroids, const int64_t* list_offsets, const void*
         if (ix->d_vec16) (void)hipFree(ix->d_vec16);
         if (ix->d_flag) (void)hipFree(ix->d_flag);
         delete ix;
+        if (e == hipSuccess) return fail(HR_ERR_ARG, "list_ids holds a negative label (labels must be >= 0: -1 marks an empty place in results)");
         return fail(HR_ERR_HIP, "hr_ivf_load: %s", hipGetErrorString(e));
     }
     ix->magic = kMagic;
@@ -434,20 +446,15 @@ int hr_ivf_free(hr_ivf_index* ix)
 size_t hr_ivf_workspace_bytes(const hr_ivf_index* ix, int64_t nq, int32_t nprobe, int32_t k)
 {
     if (check_index(ix)) return 0;
-    if (check_batch(ix, nq, nprobe, k, HR_METRIC_IP, true)) return 0;
+    // (hr_ivf_scan and its step-wise forms take rows of up to HR_NPROBE_MAX places whatever the number of lists)
+    if (nprobe < 1 || nprobe > HR_NPROBE_MAX) { fail(HR_ERR_ARG, "nprobe=%d must be in 1..%d", nprobe, HR_NPROBE_MAX); return 0; }
+    if (check_batch(ix, nq, nprobe > ix->nlist ? (int)ix->nlist : nprobe, k, HR_METRIC_IP, true)) return 0;
     return make_plan(ix, nq, nprobe, k).total;
 }
 
 }  // extern "C"
 
 // ---------------------------------------------------------------------------------------
-// persistent workgroups: as many as can be resident (LDS and, for 8-wave groups, registers)
-#ifdef HR_SCAN_TIMING
-// development builds only: where the list scan leaves its per-workgroup phase timers
-static long long* g_dbg = nullptr;
-extern "C" void hr_debug_scan_timing(void* p) { g_dbg = (long long*)p; }
-#endif
-
 // persistent workgroups: one per CU (8-wave shape), or two where LDS lets two 4-wave ones share a CU
 static int scan_grid(const hr_ivf_index* ix, size_t lds, int shape)
 {
@@ -522,6 +529,9 @@ static int enqueue_scan(const hr_ivf_index* ix, const Plan& p, char* ws, int64_t
     b.bucket_off = (int*)(ws + p.o_bucket_off);
     b.bucket_q = (int*)(ws + p.o_bucket_q);
     b.item_base = (int*)(ws + p.o_item_base);
+    b.slot_base = (int*)(ws + p.o_slot_base);
+    b.slot_cap = p.slot_cap;
+    b.item_target = p.item_target;
     b.item_tab = (int4*)(ws + p.o_item_tab);
     b.dyn = zero + ix->nlist;
     b.xq = (int*)(ws + p.o_xq);
@@ -566,9 +576,6 @@ static int enqueue_scan(const hr_ivf_index* ix, const Plan& p, char* ws, int64_t
     a.xq_count = b.xq_count;
     a.xq_head = zero + ix->nlist + DYN_COUNT + 16;
     a.xq_stride = p.item_cap;
-#ifdef HR_SCAN_TIMING
-    a.dbg = g_dbg;
-#endif
     a.dense = 0;
     a.nq = (int)nq; a.k = k; a.cap = p.cap_s; a.l2 = metric == HR_METRIC_L2;
     a.nbuf = p.nbuf_s;
@@ -589,8 +596,8 @@ static int enqueue_scan(const hr_ivf_index* ix, const Plan& p, char* ws, int64_t
     m.row_ids = ix->ids;
     m.qnorm = (const float*)(ws + p.o_qnorm_s);
     m.probe = probe; m.pair_entry = b.pair_entry;
-    m.list_off = ix->d_list_off; m.bucket_off = b.bucket_off; m.item_base = b.item_base; m.dyn = b.dyn;
-    m.nq = (int)nq; m.nprobe = nprobe; m.nlist = (int)ix->nlist; m.k = k; m.cw = p.cw_s; m.l2 = a.l2;
+    m.list_off = ix->d_list_off; m.bucket_off = b.bucket_off; m.slot_base = b.slot_base; m.dyn = b.dyn;
+    m.nq = (int)nq; m.nprobe = nprobe; m.nlist = (int)ix->nlist; m.k = k; m.l2 = a.l2;
     m.out_ids = out_ids; m.out_scores = out_scores;
     m.carried = carried ? 1 : 0;
     m.io_rows = io_rows;
@@ -765,8 +772,19 @@ int hr_ivf_refresh_rows(hr_ivf_index* ix, int64_t row_begin, int64_t row_end, vo
     const size_t esize = ix->dtype == HR_F32 ? 4 : 2;
     const char* rows = (const char*)ix->vectors + (size_t)row_begin * ix->d * esize;
     HR_HIP(launch_row_norms(rows, ix->dtype, n, ix->d, ix->d_row_norm + row_begin, s));
-    if (ix->d_vec16)
+    if (ix->d_vec16) {
+        // (the only case in which this call waits for the stream: a new value beyond binary16 cannot go into the
+        // table, and a later search must not read an infinity there)
         HR_HIP(launch_bf16_to_f16(rows, n * ix->d, (char*)ix->d_vec16 + (size_t)row_begin * ix->d * 2, ix->d_flag, s));
+        int over = 0;
+        HR_HIP(hipMemcpyAsync(&over, ix->d_flag, sizeof(int), hipMemcpyDeviceToHost, s));
+        HR_HIP(hipStreamSynchronize(s));
+        if (over) {
+            HR_HIP(hipMemsetAsync(ix->d_flag, 0, sizeof(int), s));
+            return fail(HR_ERR_UNSUPPORTED, "a refreshed bfloat16 value exceeds 65504 and does not fit the binary16 row table: "
+                                            "replace the rows again, or load the index without HR_LOAD_ROW_TABLES");
+        }
+    }
     if (ix->d_vec_hi)
         HR_HIP(launch_split_f32((const float*)rows, n * ix->d, (char*)ix->d_vec_hi + (size_t)row_begin * ix->d * 2,
                                 (char*)ix->d_vec_lo + (size_t)row_begin * ix->d * 2, s));

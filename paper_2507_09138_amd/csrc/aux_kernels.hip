@@ -52,6 +52,21 @@ hipError_t launch_bf16_to_f16(const void* x, int64_t n, void* out, int* overflow
     return hipGetLastError();
 }
 
+// Labels must be non-negative: a negative id marks an empty place in results and carried results.
+__global__ void k_check_labels(const int64_t* ids, int64_t n, int* negative)
+{
+    bool neg = false;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) neg |= ids[i] < 0;
+    if (neg) atomicOr(negative, 1);
+}
+
+hipError_t launch_check_labels(const int64_t* ids, int64_t n, int* negative, hipStream_t s)
+{
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_check_labels, dim3((unsigned)std::min<int64_t>((n + 255) / 256, 1 << 16)), dim3(256), 0, s, ids, n, negative);
+    return hipGetLastError();
+}
+
 hipError_t launch_split_f32(const float* x, int64_t n, void* hi, void* lo, hipStream_t s)
 {
     if (n <= 0) return hipSuccess;
@@ -273,15 +288,15 @@ __global__ __launch_bounds__(1024) void k_bucket_scan(BucketArgs a)
         if (t == 0) { a.bucket_off[a.nlist] = total; a.dyn[DYN_PAIRS] = total; }
     }
     const long long c = block_sum_1024(cost, s_lwave);
-    // rows per segment: about kItemTarget items at most; and, since every item costs some ten
+    // rows per segment: about item_target items at most; and, since every item costs some ten
     // microseconds whatever its size, segments of up to 1024 rows as long as that leaves 1024 items
-    // (C2, one million rows: 1024 items of 1024 rows, 0.60 ms; 4096 items of 256 rows, 0.65 ms)
-    long long segll = (c + kItemTarget - 1) / kItemTarget;
+    // (one million rows in 1024 lists: 1024 items of 1024 rows, 0.60 ms; 4096 items of 256 rows, 0.65 ms)
+    long long segll = (c + a.item_target - 1) / a.item_target;
     const long long fewer = c / 1024 < 1024 ? c / 1024 : 1024;
     if (segll < fewer) segll = fewer;
     segll = (segll + 15) & ~15LL;
     if (segll < kMinSegRows) segll = kMinSegRows;
-    if (segll > (1LL << 30)) segll = 1LL << 30;
+    if (segll > 0x7ffffff0LL) segll = 0x7ffffff0LL;          // (a list has fewer than 2^31 rows: one segment then)
     const int seg = (int)segll;
     const long long r = block_sum_1024(rows, s_lwave);
     if (t == 0) {
@@ -290,15 +305,16 @@ __global__ __launch_bounds__(1024) void k_bucket_scan(BucketArgs a)
         a.dyn[DYN_ROWS_HI] = (int)(r >> 32);
     }
 
-    // pass 2: work items per list = segments * query tiles
+    // pass 2: work items per list = segments * query tiles; result slots per list = segments * bucket width
+    // (one slot per (segment, query of the bucket): slot of entry e of segment s = slot_base[l] + s * w + e)
     auto list_items = [&](int l, int& nseg, int& nqt) {
         const int w = a.list_w[l];
         const int len = a.list_off[l + 1] - a.list_off[l];
         nseg = (w > 0 && len > 0) ? (len + seg - 1) / seg : 0;
         nqt = (w + a.cw - 1) / a.cw;
     };
-    int items = 0;
-    for (int l = l0; l < l1; l++) { int nseg, nqt; list_items(l, nseg, nqt); items += nseg * nqt; }
+    int items = 0, slots = 0;
+    for (int l = l0; l < l1; l++) { int nseg, nqt; list_items(l, nseg, nqt); items += nseg * nqt; slots += nseg * a.list_w[l]; }
     {
         int run = block_scan_1024(items, s_wave, total);
         for (int l = l0; l < l1; l++) {
@@ -311,6 +327,15 @@ __global__ __launch_bounds__(1024) void k_bucket_scan(BucketArgs a)
             // never more than the table holds (cannot happen: the host sizes it from the same bound)
             a.dyn[DYN_ITEMS] = min(total, a.item_cap);
         }
+    }
+    {
+        int run = block_scan_1024(slots, s_wave, total);
+        for (int l = l0; l < l1; l++) {
+            a.slot_base[l] = run;
+            int nseg, nqt; list_items(l, nseg, nqt);
+            run += nseg * a.list_w[l];
+        }
+        if (t == 0) { a.slot_base[a.nlist] = total; a.dyn[DYN_SLOTS] = total; }
     }
 }
 
@@ -375,13 +400,18 @@ __global__ __launch_bounds__(256) void k_item_expand(BucketArgs a)
     int nqt = (w + a.cw - 1) / a.cw;
     int nseg = (len + seg - 1) / seg;
     long long base = a.item_base[l];
+    const long long sbase = a.slot_base[l];
     for (int s = lane; s < nseg; s += 64) {
         const int x = queue_of(l, s), slot = x * kRounds + round_of(s);
         const int pos = a.round_cnt[slot] + atomicAdd(&a.round_cur[slot], nqt);
         for (int t = 0; t < nqt; t++) {
             long long idx = base + (long long)s * nqt + t;
-            if (idx < a.item_cap && pos + t < a.item_cap) {
-                a.item_tab[idx] = make_int4(l, s, t, 0);
+            // first result slot of the item: entries t*cw .. of segment s (the last tile of a bucket has fewer
+            // than cw entries; what lies behind them belongs to the next segment and is never touched)
+            const long long first = sbase + (long long)s * w + (long long)t * a.cw;
+            // (the guards cannot fail: the host sizes the tables from the same bounds)
+            if (idx < a.item_cap && pos + t < a.item_cap && first + min(a.cw, w - t * a.cw) <= a.slot_cap) {
+                a.item_tab[idx] = make_int4(l, s, t, (int)first);
                 a.xq[(size_t)x * a.item_cap + pos + t] = (int)idx;
             }
         }
@@ -402,8 +432,8 @@ hipError_t launch_bucketing(const BucketArgs& a, hipStream_t s)
 }
 
 // ------------------------------------------------------------------------------------------
-// Per-query merge of the scan's partial results (the "effective reduction" of Section 5 and
-// the per-request merge of Section 4.4): one wave per query walks the slots that hold its
+// Per-query merge of the scan's partial results (the reduction step of the cluster search of
+// Section 5 and the per-request merge of Section 4.4): one wave per query walks the slots that hold its
 // candidates, keeps the k best in an LDS buffer pruned as in the scan, then orders the
 // survivors by (key, label) and writes the output row.
 // Key (larger is better) of an entry of a carried result, from its reported score: the score
@@ -524,9 +554,7 @@ __global__ __launch_bounds__(256) void k_merge(MergeArgs a)
                 int l = a.probe[q * a.nprobe + p];
                 int e = a.pair_entry[q * a.nprobe + p];
                 int w = a.bucket_off[l + 1] - a.bucket_off[l];
-                int nqt = (w + a.cw - 1) / a.cw;
-                size_t item = (size_t)a.item_base[l] + (size_t)s * nqt + (size_t)(e / a.cw);
-                slot = item * a.cw + (size_t)(e % a.cw);
+                slot = (size_t)a.slot_base[l] + (size_t)s * w + (size_t)e;
             }
             c = a.slot_cnt[slot];
         }

@@ -16,8 +16,8 @@ constexpr int kRowPad = 32;                // bytes of LDS padding per staged ro
                                            // for the 16-rows x 16-byte MFMA fragment reads (16 is 2-way)
 constexpr int kAppendMax = 16;             // most candidates one column can gain per block
 constexpr int kMinSegRows = 256;           // smallest rows-per-work-item
-constexpr int kItemTarget = 4096;
-constexpr int kHistBins = 64;              // per-query histogram of candidate keys (one bin per lane)         // aimed number of scan work items per batch
+constexpr int kItemTarget = 4096;          // aimed number of scan work items per batch
+constexpr int kHistBins = 64;              // per-query histogram of candidate keys (one bin per lane)
 
 // columns (queries) per 16-column MFMA set: 16 when the query operand is one binary16 row, 8
 // when it is a (hi, lo) pair occupying two MFMA columns.
@@ -86,15 +86,15 @@ struct ScanArgs {
     const int64_t* row_ids;     // [nrows] labels, or nullptr: label = row number
     const void* qop;            // query operand rows (layout depends on dtype)
     uint32_t* thr;              // [nq] running per-query lower bound of the k-th key (enc_key)
-    int* slot_cnt;              // [items * CW]
-    Cand* slot_ent;             // [items * CW * slot_stride]
+    int* slot_cnt;              // [slots]: one slot per (list segment, query of the list's bucket)
+    Cand* slot_ent;             // [slots * slot_stride]
     int slot_stride;            // entries per slot: k, or cap where that is small (no cut at the end of an item)
     int* work_counter;          // zeroed before launch
     // bucket mode
     const int* list_off;        // [nlist+1] row offsets
     const int* bucket_off;      // [nlist+1]
     const int* bucket_q;        // [pairs] query index per bucket entry
-    const int4* item_tab;       // [items] (list, segment, query tile, 0)
+    const int4* item_tab;       // [items] (list, segment, query tile, first result slot of the item)
     const int* dyn;             // device scalars: [0] = items, [1] = rows per segment
     const int* xq;              // [8][xq_stride] item numbers queued per XCD
     const int* xq_count;        // [8] queue lengths
@@ -108,7 +108,6 @@ struct ScanArgs {
     float* key_out;             // dense mode: [nq, dense_nrows] every key is written here and nothing is selected
     int* hist;                  // [nq][kHistBins] keys found so far per query, by key range (or nullptr)
     const float* hpar;          // [nq][2] lower edge of bin 0 and bin width (width 0: query has no histogram)
-    long long* dbg;             // per-workgroup phase timers (HR_SCAN_TIMING builds only, else unused)
 };
 
 struct SeedArgs {
@@ -123,7 +122,7 @@ struct SeedArgs {
 };
 
 // Device scalars written by the bucketing kernels (ints in workspace)
-enum { DYN_ITEMS = 0, DYN_SEG_ROWS = 1, DYN_ROWS_LO = 2, DYN_ROWS_HI = 3, DYN_PAIRS = 4, DYN_COUNT = 8 };
+enum { DYN_ITEMS = 0, DYN_SEG_ROWS = 1, DYN_ROWS_LO = 2, DYN_ROWS_HI = 3, DYN_PAIRS = 4, DYN_SLOTS = 5, DYN_COUNT = 8 };
 
 struct MergeArgs {
     const int* slot_cnt;
@@ -135,9 +134,9 @@ struct MergeArgs {
     const int* pair_entry;      // [nq, nprobe] position of the pair inside its list's bucket
     const int* list_off;        // [nlist+1]
     const int* bucket_off;      // [nlist+1]
-    const int* item_base;       // [nlist+1]
+    const int* slot_base;       // [nlist+1] first result slot of every list
     const int* dyn;
-    int nq, nprobe, nlist, k, cw, l2;
+    int nq, nprobe, nlist, k, l2;
     int carried;                // out_ids / out_scores hold a previous result on entry: merged in (ids < 0: empty places)
     int64_t* out_ids;           // [nq, k] or nullptr
     float* out_scores;          // [nq, k] or nullptr
@@ -167,6 +166,7 @@ hipError_t launch_rescore(const float* q, int64_t nq, int d, int dtype, const vo
                           int64_t* out_ids, float* out_scores, int32_t* out_rows, hipStream_t s);
 hipError_t launch_bf16_to_f16(const void* x, int64_t n, void* out, int* overflow, hipStream_t s);
 hipError_t launch_split_f32(const float* x, int64_t n, void* hi, void* lo, hipStream_t s);
+hipError_t launch_check_labels(const int64_t* ids, int64_t n, int* negative, hipStream_t s);
 
 struct BucketArgs {
     const int* probe;           // [nq*nprobe]
@@ -177,6 +177,7 @@ struct BucketArgs {
     int* bucket_off;            // [nlist+1]
     int* bucket_q;              // [nq*nprobe]
     int* item_base;             // [nlist+1]
+    int* slot_base;             // [nlist+1] first result slot of every list
     int4* item_tab;             // [item_cap]
     int* dyn;                   // device scalars
     int* xq;                    // [8][item_cap] per-XCD queues of item numbers
@@ -184,6 +185,8 @@ struct BucketArgs {
     int* round_cnt;             // [8][64] items per queue and round, then where each round starts (zeroed before launch)
     int* round_cur;             // [8][64] items placed so far per queue and round (zeroed before launch)
     int item_cap;
+    int slot_cap;               // result slots the workspace holds
+    int item_target;            // aimed number of work items (rows per segment follow from it)
     unsigned long long* hits;   // [nlist] probes per list since load or the last reset (index-owned), or nullptr
 };
 hipError_t launch_bucketing(const BucketArgs& a, hipStream_t s);

@@ -258,13 +258,6 @@ struct ScanShape {
 // nothing else
 __host__ __device__ constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }
 
-#ifdef HR_SCAN_TIMING
-#define HR_TIC(var) long long var = clock64()
-#define HR_TOC(acc, var) do { long long n_ = clock64(); acc += n_ - var; var = n_; } while (0)
-#else
-#define HR_TIC(var)
-#define HR_TOC(acc, var)
-#endif
 
 // Every thread always loads (chunks past the end of the segment re-read its last chunk; the
 // rows they would belong to are masked out of the selection): an unconditional load keeps the
@@ -434,11 +427,6 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
             for (int m = 0; m < NLD; m++) goff[m] = 0;
         }
     }
-#ifdef HR_SCAN_TIMING
-    long long t_pop = 0, t_setup = 0, t_mfma = 0, t_sel = 0, t_stage = 0, t_bar = 0, t_emit = 0;
-    int n_items = 0, n_blocks = 0, n_cand_blocks = 0, n_prunes = 0;
-#endif
-    HR_TIC(tk);
 
     for (;;) {
         if (threadIdx.x == 0) {
@@ -462,10 +450,9 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
         __syncthreads();
         const int item = __builtin_amdgcn_readfirstlane(*s_item);
         if (item < 0) break;
-        HR_TOC(t_pop, tk);
 
         // ---- decode the work item
-        int list, seg, qt, row0, row_end, w, boff;
+        int list, seg, qt, row0, row_end, w, boff, slot0 = 0;
         if (a.dense) {
             seg = item / a.dense_nqt;
             qt = item - seg * a.dense_nqt;
@@ -476,7 +463,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
             boff = 0;
         } else {
             int4 it = a.item_tab[item];
-            list = it.x; seg = it.y; qt = it.z;
+            list = it.x; seg = it.y; qt = it.z; slot0 = it.w;
             int l0 = a.list_off[list], l1 = a.list_off[list + 1];
             row0 = l0 + seg * seg_rows;
             row_end = min(l1, row0 + seg_rows);
@@ -485,7 +472,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
         }
         const int nrows = row_end - row0;
         const int nblk = (nrows + kBlockRows - 1) / kBlockRows;
-        Cand* const gsel = a.slot_ent + ((size_t)item * S::cw + wave * WC) * (size_t)a.slot_stride;   // (GS: slot_stride = cap)
+        Cand* const gsel = a.slot_ent + ((size_t)slot0 + wave * WC) * (size_t)a.slot_stride;   // (GS: slot_stride = cap)
         const char* src = (const char*)a.rows + (size_t)row0 * S::rowb;
         const char* src_lo = S::planes == 2 ? (const char*)a.rows_lo + (size_t)row0 * S::rowb : src;
 
@@ -598,7 +585,6 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
             // includes the blocks on their way to LDS.
             __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
         }
-        HR_TOC(t_setup, tk);
 
         // ---- the blocks of the segment.  Per block (direct staging): (1) this wave's part of
         // the block has landed, (2) barrier: so has everybody's, and nobody reads the previous
@@ -668,9 +654,6 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
                 const float best = fmaxf(fmaxf(key[0], key[1]), fmaxf(key[2], key[3]));
                 // ---- append what reaches the column's threshold
                 if (__builtin_amdgcn_ballot_w64(best >= thr[s]) != 0) {
-#ifdef HR_SCAN_TIMING
-                    n_cand_blocks++;
-#endif
                     bool pass[4];
 #pragma unroll
                     for (int r = 0; r < 4; r++) pass[r] = key[r] >= thr[s] && (rbase + r < row_end);
@@ -699,9 +682,6 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
                         int n = __builtin_amdgcn_readlane(ccnt[s], col);
                         uint32_t kth = GS ? select_k(gs + col * a.cap, n, a.k, a.cap, a.row_ids)
                                               : select_k(ssel + col * a.cap, n, a.k, a.cap, a.row_ids);
-#ifdef HR_SCAN_TIMING
-                        n_prunes++;
-#endif
                         float nt = 0.f;
                         if (lane == col) {
                             uint32_t old = atomicMax(&a.thr[q[s]], kth);
@@ -712,7 +692,6 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
                     }
                 }
             }
-            HR_TOC(t_sel, tk);
         };
 
         int bi = 0;                                              // blk % NB
@@ -739,20 +718,14 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
                 }
             }
             __builtin_amdgcn_s_barrier();
-            HR_TOC(t_bar, tk);
-#ifdef HR_SCAN_TIMING
-            n_blocks++;
-#endif
             if (a.key_out != nullptr) flush_keys();
             fill_direct(blk + D, bi == 0 ? NB - 1 : bi - 1);
-            HR_TOC(t_stage, tk);
             if (nact > 0) {
                 const char* cur = stage + bi * S::buf_bytes;
                 if (a.l2) nrms[0] = *(const floatx4*)(nstage + bi * kBlockRows + g * 4);
                 const char* const ap[4] = {cur + abase[0], cur + abase[1], cur + abase[2], cur + abase[3]};
                 if (NCS == 2 && nact == 2) mfma_block<DT, KSTEPS, NCS, NCS, S>(ap, bfrag, accs[0]);
                 else                       mfma_block<DT, KSTEPS, NCS, 1, S>(ap, bfrag, accs[0]);
-                HR_TOC(t_mfma, tk);
                 select_block(accs[0], nrms[0], row0 + blk * kBlockRows + g * 4);
             }
             bi = bi + 1 == NB ? 0 : bi + 1;
@@ -765,7 +738,6 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
             else if (a.l2) wait_vmcnt<2 * S::lpf>();
             else wait_vmcnt<2 * (S::lpf - 1)>();
             __builtin_amdgcn_s_barrier();
-            HR_TOC(t_bar, tk);
             // (the requests of all waves at once keep the address unit busy for a while, and a
             // wave cannot go on before its own are accepted: half of the waves send theirs
             // now, the other half after their first block, when the first half multiplies)
@@ -774,21 +746,16 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
                 const int fb = bi + D >= NB ? bi + D - NB : bi + D;     // the buffers the pair before this one used
                 fill_direct(blk + D, fb);
                 fill_direct(blk + D + 1, fb + 1);
-                HR_TOC(t_stage, tk);
             };
             if (early) requests();
 #pragma unroll
             for (int h = 0; h < 2; h++) {
                 if (nact > 0 && blk + h < nblk) {
-#ifdef HR_SCAN_TIMING
-                    n_blocks++;
-#endif
                     const char* cur = stage + (bi + h) * S::buf_bytes;
                     if (a.l2) nrms[0] = *(const floatx4*)(nstage + (bi + h) * kBlockRows + g * 4);
                     const char* const ap[4] = {cur + abase[0], cur + abase[1], cur + abase[2], cur + abase[3]};
                     if (NCS == 2 && nact == 2) mfma_block<DT, KSTEPS, NCS, NCS, S>(ap, bfrag, accs[0]);
                     else                       mfma_block<DT, KSTEPS, NCS, 1, S>(ap, bfrag, accs[0]);
-                    HR_TOC(t_mfma, tk);
                     select_block(accs[0], nrms[0], row0 + (blk + h) * kBlockRows + g * 4);
                 }
                 if (h == 0 && !early) requests();
@@ -802,23 +769,17 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
             constexpr int p = decltype(pc)::value;               // ring position
             const bool live = blk < nblk;
             __syncthreads();
-            HR_TOC(t_bar, tk);
             constexpr int pn = (p + 1) % PF;
             stage_block<DT, S>(stage + (bi ^ 1) * S::buf_bytes, ring[pn]);
             nstage[(bi ^ 1) * kBlockRows + (threadIdx.x & (kBlockRows - 1))] = nring[pn];
             load_block<S>(block_src(blk + 1 + PF), block_chunks(blk + 1 + PF), ring[pn]);
             nring[pn] = load_norm(blk + 1 + PF);
-            HR_TOC(t_stage, tk);
-#ifdef HR_SCAN_TIMING
-            n_blocks++;
-#endif
             if (live && nact > 0) {
                 const char* cur = stage + bi * S::buf_bytes;
                 nrms[0] = *(const floatx4*)(nstage + bi * kBlockRows + g * 4);
                 const char* const ap[4] = {cur + abase[0], cur + abase[1], cur + abase[2], cur + abase[3]};
                 if (NCS == 2 && nact == 2) mfma_block<DT, KSTEPS, NCS, NCS, S>(ap, bfrag, accs[0]);
                 else                       mfma_block<DT, KSTEPS, NCS, 1, S>(ap, bfrag, accs[0]);
-                HR_TOC(t_mfma, tk);
                 select_block(accs[0], nrms[0], row0 + blk * kBlockRows + g * 4);
             }
             bi ^= 1;
@@ -875,7 +836,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
             }
             const int n = c > a.slot_stride ? a.k : c;
             if (lane < WC && ok) {
-                const size_t slot = (size_t)item * S::cw + wave * WC + lane;
+                const size_t slot = (size_t)slot0 + wave * WC + lane;
                 a.slot_cnt[slot] = n;
                 if (!GS) {
                     const Cand* cb = mysel + lane * a.cap;
@@ -970,19 +931,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
             }
         }
         __syncthreads();
-        HR_TOC(t_emit, tk);
-#ifdef HR_SCAN_TIMING
-        n_items++;
-#endif
     }
-#ifdef HR_SCAN_TIMING
-    if (a.dbg && threadIdx.x == 0) {
-        long long* o = a.dbg + blockIdx.x * 8;
-        o[0] = t_pop; o[1] = t_setup; o[2] = t_mfma; o[3] = t_sel; o[4] = t_stage; o[5] = t_bar; o[6] = t_emit; o[7] = n_items;
-        long long* o2 = a.dbg + 4096 + blockIdx.x * 4;
-        o2[0] = n_blocks; o2[1] = n_cand_blocks; o2[2] = n_prunes;
-    }
-#endif
 }
 
 template <int DT, int NCS, int NW, bool GS>

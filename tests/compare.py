@@ -42,6 +42,7 @@ def check_probes(got_probe, got_scores, ref_probe, ref_scores, score_of, metric,
     nq, nprobe = ref_probe.shape
     exact_rows = 0
     exact_sets = 0
+    under = 0               # comparisons in which the absolute floor, not the score itself, set the tolerance
     for q in range(nq):
         g, r = got_probe[q], ref_probe[q]
         assert len(set(g.tolist())) == nprobe, f"query {q}: duplicate probe"
@@ -67,12 +68,14 @@ def check_probes(got_probe, got_scores, ref_probe, ref_scores, score_of, metric,
             s_g = score_of(q, g)
             d = _worse_by(s_g[:-1], s_g[1:], metric)          # >0 where an earlier one is worse
             assert np.all(d <= 2 * tol), f"query {q}: probes out of order"
+        sc = scale[q] if np.ndim(scale) else scale
+        under += int((np.abs(ref_scores[q]) < sc).sum())
         if got_scores is not None:
             s_g = score_of(q, g)
-            sc = scale[q] if np.ndim(scale) else scale
             assert np.all(np.abs(got_scores[q] - s_g) <= _tol(s_g, sc, tau)), \
                 f"query {q}: coarse scores off by {np.abs(got_scores[q] - s_g).max()}"
-    return {"exact_order_rate": exact_rows / max(nq, 1), "exact_set_rate": exact_sets / max(nq, 1)}
+    return {"exact_order_rate": exact_rows / max(nq, 1), "exact_set_rate": exact_sets / max(nq, 1),
+            "n_under_floor": under}
 
 
 def check_topk(got_ids, got_scores, ref_ids, ref_scores, score_of, metric, tau, scale):
@@ -82,6 +85,8 @@ def check_topk(got_ids, got_scores, ref_ids, ref_scores, score_of, metric, tau, 
     nq, k = ref_ids.shape
     exact = 0
     max_rel = 0.0
+    under = 0               # comparisons in which the absolute floor, not the score itself, set the tolerance
+    same = total = 0        # ids shared with the oracle / ids the oracle reports
     for q in range(nq):
         g_i, g_s = got_ids[q], got_scores[q].astype(np.float64)
         r_i, r_s = ref_ids[q], ref_scores[q]
@@ -96,6 +101,9 @@ def check_topk(got_ids, got_scores, ref_ids, ref_scores, score_of, metric, tau, 
         g_i, g_s, r_i, r_s = g_i[:nvalid], g_s[:nvalid], r_i[:nvalid], r_s[:nvalid]
         assert len(set(g_i.tolist())) == nvalid, f"query {q}: duplicate ids"
         tol = _tol(r_s, sc, tau)
+        under += int((np.abs(r_s) < sc).sum())
+        total += nvalid
+        same += int(np.isin(g_i, r_i).sum())
         err = np.abs(g_s - r_s)
         assert np.all(err <= tol), f"query {q}: rank-wise score error {err.max()} > tol"
         max_rel = max(max_rel, float((err / np.maximum(np.abs(r_s), sc)).max()))
@@ -117,4 +125,5 @@ def check_topk(got_ids, got_scores, ref_ids, ref_scores, score_of, metric, tau, 
             assert np.all(_worse_by(r_s[-1], s_miss, metric) <= kth_tol) or \
                 np.all(_worse_by(g_s[-1], s_miss, metric) <= kth_tol), \
                 f"query {q}: oracle id {missing} clearly inside the top-k is missing"
-    return {"exact_id_rows": exact / max(nq, 1), "max_rel_err": max_rel}
+    return {"exact_id_rows": exact / max(nq, 1), "id_set_overlap": same / max(total, 1), "max_rel_err": max_rel,
+            "n_under_floor": under}

@@ -34,7 +34,7 @@ def test_header_constants_match_binding(hr):
     text = open(os.path.join(ROOT, "include", "hr_ivf.h")).read()
     assert int(re.search(r"#define HR_K_MAX (\d+)", text).group(1)) == hr.HR_K_MAX
     assert int(re.search(r"#define HR_NPROBE_MAX (\d+)", text).group(1)) == hr.HR_NPROBE_MAX
-    assert int(re.search(r"#define HR_LOAD_NO_ROW_TABLES (0x[0-9a-f]+)", text).group(1), 16) == hr.HR_LOAD_NO_ROW_TABLES
+    assert int(re.search(r"#define HR_LOAD_ROW_TABLES (0x[0-9a-f]+)", text).group(1), 16) == hr.HR_LOAD_ROW_TABLES
 
 
 def test_load_argument_validation_on_host(hr):
@@ -55,7 +55,7 @@ def test_load_argument_validation_on_host(hr):
     assert load(N=-1) == -1
     assert load(N=1 << 31) == -1
     assert load(dtype=3) == -1
-    assert load(dtype=3 | hr.HR_LOAD_NO_ROW_TABLES) == -1
+    assert load(dtype=3 | hr.HR_LOAD_ROW_TABLES) == -1
     assert load(d=0) == -1
     assert load(d=100) == -5 and "d=100" in hr.hr_last_error()
     assert load(offs=bad) == -1 and "decreases" in hr.hr_last_error()
@@ -92,3 +92,38 @@ def test_reorder_argument_validation_on_host(hr):
     assert f(fake, 4, 8, None, 0, None, 0, fake, None) == -1 and "must not be probe" in hr.hr_last_error()
     assert f(fake, 0, 8, None, 0, None, 0, other, None) == 0      # empty batch: nothing to do
 
+
+
+def test_binding_rejects_tensors_the_kernels_would_read_out_of_bounds(hr):
+    """The binding hands raw addresses to the kernels; a tensor on the host, of another type or of another shape
+    must be refused before that (no GPU needed: the checks run first)."""
+    import torch
+    from paper_2507_09138_amd import binding as b
+    cpu = torch.device("cpu")
+    ok = torch.zeros(5, 64)
+    assert b._want(ok, "queries", torch.float32, (None, 64), cpu).shape == (5, 64)
+    for bad in (torch.zeros(5, 64, dtype=torch.float16), torch.zeros(5, 64, dtype=torch.float64), torch.zeros(5, 32),
+                torch.zeros(64), ok.numpy()):
+        with pytest.raises(hr.HrError) as e:
+            b._want(bad, "queries", torch.float32, (None, 64), cpu)
+        assert e.value.code == -1
+    with pytest.raises(hr.HrError):                                  # wrong device
+        b._want(ok, "queries", torch.float32, (None, 64), torch.device("cuda:0"))
+    with pytest.raises(hr.HrError):                                  # float list numbers
+        b._want_int(torch.zeros(5, 3), "probe_ids", (5, None), cpu)
+    with pytest.raises(hr.HrError):                                  # rows of another batch size
+        b._want_int(torch.zeros(4, 3, dtype=torch.int64), "probe_ids", (5, None), cpu)
+    assert b._want_int(torch.zeros(5, 3, dtype=torch.int64), "probe_ids", (5, None), cpu).dtype == torch.int32
+    # an index object without a library handle: every method must refuse host tensors before calling the library
+    ix = b.IvfIndex.__new__(b.IvfIndex)
+    ix.handle, ix.d, ix.nlist, ix.device, ix._ws = None, 64, 10, torch.device("cuda:0"), None
+    probe = torch.zeros(5, 3, dtype=torch.int32)
+    state = (torch.zeros(5, 4, dtype=torch.int64), torch.zeros(5, 4), torch.zeros(5, 4, dtype=torch.int32))
+    for call in (lambda: ix.search(ok, 3, 4), lambda: ix.coarse(ok, 3), lambda: ix.scan(ok, probe, 4),
+                 lambda: ix.scan_step(ok, probe, state[:2]), lambda: ix.scan_step_rows(ok, probe, state),
+                 lambda: ix.rescore(ok, probe, 4), lambda: ix.lists_of_rows(probe), lambda: b.reorder_probes(probe),
+                 lambda: b.IvfIndex(ok, torch.zeros(6, dtype=torch.int64), ok, torch.zeros(5, dtype=torch.int64))):
+        with pytest.raises(hr.HrError) as e:
+            call()
+        assert e.value.code == -1
+    ix.handle = None                                                  # (nothing to free)

@@ -22,7 +22,9 @@ def test_topk_exact_and_near_tie_swap():
     gi = np.array([[10, 11, 12]], np.int64)             # near-tie swapped: fine
     gs = np.array([[0.9, 0.80001, 0.8]], np.float32)
     st = check_topk(gi, gs, ri, rs, _score_of, "ip", 1e-4, 0.02)
-    assert st["exact_id_rows"] == 0.0
+    assert st["exact_id_rows"] == 0.0 and st["id_set_overlap"] == 1.0 and st["n_under_floor"] == 0
+    st = check_topk(ri.copy(), rs.astype(np.float32), ri, rs, _score_of, "ip", 1e-4, 0.85)
+    assert st["n_under_floor"] == 2                      # 0.80001 and 0.8 are judged against 0.85, not against themselves
 
 
 def test_topk_rejects_wrong_id_score_order_dups_padding():
@@ -51,9 +53,12 @@ def test_probes():
     rp = np.array([[10, 12, 11]], np.int32)
     rs = np.array([[0.9, 0.80001, 0.8]])
     st = check_probes(rp.copy(), None, rp, rs, _score_of, "ip", 1e-4, 0.02)
-    assert st == {"exact_order_rate": 1.0, "exact_set_rate": 1.0}
+    assert st == {"exact_order_rate": 1.0, "exact_set_rate": 1.0, "n_under_floor": 0}
     st = check_probes(np.array([[10, 11, 12]], np.int32), None, rp, rs, _score_of, "ip", 1e-4, 0.02)
-    assert st == {"exact_order_rate": 0.0, "exact_set_rate": 1.0}
+    assert st == {"exact_order_rate": 0.0, "exact_set_rate": 1.0, "n_under_floor": 0}
+    # a boundary score smaller than the floor is counted: the tolerance there is absolute
+    st = check_probes(rp.copy(), None, rp, rs, _score_of, "ip", 1e-4, 0.85)
+    assert st["n_under_floor"] == 2
     with pytest.raises(AssertionError):                 # 13 is no near-tie of the boundary
         check_probes(np.array([[10, 12, 13]], np.int32), None, rp, rs, _score_of, "ip", 1e-4, 0.02)
     with pytest.raises(AssertionError):                 # out of order beyond tolerance

@@ -58,12 +58,17 @@ def _scale(q, xn, metric):
     return floor_for(q.shape[1]) * (qn * xn if metric == "ip" else qn ** 2 + xn ** 2)
 
 
-def compare_all(index, queries, nprobe, k, metric, sample=None, label="", row_tables=True):
-    """coarse vs oracle; scan (with the GPU's probe lists) vs oracle; search == coarse + scan."""
+def compare_all(index, queries, nprobe, k, metric, sample=None, label="", row_tables=False, host=None,
+                floor_free=False, also_with_row_tables=False):
+    """coarse vs oracle; scan (with the GPU's probe lists) vs oracle; search == coarse + scan.
+    floor_free: no comparison may have been judged under the absolute floor of the comparator (the workload shapes:
+    their scores are far above it, so the tolerance there is purely relative).  also_with_row_tables: the same
+    queries through an index loaded with the derived row tables (HR_LOAD_ROW_TABLES), against the same oracle results
+    (the coarse step does not depend on the tables, so the probe lists must be the same bits)."""
     hr = _hr()
     cfg = index.cfg
     tau = TAU[cfg.dtype]
-    host = Host(index)
+    host = host or Host(index)
     ix = hr.IvfIndex(index.centroids, index.list_offsets, index.list_vectors, index.list_ids, row_tables=row_tables)
     q_dev = queries
     t0 = time.time()
@@ -73,6 +78,7 @@ def compare_all(index, queries, nprobe, k, metric, sample=None, label="", row_ta
     torch.cuda.synchronize()
     t_gpu = time.time() - t0
     st = ix.stats(q_dev.shape[0], nprobe, k)
+    ix.close()
     probe_g, pscore_g = probe_g.cpu().numpy(), pscore_g.cpu().numpy()
     ids_s, sc_s = ids_s.cpu().numpy(), sc_s.cpu().numpy()
     ids_f, sc_f = ids_f.cpu().numpy(), sc_f.cpu().numpy()
@@ -90,17 +96,37 @@ def compare_all(index, queries, nprobe, k, metric, sample=None, label="", row_ta
                         metric, TAU["f32"], _scale(qs, cn, metric))
     ids_o, sc_o = oracle.scan(qs, host.off, host.vec, cfg.dtype, host.ids,
                               np.ascontiguousarray(probe_g[sel]), k, m)
-    st_k = check_topk(ids_s[sel], sc_s[sel], ids_o, sc_o,
-                      lambda i, ids: oracle.pair_scores(qs, host.vec, cfg.dtype, m, np.full(len(ids), i),
-                                                        host.rows_of(ids)),
-                      metric, tau, _scale(qs, host.xnorm(), metric))
-    # end to end against the unstaged oracle: how often is everything identical
-    _, ids_e, _ = oracle.ivf_search(qs, host.cent, host.off, host.vec, cfg.dtype, host.ids, nprobe, k, m)
+    score_of = lambda i, ids: oracle.pair_scores(qs, host.vec, cfg.dtype, m, np.full(len(ids), i), host.rows_of(ids))
+    scale = _scale(qs, host.xnorm(), metric)
+    st_k = check_topk(ids_s[sel], sc_s[sel], ids_o, sc_o, score_of, metric, tau, scale)
+    # end to end against the unstaged oracle: how often is everything identical.  (Where the GPU's probe set is the
+    # oracle's, the oracle's whole search is its scan of the GPU's probe lists: same candidates, same order; only
+    # the other queries are searched again.)
+    ids_e = ids_o.copy()
+    other = np.nonzero((np.sort(probe_g[sel], 1) != np.sort(probe_o, 1)).any(1))[0]
+    if len(other):
+        _, ids_x, _ = oracle.ivf_search(np.ascontiguousarray(qs[other]), host.cent, host.off, host.vec, cfg.dtype, host.ids,
+                                        nprobe, k, m)
+        ids_e[other] = ids_x
     e2e = float((ids_e == ids_f[sel]).all(1).mean())
     t_or = time.time() - t0
     print(f"[parity {label or cfg.name}] nq={len(sel)} probes: {st_p} topk: {st_k} end-to-end exact rows: {e2e:.4f} "
           f"stats: {st} gpu {t_gpu:.2f}s oracle {t_or:.1f}s", flush=True)
-    ix.close()
+    if floor_free:
+        assert st_k["n_under_floor"] == 0, "a top-k comparison was judged under the absolute floor"
+        assert st_p["n_under_floor"] == 0 or floor_free == "topk", "a probe comparison was judged under the absolute floor"
+    if also_with_row_tables:
+        ix = hr.IvfIndex(index.centroids, index.list_offsets, index.list_vectors, index.list_ids, row_tables=True)
+        probe_n, _ = ix.coarse(q_dev, nprobe, metric)
+        ids_n, sc_n = ix.scan(q_dev, probe_n, k, metric)
+        torch.cuda.synchronize()
+        ix.close()
+        assert np.array_equal(probe_n.cpu().numpy(), probe_g), "probe lists depend on the row tables"
+        st_n = check_topk(ids_n.cpu().numpy()[sel], sc_n.cpu().numpy()[sel], ids_o, sc_o, score_of, metric, tau, scale)
+        print(f"[parity {label or cfg.name}, with row tables] topk: {st_n}", flush=True)
+        if floor_free:
+            assert st_n["n_under_floor"] == 0
+        return st_p, st_k, e2e, st_n
     return st_p, st_k, e2e
 
 
@@ -368,12 +394,16 @@ def test_errors_and_determinism():
 
 
 # ---------------------------------------------------------------- the five workload shapes
-def _run_config(name, sample=None, **scale):
+# Floors asserted below on the share of rows with identical ids / of identical id sets are the rates of earlier runs
+# less a margin: a drop in id agreement that stays inside the score tolerance would otherwise pass unnoticed.
+def _run_config(name, sample=None, **kw):
+    scale = {a: b for a, b in kw.items() if a not in ("also_with_row_tables", "floor_free")}
     cfg = synth.CONFIGS[name]
     if scale:
         cfg = synth.scaled(cfg, **scale)
     print(f"case config {name} {scale or 'full size'}", flush=True)
     idx = synth.make_index(cfg, "cuda")
+    host = Host(idx)
     rounds = synth.make_queries(cfg, idx)
     out = []
     for r, q in enumerate(rounds):
@@ -381,28 +411,30 @@ def _run_config(name, sample=None, **scale):
         if sample is not None:
             gs = np.random.default_rng(99 + r)
             sel = np.sort(gs.choice(q.shape[0], size=min(sample, q.shape[0]), replace=False))
-        out.append(compare_all(idx, q, cfg.nprobe, cfg.k, cfg.metric, sample=sel,
+        out.append(compare_all(idx, q, cfg.nprobe, cfg.k, cfg.metric, sample=sel, host=host, floor_free=kw.get("floor_free", True),
+                               also_with_row_tables=kw.get("also_with_row_tables", False),
                                label=f"{name} round {r}" if len(rounds) > 1 else name))
     return out
 
 
 def test_config1_tiny_fp32_full():
-    (st_p, st_k, e2e), = _run_config("C1")
-    assert st_p["exact_set_rate"] >= 0.98 and st_k["exact_id_rows"] >= 0.98
+    (st_p, st_k, e2e, st_t), = _run_config("C1", also_with_row_tables=True)
+    assert st_p["exact_set_rate"] >= 0.98 and st_k["exact_id_rows"] >= 0.98 and st_t["exact_id_rows"] >= 0.98
 
 
 def test_config2_medium_fp32_full_size_sampled():
-    (st_p, st_k, e2e), = _run_config("C2", sample=192)
-    assert st_p["exact_set_rate"] >= 0.98 and st_k["exact_id_rows"] >= 0.98
+    (st_p, st_k, e2e, st_t), = _run_config("C2", sample=256, also_with_row_tables=True)
+    assert st_p["exact_set_rate"] >= 0.98 and st_k["exact_id_rows"] >= 0.98 and st_t["exact_id_rows"] >= 0.98
 
 
 def test_config3_skewed_fp16_scaled():
-    _run_config("C3", N=262144, nlist=256, nq=1024, nprobe=32)
+    (st_p, st_k, e2e), = _run_config("C3", N=262144, nlist=256, nq=1024, nprobe=32)
+    assert st_p["exact_set_rate"] >= 0.95 and st_k["id_set_overlap"] >= 0.99
 
 
 def test_config3_skewed_fp16_full_size_sampled():
-    (st_p, st_k, e2e), = _run_config("C3", sample=96)
-    assert st_p["exact_set_rate"] >= 0.95
+    (st_p, st_k, e2e), = _run_config("C3", sample=512)
+    assert st_p["exact_set_rate"] >= 0.95 and st_k["exact_id_rows"] >= 0.5 and st_k["id_set_overlap"] >= 0.99
 
 
 def test_config4_iterative_fp16_scaled_rounds():
@@ -410,25 +442,44 @@ def test_config4_iterative_fp16_scaled_rounds():
     assert len(out) == 8
 
 
+def test_config4_iterative_fp16_full_size_sampled():
+    """The multi-hop workload at its stated size: the index of the skewed workload (same bytes), eight rounds of 512
+    drifting queries, nprobe 32, every round one batch; 64 sampled queries of every round against the oracle."""
+    out = _run_config("C4", sample=64)
+    assert len(out) == 8
+    for st_p, st_k, e2e in out:
+        assert st_p["exact_set_rate"] >= 0.95 and st_k["exact_id_rows"] >= 0.5 and st_k["id_set_overlap"] >= 0.99
+
+
 def test_config5_large_bf16_l2_scaled():
-    _run_config("C5", N=524288, nlist=512, nq=512, nprobe=64)
+    (st_p, st_k, e2e, st_n), = _run_config("C5", N=524288, nlist=512, nq=512, nprobe=64, also_with_row_tables=True)
+    assert st_k["id_set_overlap"] >= 0.9995 and st_k["exact_id_rows"] >= 0.7 and st_n["id_set_overlap"] >= 0.998
 
 
 @pytest.mark.skipif(os.environ.get("HR_SKIP_C5_FULL") == "1", reason="HR_SKIP_C5_FULL=1")
 def test_config5_large_bf16_l2_full_size_sampled():
-    _run_config("C5", sample=48)
+    """Consecutive neighbour distances of this workload differ by 2.8e-4 of their value in the median.  As loaded by
+    default (bfloat16 rows times the query in bfloat16 hi + lo parts, error ~5e-6) the 100 ids are the oracle's in the
+    oracle's order in most rows and the id sets agree to 99.99 %.  With the binary16 row table the query is rounded to
+    binary16 once (error ~1.7e-4, inside the 2e-3 tolerance but the size of those gaps): neighbours swap places in
+    nearly every row, and what must hold is that the set of ids is the oracle's (99.9 %; floor 99.8 %)."""
+    (st_p, st_k, e2e, st_n), = _run_config("C5", sample=192, also_with_row_tables=True)
+    assert st_p["exact_set_rate"] >= 0.95
+    assert st_k["id_set_overlap"] >= 0.9995 and st_k["exact_id_rows"] >= 0.7 and st_n["id_set_overlap"] >= 0.998
 
 
 def test_paper_shape_scaled():
     """d = 1024, nprobe 128, top-1, a small batch (the paper's own parameters, Section 6.1) on a small index"""
-    (st_p, st_k, e2e), = _run_config("P1", N=1 << 20, nlist=512, nq=96)
+    # (128 of 512 lists: the last centroids chosen are nearly orthogonal to the query, their scores are a cancellation
+    # and are judged under the comparator's absolute floor; at full size, 128 of 4096, they are not)
+    (st_p, st_k, e2e), = _run_config("P1", N=1 << 20, nlist=512, nq=96, floor_free="topk")
     assert st_k["exact_id_rows"] >= 0.98
 
 
 @pytest.mark.skipif(os.environ.get("HR_SKIP_P1_FULL") == "1", reason="HR_SKIP_P1_FULL=1 (77 GB index, 80 GB of host memory)")
 def test_paper_shape_full_size_sampled():
-    _run_config("P1", sample=16)
-
+    (st_p, st_k, e2e), = _run_config("P1", sample=64)
+    assert st_k["exact_id_rows"] >= 0.95
 
 
 # ---------------------------------------------------------------- reuse of the previous retrieval (Section 4.3)
@@ -605,14 +656,14 @@ def test_search_captured_in_a_hip_graph_replays_identically():
 
 @pytest.mark.parametrize("metric", ["ip", "l2"])
 def test_float32_lists_with_and_without_row_tables(metric):
-    """float32 lists are scanned from binary16 hi/lo tables made at load, or, without them, split
-    on the fly: the same products in the same order, so the results must be the same bits; the
-    on-the-fly path is checked against the oracle as well."""
+    """float32 lists are split on the fly into binary16 hi and lo parts, or, when the caller asked for
+    row tables at load, scanned from tables of those parts: the same products in the same order, so
+    the results must be the same bits; the on-the-fly path is checked against the oracle as well."""
     print(f"case f32 row tables {metric}", flush=True)
     hr = _hr()
     idx = _random_index(40000, 256, 48, "f32", seed=71, dup=2)
     host = Host(idx)
-    a = hr.IvfIndex(idx.centroids, idx.list_offsets, idx.list_vectors, idx.list_ids)
+    a = hr.IvfIndex(idx.centroids, idx.list_offsets, idx.list_vectors, idx.list_ids, row_tables=True)
     b = hr.IvfIndex(idx.centroids, idx.list_offsets, idx.list_vectors, idx.list_ids, row_tables=False)
     q = torch.randn(300, 256, generator=torch.Generator().manual_seed(2)).cuda()
     m = METRIC[metric]
@@ -649,32 +700,89 @@ def test_hot_lists_by_access_counters():
     ix.close()
 
 
-@pytest.mark.parametrize("dtype,metric", [("f32", "l2"), ("f16", "l2"), ("bf16", "ip")])
-def test_refresh_rows_after_vectors_replaced_in_place(dtype, metric):
+@pytest.mark.parametrize("dtype,metric,tables", [("f32", "l2", True), ("f32", "ip", False), ("f16", "l2", False),
+                                                 ("bf16", "ip", True), ("bf16", "l2", False)])
+def test_refresh_rows_after_vectors_replaced_in_place(dtype, metric, tables):
     """A cluster's vectors replaced in place (what an asynchronous load of another cluster into its
-    slot does): after hr_ivf_refresh_rows the index answers like one loaded from the new data, bit
-    for bit (squared norms, and for float32 the row tables, are derived again)."""
+    slot does): after hr_ivf_refresh_rows the index answers for the new bytes: against the oracle on
+    a host copy of the new data, and bit for bit like an index loaded from it (squared norms and
+    the row tables are derived again)."""
     hr = _hr()
     idx = _random_index(16000, 128, 30, dtype, seed=9)
-    ix = hr.IvfIndex(idx.centroids, idx.list_offsets, idx.list_vectors, idx.list_ids)
+    ix = hr.IvfIndex(idx.centroids, idx.list_offsets, idx.list_vectors, idx.list_ids, row_tables=tables)
     q = torch.randn(64, 128, generator=torch.Generator().manual_seed(1)).cuda()
     before = ix.search(q, 30, 10, metric)
     off = idx.list_offsets
     lst = int(torch.argmax(off[1:] - off[:-1]))
     r0, r1 = int(off[lst]), int(off[lst + 1])
-    new = (torch.randn(r1 - r0, 128, generator=torch.Generator().manual_seed(2)) * 3.0).to(idx.list_vectors.dtype)
+    # (longer vectors win inner products, shorter ones are nearer: either way the new rows enter the results)
+    new = (torch.randn(r1 - r0, 128, generator=torch.Generator().manual_seed(2)) * (3.0 if metric == "ip" else 0.3)).to(idx.list_vectors.dtype)
     idx.list_vectors[r0:r1] = new.cuda()
     ix.refresh_rows(r0, r1)
     ix.refresh_rows(r0, r0)                                   # empty range: nothing to do
-    got = ix.search(q, 30, 10, metric)
-    fresh = hr.IvfIndex(idx.centroids, idx.list_offsets, idx.list_vectors, idx.list_ids)
+    probe, _ = ix.coarse(q, 30, metric)
+    got = ix.scan(q, probe, 10, metric)
+    host = Host(idx)                                          # (copied after the replacement: the new bytes)
+    qn = synth.to_numpy(q)
+    m = METRIC[metric]
+    ids_o, sc_o = oracle.scan(qn, host.off, host.vec, dtype, host.ids, probe.cpu().numpy(), 10, m)
+    st = check_topk(got[0].cpu().numpy(), got[1].cpu().numpy(), ids_o, sc_o,
+                    lambda i, ids: oracle.pair_scores(qn, host.vec, dtype, m, np.full(len(ids), i), host.rows_of(ids)),
+                    metric, TAU[dtype], _scale(qn, host.xnorm(), metric))
+    print(f"[parity refresh {dtype} {metric} tables={tables}] {st}", flush=True)
+    in_new = np.isin(ids_o, host.ids[r0:r1]).mean()
+    assert in_new > 0.2                                       # (the replaced rows do matter)
+    fresh = hr.IvfIndex(idx.centroids, idx.list_offsets, idx.list_vectors, idx.list_ids, row_tables=tables)
     want = fresh.search(q, 30, 10, metric)
+    got = ix.search(q, 30, 10, metric)
     assert torch.equal(got[0], want[0]) and torch.equal(got[1], want[1])
-    assert not torch.equal(before[0], want[0])                # (the replaced rows do matter)
+    assert not torch.equal(before[0], want[0])
     with pytest.raises(hr.HrError):
         ix.refresh_rows(5, idx.list_vectors.shape[0] + 1)
+    if dtype == "bf16" and tables:
+        # a new value beyond binary16 cannot go into the table: the call says so
+        idx.list_vectors[r0 + 3, 5] = 1.0e6
+        with pytest.raises(hr.HrError) as e:
+            ix.refresh_rows(r0, r1)
+        assert e.value.code == -5
+        idx.list_vectors[r0 + 3, 5] = 1.0
+        ix.refresh_rows(r0, r1)                                # replaced again: fine
     ix.close()
     fresh.close()
+
+
+def test_negative_labels_are_refused_at_load():
+    """A negative id marks an empty place in results, so a label may not be negative."""
+    hr = _hr()
+    idx = _random_index(3000, 64, 7, "f16", seed=3)
+    idx.list_ids[1234] = -5
+    with pytest.raises(hr.HrError) as e:
+        hr.IvfIndex(idx.centroids, idx.list_offsets, idx.list_vectors, idx.list_ids)
+    assert e.value.code == -1 and "negative label" in str(e.value)
+
+
+def test_scan_takes_more_places_than_there_are_lists():
+    """hr_ivf_scan takes probe rows of up to HR_NPROBE_MAX places whatever the number of lists (the
+    other places empty), and hr_ivf_workspace_bytes sizes a workspace for that shape."""
+    hr = _hr()
+    idx = _random_index(4000, 64, 6, "f16", seed=13)
+    host = Host(idx)
+    ix = hr.IvfIndex(idx.centroids, idx.list_offsets, idx.list_vectors, idx.list_ids)
+    assert hr.hr_ivf_workspace_bytes(ix.handle, 20, 40, 5) > 0
+    assert hr.hr_ivf_workspace_bytes(ix.handle, 20, hr.HR_NPROBE_MAX + 1, 5) == 0
+    q = torch.randn(20, 64, generator=torch.Generator().manual_seed(2)).cuda()
+    probe = torch.full((20, 40), -1, dtype=torch.int32)
+    probe[:, 7] = 2
+    probe[:, 33] = 5
+    ids, sc = ix.scan(q, probe.cuda(), 5, "ip")
+    qn = synth.to_numpy(q)
+    ids_o, sc_o = oracle.scan(qn, host.off, host.vec, "f16", host.ids, probe.numpy(), 5, oracle.IP)
+    check_topk(ids.cpu().numpy(), sc.cpu().numpy(), ids_o, sc_o,
+               lambda i, v: oracle.pair_scores(qn, host.vec, "f16", oracle.IP, np.full(len(v), i), host.rows_of(v)),
+               "ip", TAU["f16"], _scale(qn, host.xnorm(), "ip"))
+    with pytest.raises(hr.HrError):
+        ix.search(q, 7, 5, "ip")                               # the whole search still wants nprobe <= nlist
+    ix.close()
 
 
 
@@ -682,7 +790,7 @@ def test_seeded_sweep_of_small_configurations():
     """Forty seeded draws of (N, d, lists, storage, metric, batch, nprobe, k) from the corners of
     the supported ranges (one row, one list, one query, k at the buffer-size boundaries 24/25,
     64/65 and at its maximum, nprobe up to 300), each through coarse, scan and search against
-    the oracle."""
+    the oracle; every other draw with row tables."""
     rng = np.random.default_rng(1)
     for c in range(40):
         d = int(rng.choice([64, 128, 256, 512, 768, 1024]))
@@ -696,24 +804,25 @@ def test_seeded_sweep_of_small_configurations():
         print(f"case sweep {c}: n={n} d={d} nlist={nlist} {dtype} {metric} nq={nq} nprobe={nprobe} k={k}", flush=True)
         idx = _random_index(n, d, nlist, dtype, seed=1000 + c)
         q = torch.randn(nq, d, generator=torch.Generator().manual_seed(c)).cuda()
-        compare_all(idx, q, nprobe=nprobe, k=k, metric=metric)
+        compare_all(idx, q, nprobe=nprobe, k=k, metric=metric, row_tables=bool(c & 1))
 
 
 @pytest.mark.parametrize("metric", ["ip", "l2"])
-def test_bfloat16_lists_without_the_binary16_table(metric):
-    """bfloat16 lists are scanned from a binary16 copy made at load (query rounded to binary16, one
-    MFMA column per query); without it, as bfloat16 with the query in bfloat16 hi and lo parts.
-    The second way is checked here (the first is what every other bfloat16 test runs), on random
-    data with k on both sides of the buffer-size boundary and on the scaled large workload."""
-    print(f"case bf16 without table {metric}", flush=True)
+def test_bfloat16_lists_with_the_binary16_table(metric):
+    """bfloat16 lists are scanned as bfloat16 with the query in bfloat16 hi and lo parts, or, when the
+    caller asked for row tables at load, from a binary16 copy (query rounded to binary16, one MFMA
+    column per query).  The second way is checked here (the first is what every other bfloat16 test
+    runs), on random data with k on both sides of the buffer-size boundary and on the scaled large
+    workload."""
+    print(f"case bf16 with table {metric}", flush=True)
     idx = _random_index(30000, 256, 40, "bf16", seed=83, dup=2)
     q = torch.randn(200, 256, generator=torch.Generator().manual_seed(5)).cuda()
-    compare_all(idx, q, nprobe=9, k=10, metric=metric, row_tables=False)
-    compare_all(idx, q, nprobe=9, k=100, metric=metric, row_tables=False)
+    compare_all(idx, q, nprobe=9, k=10, metric=metric, row_tables=True)
+    compare_all(idx, q, nprobe=9, k=100, metric=metric, row_tables=True)
     if metric == "l2":
         cfg = synth.scaled(synth.CONFIGS["C5"], N=262144, nlist=256, nq=256, nprobe=32)
         ci = synth.make_index(cfg, "cuda")
-        compare_all(ci, synth.make_queries(cfg, ci)[0], cfg.nprobe, cfg.k, cfg.metric, row_tables=False, label="C5 scaled, no table")
+        compare_all(ci, synth.make_queries(cfg, ci)[0], cfg.nprobe, cfg.k, cfg.metric, row_tables=True, label="C5 scaled, with table")
 
 
 def test_bfloat16_values_beyond_binary16_keep_the_bfloat16_scan():
@@ -723,7 +832,7 @@ def test_bfloat16_values_beyond_binary16_keep_the_bfloat16_scan():
     idx.list_vectors[1234, 7] = 1.0e6
     idx.list_vectors[77, 0] = -3.0e5
     q = torch.randn(50, 64, generator=torch.Generator().manual_seed(8)).cuda()
-    compare_all(idx, q, nprobe=12, k=5, metric="ip")
+    compare_all(idx, q, nprobe=12, k=5, metric="ip", row_tables=True)
 
 
 
