@@ -48,6 +48,7 @@ enum {
 #define HR_NPROBE_MAX 512     /* largest nprobe (the paper probes 128 to 512 clusters: Section 6.1) */
 #define HR_WORKSPACE_ALIGN 256
 #define HR_LOAD_ROW_TABLES 0x100      /* or-ed into hr_ivf_load's dtype: see there */
+#define HR_STATIC_SCRATCH_BYTES (64u << 20)   /* scratch of hr_ivf_search_static: 64 MiB per GPU */
 
 /*
  * hr_ivf_load — wrap an IVF-Flat index that already lives in HBM (Section 2.2: vectors
@@ -113,6 +114,27 @@ size_t hr_ivf_workspace_bytes(const hr_ivf_index* index, int64_t nq, int32_t npr
 int hr_ivf_search(const hr_ivf_index* index, const float* queries, int64_t nq, int32_t nprobe,
                   int32_t k, int32_t metric, int64_t* out_ids, float* out_scores,
                   void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * hr_ivf_search_static — hr_ivf_search for callers that cannot allocate device memory or have no
+ * workspace to pass: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments without the workspace; the scratch memory is an array of
+ * HR_STATIC_SCRATCH_BYTES (64 MiB) inside the library's device image, which every GPU the
+ * library runs on holds until the process ends.  The call allocates nothing and frees nothing,
+ * it only enqueues kernels on `stream`; the index's device must be the current one.
+ * To fit the array, the list scan is cut into about 256 work items instead of about 4096 and the
+ * coarse keys of at most 4 MiB of queries x lists are scored at a time; results are the same bits
+ * as hr_ivf_search's.  A batch shape that needs more scratch is refused with HR_ERR_WORKSPACE and
+ * a message that gives the bytes needed (what fits: e.g. 512 queries x nprobe 32, k 10 on 4096
+ * lists of 768 dimensions takes about 31 MiB; the bulk are the 128 x 256 + nq x nprobe result
+ * slots of 512 bytes each for k <= 24, 1024 up to k = 64, 1536 beyond).
+ * All calls on one GPU share that GPU's array: two calls that overlap in time (different
+ * streams, or threads) race; put them on one stream or give one of them hr_ivf_search with a
+ * workspace of its own.  The array keeps what the last call left; every call clears what it
+ * needs cleared.
+ */
+int hr_ivf_search_static(const hr_ivf_index* index, const float* queries, int64_t nq, int32_t nprobe,
+                         int32_t k, int32_t metric, int64_t* out_ids, float* out_scores, void* stream);
 
 /*
  * hr_ivf_coarse — first half only: the choice of the clusters a query is searched in (Section 2.2).

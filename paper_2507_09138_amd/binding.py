@@ -16,6 +16,7 @@ HR_METRIC_IP, HR_METRIC_L2 = 0, 1
 HR_F32, HR_F16, HR_BF16 = 0, 1, 2
 HR_K_MAX, HR_NPROBE_MAX = 128, 512
 HR_LOAD_ROW_TABLES = 0x100
+HR_STATIC_SCRATCH_BYTES = 64 << 20
 _ERR = {-1: "HR_ERR_ARG", -2: "HR_ERR_HANDLE", -3: "HR_ERR_WORKSPACE", -4: "HR_ERR_HIP",
         -5: "HR_ERR_UNSUPPORTED"}
 _DTYPE = {torch.float32: HR_F32, torch.float16: HR_F16, torch.bfloat16: HR_BF16}
@@ -41,6 +42,7 @@ def _load_lib():
     L.hr_ivf_workspace_bytes.argtypes = [p, c.c_int64, c.c_int32, c.c_int32]
     L.hr_ivf_workspace_bytes.restype = c.c_size_t
     L.hr_ivf_search.argtypes = [p, p, c.c_int64, c.c_int32, c.c_int32, c.c_int32, p, p, p, c.c_size_t, p]
+    L.hr_ivf_search_static.argtypes = [p, p, c.c_int64, c.c_int32, c.c_int32, c.c_int32, p, p, p]
     L.hr_ivf_coarse.argtypes = [p, p, c.c_int64, c.c_int32, c.c_int32, p, p, p, c.c_size_t, p]
     L.hr_ivf_scan.argtypes = [p, p, c.c_int64, p, c.c_int32, c.c_int32, c.c_int32, p, p, p, c.c_size_t, p]
     L.hr_ivf_list_hits.argtypes = [p, p, c.c_int32, p]
@@ -111,6 +113,11 @@ def hr_ivf_search(handle, queries, nq, nprobe, k, metric, out_ids, out_scores, w
                   workspace_bytes, stream=None):
     _check(lib.hr_ivf_search(handle, _addr(queries), nq, nprobe, k, metric, _addr(out_ids),
                              _addr(out_scores), _addr(workspace), workspace_bytes, _stream(stream)))
+
+
+def hr_ivf_search_static(handle, queries, nq, nprobe, k, metric, out_ids, out_scores, stream=None):
+    _check(lib.hr_ivf_search_static(handle, _addr(queries), nq, nprobe, k, metric, _addr(out_ids),
+                                    _addr(out_scores), _stream(stream)))
 
 
 def hr_ivf_coarse(handle, queries, nq, nprobe, metric, out_probe_ids, out_probe_scores, workspace,

@@ -4,8 +4,39 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 
 #include "common.h"
+
+// Scratch memory of hr_ivf_search_static, the entry point for callers that cannot allocate: a
+// fixed array in the library's device image, one copy per GPU, held until the process ends.  In
+// host code the array's name only stands for the symbol; its address on a device is asked for
+// once per device (with that device current) and kept, and that pointer is what the kernels get.
+static __device__ __align__(256) unsigned char scratch[HR_STATIC_SCRATCH_BYTES];
+static constexpr int kMaxDevices = 64;
+static void* g_scratch[kMaxDevices];           // device address of `scratch` per device, null until asked for
+static std::mutex g_scratch_mu;
+
+// address of the scratch array on device `dev`, which must be the current device.  (Not a static function: the
+// compiler gives a file-scope static device variable a symbol that the runtime can look up only when a host
+// function with external linkage names it.)
+namespace hr {
+hipError_t static_scratch_address(int dev, void** out);
+}
+hipError_t hr::static_scratch_address(int dev, void** out)
+{
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (g_scratch[dev] == nullptr) {
+        void* p = nullptr;
+        hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (p == nullptr) return hipErrorInvalidSymbol;
+        g_scratch[dev] = p;
+    }
+    *out = g_scratch[dev];
+    return hipSuccess;
+}
 
 namespace hr {
 hipError_t launch_scan_f32(int d, const ScanArgs& a, int shape, int grid, size_t lds, hipStream_t s);
@@ -130,6 +161,8 @@ struct hr_ivf_index {
     unsigned long long* d_hits;   // [nlist] probes per list since load / last reset
     int num_cus;
     int lds_limit;
+    int device;            // the device the index lives on
+    void* scratch;         // address of the library's static scratch array on that device
     // optional kernel timing (hr_ivf_profile_begin/end)
     hipEvent_t* prof_ev;   // 2 * prof_cap events
     int prof_cap, prof_n;
@@ -299,7 +332,9 @@ int hr_ivf_load(const float* centroids, const int64_t* list_offsets, const void*
     int* h_off = new (std::nothrow) int[nlist + 1];
     if (!h_off) { delete ix; return fail(HR_ERR_HIP, "out of host memory"); }
     for (int64_t l = 0; l <= nlist; l++) h_off[l] = (int)list_offsets[l];
+    ix->device = dev;
     hipError_t e = hipDeviceGetAttribute(&ix->num_cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e == hipSuccess) e = hr::static_scratch_address(dev, &ix->scratch);
     ix->lds_limit = 160 * 1024;     // LDS per workgroup on gfx950
     if (e == hipSuccess) {
         hipDeviceProp_t prop;
@@ -618,6 +653,34 @@ int hr_ivf_search(const hr_ivf_index* ix, const float* queries, int64_t nq, int3
     const Plan p = make_plan(ix, nq, nprobe, k);
     if (int rc = check_ws(p, workspace, workspace_bytes)) return rc;
     char* ws = (char*)workspace;
+    hipStream_t s = (hipStream_t)stream;
+    if (int rc = enqueue_clear(p, ws, nq, s)) return rc;
+    HR_HIP(launch_prep_queries(queries, nq, ix->d, operand_dtype(ix), ws + p.o_qop_c, (float*)(ws + p.o_qnorm_c),
+                               operand_dtype(ix) == HR_F32 ? nullptr : ws + p.o_qop_s, (float*)(ws + p.o_qnorm_s), s));
+    int32_t* probe = (int32_t*)(ws + p.o_probe);
+    if (int rc = enqueue_coarse(ix, p, ws, nq, nprobe, metric, probe, nullptr, s)) return rc;
+    return enqueue_scan(ix, p, ws, nq, probe, nprobe, k, metric, out_ids, out_scores, s);
+}
+
+// Limits of a plan that has to fit the static scratch array: few, large work items (result slots are
+// what takes the room) and a small coarse key table.
+static constexpr PlanLimits kStaticLimits = {256, (size_t)4 << 20};
+
+int hr_ivf_search_static(const hr_ivf_index* ix, const float* queries, int64_t nq, int32_t nprobe, int32_t k,
+                         int32_t metric, int64_t* out_ids, float* out_scores, void* stream)
+{
+    if (int rc = check_index(ix)) return rc;
+    if (int rc = check_batch(ix, nq, nprobe, k, metric, true)) return rc;
+    if (nq == 0) return HR_OK;
+    if (!queries || !out_ids || !out_scores) return fail(HR_ERR_ARG, "queries / out_ids / out_scores is null");
+    int dev = -1;
+    HR_HIP(hipGetDevice(&dev));
+    if (dev != ix->device) return fail(HR_ERR_ARG, "current device is %d, the index lives on device %d", dev, ix->device);
+    const Plan p = make_plan(ix, nq, nprobe, k, kStaticLimits);
+    if (p.total > (size_t)HR_STATIC_SCRATCH_BYTES)
+        return fail(HR_ERR_WORKSPACE, "this batch (nq=%lld, nprobe=%d, k=%d) needs %zu bytes of scratch, the static array has %zu: "
+                                      "use hr_ivf_search with a workspace", (long long)nq, nprobe, k, p.total, (size_t)HR_STATIC_SCRATCH_BYTES);
+    char* ws = (char*)ix->scratch;
     hipStream_t s = (hipStream_t)stream;
     if (int rc = enqueue_clear(p, ws, nq, s)) return rc;
     HR_HIP(launch_prep_queries(queries, nq, ix->d, operand_dtype(ix), ws + p.o_qop_c, (float*)(ws + p.o_qnorm_c),
