@@ -19,8 +19,25 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-MFMA_PEAK_TFLOPS = {"f16": 2500.0, "bf16": 2500.0, "f32": 2500.0}   # f32 rows run as binary16 pairs
+F16_MFMA_PEAK_TFLOPS = 2500.0      # dense binary16 / bfloat16 MFMA
+F32_PEAK_TFLOPS = 157.3            # float32 (vector or MFMA): what float32 storage is priced against
 ESIZE = {"f32": 4, "f16": 2, "bf16": 2}
+
+
+def mfma_peak(cfg, ix):
+    """float32 lists are a float32 contraction to the caller (that it runs as three binary16 products per element on
+    the matrix pipes is this library's choice): its 2 d flops per (query, row) pair are priced against the float32
+    peak; 16-bit lists against the dense 16-bit MFMA peak."""
+    return F32_PEAK_TFLOPS if cfg.dtype == "f32" else F16_MFMA_PEAK_TFLOPS
+
+
+def operand_name(cfg, ix):
+    """The type the list scan multiplies in (accumulation is float32 throughout)."""
+    if cfg.dtype == "f32":
+        return "f16x2"                              # binary16 hi + scaled lo parts of both operands
+    if cfg.dtype == "bf16":
+        return "f16" if ix.row_tables else "bf16"   # binary16 row table asked for at load, else bfloat16 rows x (hi, lo) query
+    return "f16"
 # HBM bytes per list-scan launch (read + written) from the rocprofv3 FETCH_SIZE / WRITE_SIZE counter runs
 # summarised under profiles/ (counters cannot be read from inside this process); other workloads: null
 MEASURED_TRAFFIC = {"C3": 8.94e9 + 0.04e9}
@@ -56,6 +73,64 @@ def cpu_baseline(cfg, idx, q, target_s=30.0):
     return {"value": total_n / total_t, "unit": "queries/s", "cores": threads, "kind": "oracle",
             "sample": f"{total_n} randomly chosen queries of the batch (full index, nprobe={cfg.nprobe}, "
                       f"k={cfg.k}), {total_t:.1f} s after a {n0}-query pilot"}
+
+
+def bench_width_split(args, cfg, hr, ix, idx, rounds, metric):
+    """The list scan on a part of the probe lists only: the lists that at least `--wide-only W` queries of the batch
+    probe (the wide buckets: a dense [rows x d] . [d x queries] contraction, bound by the matrix pipes), or the lists
+    that fewer than `--narrow-only W` probe (bound by the row stream from HBM).  One step = one hr_ivf_scan call with
+    the other places of the probe lists emptied; the scan kernel is timed by the library's events."""
+    import torch
+    nq = cfg.nq
+    q = rounds[0]
+    probe, _ = ix.coarse(q, cfg.nprobe, cfg.metric)
+    w = torch.bincount(probe.flatten().long(), minlength=cfg.nlist)
+    wide = args.wide_only > 0
+    W = args.wide_only if wide else args.narrow_only
+    keep_list = (w >= W) if wide else ((w < W) & (w > 0))
+    part = torch.where(keep_list[probe.long()], probe, torch.full_like(probe, -1)).contiguous()
+    ids = torch.empty(nq, cfg.k, dtype=torch.int64, device="cuda")
+    scores = torch.empty(nq, cfg.k, dtype=torch.float32, device="cuda")
+    ws = ix.workspace(nq, cfg.nprobe, cfg.k)
+
+    def step():
+        hr.hr_ivf_scan(ix.handle, q, nq, part, cfg.nprobe, cfg.k, metric, ids, scores, ws, ws.numel())
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    hr.hr_ivf_profile_begin(ix.handle, args.steps)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / args.steps * 1e3
+    n_timed, scan_ms = hr.hr_ivf_profile_end(ix.handle)
+    st = ix.stats(nq, cfg.nprobe, cfg.k)
+    lens = (idx.list_offsets[1:] - idx.list_offsets[:-1])
+    wk = (w.cpu() * keep_list.cpu())
+    rows = int(lens[keep_list.cpu()].sum())
+    pair_rows = int((wk * lens).sum())
+    assert rows == st["rows_streamed"], (rows, st)
+    nbytes = rows * cfg.d * ESIZE[cfg.dtype]
+    flops = 2.0 * cfg.d * pair_rows
+    tf = flops / (scan_ms * 1e-3) / 1e12
+    gbs = nbytes / (scan_ms * 1e-3) / 1e9
+    peak = mfma_peak(cfg, ix)
+    ix.close()
+    roof = ({"bound": "mfma", "achieved": tf, "peak": peak, "unit": "TFLOP/s", "frac": tf / peak} if wide else
+            {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS})
+    roof.update({"kernel": "k_scan (list scan)", "traffic": None, "scan_ms_avg": scan_ms, "launches_timed": n_timed,
+                 "algorithmic_bytes_per_launch": nbytes, "algorithmic_flops_per_launch": flops,
+                 "hbm_gbs": gbs, "mfma_tflops": tf})
+    print(json.dumps({"metric": "list scan on the %s buckets only" % ("wide" if wide else "narrow"),
+                      "value": tf if wide else gbs, "unit": roof["unit"], "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+                      "ms_per_step": ms, "higher_is_better": True, "data": "synthetic", "dtype": operand_name(cfg, ix),
+                      "config": {"workload": f"{cfg.name}: lists probed by {'at least' if wide else 'fewer than'} {W} of the "
+                                             f"{nq} queries (nprobe={cfg.nprobe}, k={cfg.k}, {cfg.dtype} storage, {cfg.metric})",
+                                 "lists": int(keep_list.sum()), "widest_bucket": int(wk.max()), "pairs": st["pairs"],
+                                 "scan_items": st["items"], "seg_rows": st["seg_rows"]},
+                      "roofline": roof}))
 
 
 def bench_substages(args, cfg, hr, ix, rounds, metric):
@@ -183,6 +258,14 @@ def main():
     ap.add_argument("--graph", action="store_true",
                     help="replay the search from a captured HIP graph (one graph per round of the workload) instead of "
                          "enqueueing its kernels every step: for launch-bound small batches")
+    ap.add_argument("--wide-only", type=int, default=0,
+                    help="extra mode: the list scan over the lists that at least this many queries of the batch probe; "
+                         "reports flops / time against the MFMA peak; prints its own JSON line")
+    ap.add_argument("--narrow-only", type=int, default=0,
+                    help="extra mode: the list scan over the lists that fewer than this many queries probe; reports bytes / "
+                         "time against the HBM peak; prints its own JSON line")
+    ap.add_argument("--row-tables", action="store_true",
+                    help="load float32 / bfloat16 lists with HR_LOAD_ROW_TABLES (binary16 row tables: as many bytes again)")
     ap.add_argument("--noise", type=float, default=0.0, help="spread of vectors and queries around their centroid instead of the workload's own")
     ap.add_argument("--drift", type=float, default=0.0, help="step of a query from round to round instead of the workload's own")
     args = ap.parse_args()
@@ -205,13 +288,15 @@ def main():
     torch.cuda.set_device(0)
     idx = synth.make_index(cfg, "cuda")
     rounds = synth.make_queries(cfg, idx)
-    ix = hr.IvfIndex(idx.centroids, idx.list_offsets, idx.list_vectors, idx.list_ids)
+    ix = hr.IvfIndex(idx.centroids, idx.list_offsets, idx.list_vectors, idx.list_ids, row_tables=args.row_tables)
     nq = cfg.nq
     metric = hr.HR_METRIC_IP if cfg.metric == "ip" else hr.HR_METRIC_L2
     ids = torch.empty(nq, cfg.k, dtype=torch.int64, device="cuda")
     scores = torch.empty(nq, cfg.k, dtype=torch.float32, device="cuda")
     ws = ix.workspace(nq, cfg.nprobe, cfg.k)
 
+    if args.wide_only > 0 or args.narrow_only > 0:
+        return bench_width_split(args, cfg, hr, ix, idx, rounds, metric)
     if args.substages > 0:
         return bench_substages(args, cfg, hr, ix, rounds, metric)
     if args.reuse > 0:
@@ -273,19 +358,19 @@ def main():
         "metric": "queries/sec batched IVF top-k search", "value": nq / (ms_per_step * 1e-3),
         "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": {"f16": "f16", "bf16": "bf16", "f32": "f16x2"}[cfg.dtype],      # MFMA operand type; float32 accumulation
+        "dtype": operand_name(cfg, ix),      # MFMA operand type; float32 accumulation
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}: N={cfg.N}, d={cfg.d}, nlist={cfg.nlist}, nq={nq}, "
                                f"nprobe={cfg.nprobe}, k={cfg.k}, {cfg.dtype} storage, {cfg.metric}",
-                   "rounds": cfg.rounds, "launch": "hip graph replay" if args.graph else "eager", "scan_items": st["items"], "seg_rows": st["seg_rows"],
+                   "row_tables": bool(args.row_tables and cfg.dtype != "f16"), "rounds": cfg.rounds, "launch": "hip graph replay" if args.graph else "eager", "scan_items": st["items"], "seg_rows": st["seg_rows"],
                    "pairs": st["pairs"]},
         "roofline": {"bound": "hbm", "kernel": "k_scan (list scan)", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": MEASURED_TRAFFIC.get(cfg.name), "scan_ms_avg": scan_ms, "launches_timed": n_timed,
                      "algorithmic_bytes_per_launch": scan_bytes,
                      "mfma_tflops": scan_flops / (scan_ms * 1e-3) / 1e12 if scan_ms > 0 else 0.0,
-                     "mfma_frac": (scan_flops / (scan_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS[cfg.dtype])
-                     if scan_ms > 0 else 0.0},
+                     "mfma_frac": (scan_flops / (scan_ms * 1e-3) / 1e12 / mfma_peak(cfg, ix)) if scan_ms > 0 else 0.0,
+                     "mfma_peak_tflops": mfma_peak(cfg, ix)},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, idx, rounds[0])

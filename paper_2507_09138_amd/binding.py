@@ -243,6 +243,7 @@ class IvfIndex:
         self.nlist, self.d = self.centroids.shape
         self.N = self.list_vectors.shape[0]
         self.dtype = _DTYPE[self.list_vectors.dtype]
+        self.row_tables = bool(row_tables)
         self.handle = hr_ivf_load(self.centroids, self.list_offsets, self.list_vectors,
                                   self.list_ids, self.nlist, self.N, self.d,
                                   self.dtype | (HR_LOAD_ROW_TABLES if row_tables else 0))

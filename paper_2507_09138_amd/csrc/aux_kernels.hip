@@ -266,7 +266,9 @@ __global__ __launch_bounds__(1024) void k_bucket_scan(BucketArgs a)
 {
     __shared__ int s_wave[17];
     __shared__ long long s_lwave[16];
+    __shared__ int s_maxseg;
     const int t = threadIdx.x;
+    if (t == 0) s_maxseg = 0;
     const int per = (a.nlist + 1023) / 1024;
     const int l0 = min(a.nlist, t * per), l1 = min(a.nlist, l0 + per);
 
@@ -313,8 +315,12 @@ __global__ __launch_bounds__(1024) void k_bucket_scan(BucketArgs a)
         nseg = (w > 0 && len > 0) ? (len + seg - 1) / seg : 0;
         nqt = (w + a.cw - 1) / a.cw;
     };
-    int items = 0, slots = 0;
-    for (int l = l0; l < l1; l++) { int nseg, nqt; list_items(l, nseg, nqt); items += nseg * nqt; slots += nseg * a.list_w[l]; }
+    int items = 0, slots = 0, maxseg = 0;
+    for (int l = l0; l < l1; l++) {
+        int nseg, nqt; list_items(l, nseg, nqt);
+        items += nseg * nqt; slots += nseg * a.list_w[l]; maxseg = max(maxseg, nseg);
+    }
+    if (maxseg > 0) atomicMax(&s_maxseg, maxseg);
     {
         int run = block_scan_1024(items, s_wave, total);
         for (int l = l0; l < l1; l++) {
@@ -335,7 +341,12 @@ __global__ __launch_bounds__(1024) void k_bucket_scan(BucketArgs a)
             int nseg, nqt; list_items(l, nseg, nqt);
             run += nseg * a.list_w[l];
         }
-        if (t == 0) { a.slot_base[a.nlist] = total; a.dyn[DYN_SLOTS] = total; }
+        if (t == 0) {
+            a.slot_base[a.nlist] = total;
+            a.dyn[DYN_SLOTS] = total;
+            // rounds of the queues: the longest list has eight segments per round
+            a.dyn[DYN_ROUNDS] = max(1, min(kRounds, (s_maxseg + 7) / 8));
+        }
     }
 }
 
@@ -350,19 +361,29 @@ __global__ void k_bucket_scatter(BucketArgs a)
 }
 
 // Work items and their order of execution.  Items are numbered list-major (segment-major,
-// query tile minor inside a list); that number addresses the item's result slots.  The order
-// of execution is given by eight queues, one per XCD: all query tiles of one (list, segment)
-// go to the same queue, next to each other, so the workgroups that re-read that segment run
-// on one XCD at about the same time and share it through that XCD's L2.  Inside a queue the
-// segments are ordered in rounds: the first segment that every list has in the queue, then
-// the second ones, and so on.  The segments of a long list are thus spread over the whole
-// run, and the later ones start from the lower bounds that the earlier ones have published.
-// (Within a round the order is that of arrival; results do not depend on the order.)
-constexpr int kRounds = 64;        // segments of a list beyond that many per queue share the last round
+// query tile minor inside a list).  The order of execution is given by eight queues, one per
+// XCD: all query tiles of one (list, segment) go to the same queue, next to each other, so the
+// workgroups that re-read that segment run on one XCD at about the same time and share it
+// through that XCD's L2.  Inside a queue the segments are ordered in rounds.  The longest list
+// has eight segments per round, in order: its segments are spread over the whole run, and the
+// later ones start from the lower bounds that the earlier ones have published.  The segments
+// of a shorter list are spread evenly over the same rounds from a start that depends on the
+// list (a list of one segment lands in a round of its own choosing).  So every stretch of a
+// queue holds the same mix of items that many queries share (long lists of popular clusters:
+// bound by the matrix pipes) and items of a few queries (bound by the row stream from HBM), and
+// the two kinds run side by side on the compute units of an XCD for the whole run; with all
+// short lists in the first round the device streams rows with idle matrix pipes first and
+// multiplies with an idle HBM afterwards.  (Within a round the order is that of arrival;
+// results do not depend on the order.)
+// (kRounds, the most rounds a queue has, is declared with the device scalars in common.h)
 
-// segment s of list l: queue and round
+// segment s of the nseg segments of list l: queue and round (R rounds in use)
 __device__ __forceinline__ int queue_of(int l, int s) { return (l + s) & 7; }
-__device__ __forceinline__ int round_of(int s) { return min(s >> 3, kRounds - 1); }
+__device__ __forceinline__ int round_of(int l, int s, int nseg, int R)
+{
+    const unsigned u = ((unsigned)l * 2654435761u) >> 16;            // start of the list inside its first stretch, in 65536ths
+    return (int)((((long long)s << 16) + u) * R / ((long long)nseg << 16));
+}
 
 __global__ __launch_bounds__(256) void k_round_count(BucketArgs a)
 {
@@ -375,7 +396,8 @@ __global__ __launch_bounds__(256) void k_round_count(BucketArgs a)
     int seg = a.dyn[DYN_SEG_ROWS];
     int nqt = (w + a.cw - 1) / a.cw;
     int nseg = (len + seg - 1) / seg;
-    for (int s = lane; s < nseg; s += 64) atomicAdd(&a.round_cnt[queue_of(l, s) * kRounds + round_of(s)], nqt);
+    const int R = a.dyn[DYN_ROUNDS];
+    for (int s = lane; s < nseg; s += 64) atomicAdd(&a.round_cnt[queue_of(l, s) * kRounds + round_of(l, s, nseg, R)], nqt);
 }
 
 // 8 x kRounds counts -> where every round starts in its queue, and the queue lengths
@@ -401,8 +423,9 @@ __global__ __launch_bounds__(256) void k_item_expand(BucketArgs a)
     int nseg = (len + seg - 1) / seg;
     long long base = a.item_base[l];
     const long long sbase = a.slot_base[l];
+    const int R = a.dyn[DYN_ROUNDS];
     for (int s = lane; s < nseg; s += 64) {
-        const int x = queue_of(l, s), slot = x * kRounds + round_of(s);
+        const int x = queue_of(l, s), slot = x * kRounds + round_of(l, s, nseg, R);
         const int pos = a.round_cnt[slot] + atomicAdd(&a.round_cur[slot], nqt);
         for (int t = 0; t < nqt; t++) {
             long long idx = base + (long long)s * nqt + t;

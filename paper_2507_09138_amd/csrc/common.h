@@ -122,7 +122,8 @@ struct SeedArgs {
 };
 
 // Device scalars written by the bucketing kernels (ints in workspace)
-enum { DYN_ITEMS = 0, DYN_SEG_ROWS = 1, DYN_ROWS_LO = 2, DYN_ROWS_HI = 3, DYN_PAIRS = 4, DYN_SLOTS = 5, DYN_COUNT = 8 };
+enum { DYN_ITEMS = 0, DYN_SEG_ROWS = 1, DYN_ROWS_LO = 2, DYN_ROWS_HI = 3, DYN_PAIRS = 4, DYN_SLOTS = 5, DYN_ROUNDS = 6, DYN_COUNT = 8 };
+constexpr int kRounds = 64;                // most rounds of a work queue (see the bucketing kernels)
 
 struct MergeArgs {
     const int* slot_cnt;
