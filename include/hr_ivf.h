@@ -187,6 +187,33 @@ int hr_ivf_scan_step(const hr_ivf_index* index, const float* queries, int64_t nq
 int hr_ivf_hot_lists(const hr_ivf_index* index, int32_t gc, int32_t* out_lists, void* stream);
 
 /*
+ * Partial residency (Section 4.4: only the most frequently accessed clusters are kept in GPU memory and updated
+ * from time to time; searches of the other clusters are served elsewhere, and the partial results of a request
+ * are merged).  The index keeps a flag per list: are its vectors in place?  All lists are, after hr_ivf_load.
+ *
+ * hr_ivf_set_resident — set the flag of the given lists.
+ *   lists     DEV [n] int32 list numbers (entries outside 0..nlist-1 are ignored), or NULL: all lists.
+ *   resident  0: the lists' rows may be overwritten by the caller from now on; no search reads them: their
+ *             probes are dropped by hr_ivf_search / hr_ivf_scan / the step-wise calls (and still counted by
+ *             hr_ivf_list_hits).  1: the rows are in place again (after the caller's copy and
+ *             hr_ivf_refresh_rows on the same stream, or behind them).
+ * Enqueues one small kernel; searches enqueued later on the same stream see the new flags.
+ *
+ * hr_ivf_split_probes — which of a batch's probes can be served here.
+ *   probe_ids     DEV [nq, nprobe] int32 (as hr_ivf_coarse writes them, or any rows hr_ivf_scan would take)
+ *   out_resident  DEV [nq, nprobe] int32: the lists of each row whose vectors are in place, in the given order,
+ *                 then -1: what to hand to hr_ivf_scan / hr_ivf_scan_step
+ *   out_missing   DEV [nq, nprobe] int32: the other lists of the row, in the given order, then -1: what the
+ *                 caller has to search elsewhere (their partial results can be merged in by the caller, or
+ *                 the lists scanned here in a later step once they are resident).  These probes are counted
+ *                 as accesses here, since no scan will see them.
+ * The three arrays must be distinct.  Entries outside 0..nlist-1 appear in neither output.
+ */
+int hr_ivf_set_resident(hr_ivf_index* index, const int32_t* lists, int64_t n, int32_t resident, void* stream);
+int hr_ivf_split_probes(const hr_ivf_index* index, const int32_t* probe_ids, int64_t nq, int32_t nprobe,
+                        int32_t* out_resident, int32_t* out_missing, void* stream);
+
+/*
  * hr_ivf_refresh_rows — after the caller has replaced the vectors of rows row_begin ..
  * row_end-1 in list_vectors (a cluster loaded asynchronously into the place of another one of
  * the same length: the index loading interface of Section 5), recompute what the library

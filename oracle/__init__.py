@@ -196,6 +196,23 @@ def hot_lists(hits, gc):
     return np.lexsort((np.arange(hits.size), -hits))[:gc].astype(np.int64)
 
 
+def split_probes(probe, resident):
+    """Partial residency (Section 4.4 of the paper: only some clusters are kept where the search runs; the others
+    are searched elsewhere): every row of ``probe`` split into the lists that are resident (``resident[l]`` true) and
+    the others, each part in the given order and padded with -1; entries outside 0..nlist-1 go to neither.  Plain
+    Python, row by row."""
+    probe = np.asarray(probe)
+    nlist = len(resident)
+    res = np.full_like(probe, -1)
+    mis = np.full_like(probe, -1)
+    for q in range(probe.shape[0]):
+        a = [int(l) for l in probe[q] if 0 <= l < nlist and resident[l]]
+        b = [int(l) for l in probe[q] if 0 <= l < nlist and not resident[l]]
+        res[q, :len(a)] = a
+        mis[q, :len(b)] = b
+    return res, mis
+
+
 def ivf_search(queries, centroids, offsets, vectors, dtype, ids, nprobe, k, metric):
     """Whole search.  Returns (probe_ids, ids, scores)."""
     q = _as(queries, np.float32)

@@ -47,6 +47,8 @@ def _load_lib():
     L.hr_ivf_scan.argtypes = [p, p, c.c_int64, p, c.c_int32, c.c_int32, c.c_int32, p, p, p, c.c_size_t, p]
     L.hr_ivf_list_hits.argtypes = [p, p, c.c_int32, p]
     L.hr_ivf_hot_lists.argtypes = [p, c.c_int32, p, p]
+    L.hr_ivf_set_resident.argtypes = [p, p, c.c_int64, c.c_int32, p]
+    L.hr_ivf_split_probes.argtypes = [p, p, c.c_int64, c.c_int32, p, p, p]
     L.hr_ivf_refresh_rows.argtypes = [p, c.c_int64, c.c_int64, p]
     L.hr_ivf_scan_step.argtypes = [p, p, c.c_int64, p, c.c_int32, c.c_int32, c.c_int32, p, p, p, c.c_size_t, p]
     L.hr_ivf_scan_step_rows.argtypes = [p, p, c.c_int64, p, c.c_int32, c.c_int32, c.c_int32, p, p, p, p, c.c_size_t, p]
@@ -169,6 +171,15 @@ def hr_ivf_list_hits(handle, out_hits, reset=False, stream=None):
 
 def hr_ivf_hot_lists(handle, gc, out_lists, stream=None):
     _check(lib.hr_ivf_hot_lists(handle, gc, _addr(out_lists), _stream(stream)))
+
+
+def hr_ivf_set_resident(handle, lists, n, resident, stream=None):
+    _check(lib.hr_ivf_set_resident(handle, _addr(lists), n, 1 if resident else 0, _stream(stream)))
+
+
+def hr_ivf_split_probes(handle, probe_ids, nq, nprobe, out_resident, out_missing, stream=None):
+    _check(lib.hr_ivf_split_probes(handle, _addr(probe_ids), nq, nprobe, _addr(out_resident), _addr(out_missing),
+                                   _stream(stream)))
 
 
 def hr_ivf_refresh_rows(handle, row_begin, row_end, stream=None):
@@ -377,6 +388,22 @@ class IvfIndex:
         out = torch.empty(_want_range(gc, "gc", 1, self.nlist), dtype=torch.int32, device=self.device)
         hr_ivf_hot_lists(self.handle, gc, out)
         return out
+
+    def set_resident(self, lists, resident):
+        """Mark the given lists (int tensor on the device, or None: all lists) as in place / not in place."""
+        if lists is None:
+            hr_ivf_set_resident(self.handle, None, 0, resident)
+        else:
+            ls = _want_int(lists, "lists", (None,), self.device)
+            hr_ivf_set_resident(self.handle, ls, ls.numel(), resident)
+
+    def split_probes(self, probe_ids):
+        """(lists in place, lists not in place) of every row of probe_ids [nq, nprobe], each -1-padded."""
+        pr = _want_int(probe_ids, "probe_ids", (None, None), self.device)
+        _want_range(pr.shape[1], "nprobe", 1, HR_NPROBE_MAX)
+        res, mis = torch.empty_like(pr), torch.empty_like(pr)
+        hr_ivf_split_probes(self.handle, pr, pr.shape[0], pr.shape[1], res, mis)
+        return res, mis
 
     def refresh_rows(self, row_begin, row_end):
         """After the vectors of these rows were replaced in place: recompute what is derived from them."""

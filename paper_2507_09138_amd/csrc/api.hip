@@ -159,6 +159,7 @@ struct hr_ivf_index {
     void* d_vec16;         // bfloat16 lists only, when memory and the value range allow: [N, d] the rows as binary16
     int* d_flag;           // two device ints: [0] a bfloat16 value did not fit binary16, [1] a negative label
     unsigned long long* d_hits;   // [nlist] probes per list since load / last reset
+    int* d_resident;       // [nlist] 1 = the list's vectors are in place (all lists, until the caller says otherwise)
     int num_cus;
     int lds_limit;
     int device;            // the device the index lives on
@@ -352,6 +353,8 @@ int hr_ivf_load(const float* centroids, const int64_t* list_offsets, const void*
     if (e == hipSuccess) e = hipMalloc(&ix->d_cent_lo, (size_t)nlist * d * 2);
     if (e == hipSuccess) e = hipMalloc(&ix->d_hits, (size_t)nlist * 8);
     if (e == hipSuccess) e = hipMalloc(&ix->d_flag, 2 * sizeof(int));
+    if (e == hipSuccess) e = hipMalloc(&ix->d_resident, (size_t)nlist * sizeof(int));
+    if (e == hipSuccess) e = launch_set_resident(ix->d_resident, (int)nlist, nullptr, nlist, 1, s);
     if (e == hipSuccess) e = hipMemsetAsync(ix->d_hits, 0, (size_t)nlist * 8, s);
     if (e == hipSuccess) e = hipMemsetAsync(ix->d_flag, 0, 2 * sizeof(int), s);
     if (e == hipSuccess) e = launch_check_labels(list_ids, N, ix->d_flag + 1, s);
@@ -401,6 +404,7 @@ int hr_ivf_load(const float* centroids, const int64_t* list_offsets, const void*
         if (ix->d_cent_hi) (void)hipFree(ix->d_cent_hi);
         if (ix->d_cent_lo) (void)hipFree(ix->d_cent_lo);
         if (ix->d_hits) (void)hipFree(ix->d_hits);
+        if (ix->d_resident) (void)hipFree(ix->d_resident);
         if (ix->d_vec_hi) (void)hipFree(ix->d_vec_hi);
         if (ix->d_vec_lo) (void)hipFree(ix->d_vec_lo);
         if (ix->d_vec16) (void)hipFree(ix->d_vec16);
@@ -470,6 +474,7 @@ int hr_ivf_free(hr_ivf_index* ix)
     (void)hipFree(ix->d_cent_hi);
     (void)hipFree(ix->d_cent_lo);
     (void)hipFree(ix->d_hits);
+    (void)hipFree(ix->d_resident);
     if (ix->d_vec_hi) (void)hipFree(ix->d_vec_hi);
     if (ix->d_vec_lo) (void)hipFree(ix->d_vec_lo);
     if (ix->d_vec16) (void)hipFree(ix->d_vec16);
@@ -560,6 +565,7 @@ static int enqueue_scan(const hr_ivf_index* ix, const Plan& p, char* ws, int64_t
     b.list_off = ix->d_list_off;
     b.list_w = zero;
     b.hits = ix->d_hits;
+    b.resident = ix->d_resident;
     b.pair_entry = (int*)(ws + p.o_pair_entry);
     b.bucket_off = (int*)(ws + p.o_bucket_off);
     b.bucket_q = (int*)(ws + p.o_bucket_q);
@@ -582,7 +588,7 @@ static int enqueue_scan(const hr_ivf_index* ix, const Plan& p, char* ws, int64_t
                                 (uint32_t*)(ws + p.o_thr) + nq, s));
     SeedArgs sd{};
     sd.rows = row_table(ix); sd.row_norm = ix->d_row_norm; sd.qop = ws + p.o_qop_s;
-    sd.probe = probe; sd.list_off = ix->d_list_off;
+    sd.probe = probe; sd.list_off = ix->d_list_off; sd.resident = ix->d_resident;
     sd.thr = (uint32_t*)(ws + p.o_thr) + nq;
     sd.hpar = (float*)(zero + p.zoff_hpar);
     sd.nq = (int)nq; sd.nprobe = nprobe; sd.nlist = (int)ix->nlist; sd.k = k;
@@ -821,6 +827,30 @@ int hr_ivf_hot_lists(const hr_ivf_index* ix, int32_t gc, int32_t* out_lists, voi
     if (ix->nlist > 65536) return fail(HR_ERR_UNSUPPORTED, "hr_ivf_hot_lists ranks by counting: nlist=%lld > 65536", (long long)ix->nlist);
     if (!out_lists) return fail(HR_ERR_ARG, "out_lists is null");
     HR_HIP(launch_hot_lists(ix->d_hits, (int)ix->nlist, gc, out_lists, (hipStream_t)stream));
+    return HR_OK;
+}
+
+int hr_ivf_set_resident(hr_ivf_index* ix, const int32_t* lists, int64_t n, int32_t resident, void* stream)
+{
+    if (int rc = check_index(ix)) return rc;
+    if (n < 0) return fail(HR_ERR_ARG, "n=%lld is negative", (long long)n);
+    if (lists == nullptr) n = ix->nlist;                     // all lists
+    HR_HIP(launch_set_resident(ix->d_resident, (int)ix->nlist, lists, n, resident != 0 ? 1 : 0, (hipStream_t)stream));
+    return HR_OK;
+}
+
+int hr_ivf_split_probes(const hr_ivf_index* ix, const int32_t* probe_ids, int64_t nq, int32_t nprobe,
+                        int32_t* out_resident, int32_t* out_missing, void* stream)
+{
+    if (int rc = check_index(ix)) return rc;
+    if (nq < 0 || nq > (1 << 24)) return fail(HR_ERR_ARG, "nq=%lld out of range", (long long)nq);
+    if (nprobe < 1 || nprobe > HR_NPROBE_MAX) return fail(HR_ERR_ARG, "nprobe=%d must be in 1..%d", nprobe, HR_NPROBE_MAX);
+    if (nq == 0) return HR_OK;
+    if (!probe_ids || !out_resident || !out_missing) return fail(HR_ERR_ARG, "probe_ids / outputs null");
+    if (probe_ids == out_resident || probe_ids == out_missing || out_resident == out_missing)
+        return fail(HR_ERR_ARG, "the three arrays must be distinct");
+    HR_HIP(launch_split_probes(probe_ids, nq, nprobe, ix->d_resident, (int)ix->nlist, ix->d_hits, out_resident, out_missing,
+                               (hipStream_t)stream));
     return HR_OK;
 }
 

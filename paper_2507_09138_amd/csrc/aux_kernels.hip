@@ -90,6 +90,62 @@ hipError_t launch_read_hits(unsigned long long* hits, int64_t n, int64_t* out, i
     return hipGetLastError();
 }
 
+// Partial residency (Section 4.4 of the paper: only the most frequently accessed clusters are kept in GPU memory, the
+// searches of the others are served elsewhere and the partial results merged).  A flag per list says whether its
+// vectors are in place; the grouping of probes drops the probes of the other lists.
+__global__ void k_set_resident(int* resident, int nlist, const int32_t* lists, int64_t n, int value)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    if (lists == nullptr) { resident[i] = value; return; }
+    const int l = lists[i];
+    if (l >= 0 && l < nlist) resident[l] = value;
+}
+
+hipError_t launch_set_resident(int* resident, int nlist, const int32_t* lists, int64_t n, int value, hipStream_t s)
+{
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_set_resident, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, resident, nlist, lists, n, value);
+    return hipGetLastError();
+}
+
+// Every query's probe list split into the lists whose vectors are in place and the others, each part in the given
+// order, the rest of both rows filled with -1 (entries outside 0..nlist-1 go to neither).  The lists of the second
+// part are counted as accessed here: no scan will see them.  One wave per query.
+__global__ __launch_bounds__(256) void k_split_probes(const int32_t* probe, int64_t nq, int np, const int* resident, int nlist,
+                                                      unsigned long long* hits, int32_t* out_res, int32_t* out_mis)
+{
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int64_t q = (int64_t)blockIdx.x * 4 + wave;
+    if (q >= nq) return;
+    int nres = 0, nmis = 0;
+    for (int i0 = 0; i0 < np; i0 += 64) {
+        const int i = i0 + lane;
+        const int l = i < np ? probe[q * np + i] : -1;
+        const bool valid = l >= 0 && l < nlist;
+        const bool here = valid && resident[l] != 0;
+        const unsigned long long mr = __builtin_amdgcn_ballot_w64(here), mm = __builtin_amdgcn_ballot_w64(valid && !here);
+        if (here) out_res[q * np + nres + lanes_below(mr)] = l;
+        if (valid && !here) {
+            out_mis[q * np + nmis + lanes_below(mm)] = l;
+            if (hits != nullptr) atomicAdd(&hits[l], 1ull);
+        }
+        nres += __builtin_popcountll(mr);
+        nmis += __builtin_popcountll(mm);
+    }
+    for (int i = nres + lane; i < np; i += 64) out_res[q * np + i] = -1;
+    for (int i = nmis + lane; i < np; i += 64) out_mis[q * np + i] = -1;
+}
+
+hipError_t launch_split_probes(const int32_t* probe, int64_t nq, int np, const int* resident, int nlist, unsigned long long* hits,
+                               int32_t* out_resident, int32_t* out_missing, hipStream_t s)
+{
+    if (nq <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_split_probes, dim3((unsigned)((nq + 3) / 4)), dim3(256), 0, s, probe, nq, np, resident, nlist, hits,
+                       out_resident, out_missing);
+    return hipGetLastError();
+}
+
 // The gc most frequently probed lists, most frequent first, equal counts by list number: the
 // lists a cache of hot clusters would keep (Section 4.4).  Every list counts the lists that
 // come before it (tiles of the counters pass through LDS); its rank is its place in the output.
@@ -227,7 +283,11 @@ __global__ void k_bucket_count(BucketArgs a)
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= (int64_t)a.nq * a.nprobe) return;
     int l = a.probe[i];
-    a.pair_entry[i] = (l >= 0 && l < a.nlist) ? atomicAdd(&a.list_w[l], 1) : -1;
+    const bool valid = l >= 0 && l < a.nlist;
+    const bool here = valid && a.resident[l] != 0;
+    // (a list whose vectors are not in place is not scanned; the probe still counts as an access)
+    if (valid && !here && a.hits != nullptr) atomicAdd(&a.hits[l], 1ull);
+    a.pair_entry[i] = here ? atomicAdd(&a.list_w[l], 1) : -1;
 }
 
 // Exclusive prefix sum over the 1024 threads of a workgroup (16 waves); total returned to all.

@@ -114,8 +114,9 @@ struct SeedArgs {
     const void* rows;           // [nrows, d] storage
     const float* row_norm;      // [nrows]
     const void* qop;            // query operand rows
-    const int* probe;           // [nq, nprobe]; column 0 is the list used
+    const int* probe;           // [nq, nprobe]; the first resident list among the first 64 places is the one used
     const int* list_off;        // [nlist+1]
+    const int* resident;        // [nlist] 1 = the list's vectors are in place
     uint32_t* thr;              // [nq]
     float* hpar;                // [nq][2] histogram parameters of the scan (see ScanArgs)
     int nq, nprobe, nlist, k, seed_rows, l2;
@@ -167,6 +168,9 @@ hipError_t launch_rescore(const float* q, int64_t nq, int d, int dtype, const vo
                           int64_t* out_ids, float* out_scores, int32_t* out_rows, hipStream_t s);
 hipError_t launch_bf16_to_f16(const void* x, int64_t n, void* out, int* overflow, hipStream_t s);
 hipError_t launch_split_f32(const float* x, int64_t n, void* hi, void* lo, hipStream_t s);
+hipError_t launch_set_resident(int* resident, int nlist, const int32_t* lists, int64_t n, int value, hipStream_t s);
+hipError_t launch_split_probes(const int32_t* probe, int64_t nq, int np, const int* resident, int nlist, unsigned long long* hits,
+                               int32_t* out_resident, int32_t* out_missing, hipStream_t s);
 hipError_t launch_check_labels(const int64_t* ids, int64_t n, int* negative, hipStream_t s);
 
 struct BucketArgs {
@@ -189,6 +193,7 @@ struct BucketArgs {
     int slot_cap;               // result slots the workspace holds
     int item_target;            // aimed number of work items (rows per segment follow from it)
     unsigned long long* hits;   // [nlist] probes per list since load or the last reset (index-owned), or nullptr
+    const int* resident;        // [nlist] 1 = the list's vectors are in place; probes of the other lists are dropped
 };
 hipError_t launch_bucketing(const BucketArgs& a, hipStream_t s);
 

@@ -994,8 +994,14 @@ __global__ __launch_bounds__(256) void k_seed(SeedArgs a)
     const int lane = lane_id(), wave = threadIdx.x >> 6;
     const int64_t q = (int64_t)blockIdx.x * 4 + wave;
     if (q >= a.nq) return;
-    const int l = a.probe[q * a.nprobe];
-    if (l < 0 || l >= a.nlist) return;
+    // the best-ranked list of the query whose vectors are in place (among the first 64 places of its row)
+    int l = -1;
+    {
+        const int c = lane < a.nprobe ? a.probe[q * a.nprobe + lane] : -1;
+        const unsigned long long ok = __builtin_amdgcn_ballot_w64(c >= 0 && c < a.nlist && a.resident[c] != 0);
+        if (ok == 0) return;
+        l = __builtin_amdgcn_readlane(c, __builtin_ctzll(ok));
+    }
     const int row0 = a.list_off[l];
     const int nrows = min(a.list_off[l + 1] - row0, a.seed_rows);
     if (nrows < a.k) return;

@@ -751,6 +751,78 @@ def test_refresh_rows_after_vectors_replaced_in_place(dtype, metric, tables):
     fresh.close()
 
 
+@pytest.mark.parametrize("dtype,metric", [("f16", "ip"), ("bf16", "l2"), ("f32", "ip")])
+def test_partial_residency_hot_lists_resident_then_one_swapped_in(dtype, metric):
+    """Section 4.4: only the gc most frequently probed lists are kept in place.  A first batch fills the access
+    counters; the gc hottest lists (hr_ivf_hot_lists) are marked resident, all others not.  Then, for a second batch:
+    the split of its probe lists into lists served here and lists to be served elsewhere is the oracle's exactly;
+    the scan of the first part is the oracle's scan of those lists; a scan handed the whole probe lists drops the
+    others by itself (same bits); the dropped probes still count as accesses.  Finally one missing list is swapped
+    in (new vectors copied into its rows by the caller, hr_ivf_refresh_rows, flag set) and the search is compared
+    with the oracle on the new bytes."""
+    print(f"case residency {dtype} {metric}", flush=True)
+    hr = _hr()
+    cfg = synth.scaled(synth.CONFIGS["C3"], N=120000, nlist=96, nq=400, nprobe=12, k=10, dtype=dtype, metric=metric, d=128,
+                       normalize=metric == "ip")
+    idx = synth.make_index(cfg, "cuda")
+    q1 = synth.make_queries(cfg, idx)[0]
+    q2 = synth.make_queries(synth.scaled(cfg, seed=cfg.seed + 77), idx)[0]
+    host = Host(idx)
+    ix = hr.IvfIndex(idx.centroids, idx.list_offsets, idx.list_vectors, idx.list_ids)
+    m = METRIC[metric]
+    ix.search(q1, cfg.nprobe, cfg.k, metric)
+    gc = 30
+    hot = ix.hot_lists(gc)
+    assert np.array_equal(hot.cpu().numpy(), oracle.hot_lists(ix.list_hits(reset=True).cpu().numpy(), gc))
+    ix.set_resident(None, False)
+    ix.set_resident(hot, True)
+    resident = np.zeros(cfg.nlist, bool)
+    resident[hot.cpu().numpy()] = True
+    # the second batch
+    probe, _ = ix.coarse(q2, cfg.nprobe, metric)
+    res, mis = ix.split_probes(probe)
+    res_o, mis_o = oracle.split_probes(probe.cpu().numpy(), resident)
+    assert np.array_equal(res.cpu().numpy(), res_o) and np.array_equal(mis.cpu().numpy(), mis_o)
+    assert (mis_o >= 0).any() and (res_o >= 0).any()
+    ids_r, sc_r = ix.scan(q2, res, cfg.k, metric)
+    qn = synth.to_numpy(q2)
+    score_of = lambda i, ids: oracle.pair_scores(qn, host.vec, dtype, m, np.full(len(ids), i), host.rows_of(ids))
+    scale = _scale(qn, host.xnorm(), metric)
+    ids_o, sc_o = oracle.scan(qn, host.off, host.vec, dtype, host.ids, res_o, cfg.k, m)
+    st = check_topk(ids_r.cpu().numpy(), sc_r.cpu().numpy(), ids_o, sc_o, score_of, metric, TAU[dtype], scale)
+    print(f"[parity residency {dtype} {metric}] resident part: {st}; probes served here: {(res_o >= 0).mean():.2f}", flush=True)
+    ids_w, sc_w = ix.scan(q2, probe, cfg.k, metric)                # the whole probe lists: the others are dropped
+    assert torch.equal(ids_w, ids_r) and torch.equal(sc_w, sc_r)
+    # accesses: missing ones counted by the split and again by the scan that dropped them, resident ones by both scans
+    want = 2 * np.bincount(probe.cpu().numpy().ravel(), minlength=cfg.nlist)
+    assert np.array_equal(ix.list_hits(reset=True).cpu().numpy(), want)
+    # swap one missing list in: other vectors into its rows, norms and tables derived again, flag set
+    lst = int(mis_o[mis_o >= 0][0])
+    r0, r1 = int(host.off[lst]), int(host.off[lst + 1])
+    new = idx.centroids[lst][None, :] + 0.02 * torch.randn(r1 - r0, cfg.d, generator=torch.Generator().manual_seed(3)).cuda()
+    idx.list_vectors[r0:r1] = new.to(idx.list_vectors.dtype)
+    ix.refresh_rows(r0, r1)
+    ix.set_resident(torch.tensor([lst], dtype=torch.int32, device="cuda"), True)
+    resident[lst] = True
+    host = Host(idx)                                               # (the new bytes)
+    res2, mis2 = ix.split_probes(probe)
+    res2_o, mis2_o = oracle.split_probes(probe.cpu().numpy(), resident)
+    assert np.array_equal(res2.cpu().numpy(), res2_o) and np.array_equal(mis2.cpu().numpy(), mis2_o)
+    ids_2, sc_2 = ix.scan(q2, res2, cfg.k, metric)
+    score_of = lambda i, ids: oracle.pair_scores(qn, host.vec, dtype, m, np.full(len(ids), i), host.rows_of(ids))
+    ids_o2, sc_o2 = oracle.scan(qn, host.off, host.vec, dtype, host.ids, res2_o, cfg.k, m)
+    st2 = check_topk(ids_2.cpu().numpy(), sc_2.cpu().numpy(), ids_o2, sc_o2, score_of, metric, TAU[dtype], _scale(qn, host.xnorm(), metric))
+    got_new = np.isin(ids_o2, host.ids[r0:r1]).any(1).mean()
+    print(f"[parity residency {dtype} {metric}] after the swap: {st2}; queries with a result from the new rows: {got_new:.2f}", flush=True)
+    assert got_new > 0
+    # everything resident again: the plain search
+    ix.set_resident(None, True)
+    compare_ids, _ = ix.search(q2, cfg.nprobe, cfg.k, metric)
+    _, ids_all, _ = oracle.ivf_search(qn, host.cent, host.off, host.vec, dtype, host.ids, cfg.nprobe, cfg.k, m)
+    assert (compare_ids.cpu().numpy() == ids_all).all(1).mean() > 0.8
+    ix.close()
+
+
 def test_negative_labels_are_refused_at_load():
     """A negative id marks an empty place in results, so a label may not be negative."""
     hr = _hr()

@@ -395,3 +395,25 @@ def test_hot_lists_worked_example():
     assert oracle.hot_lists(hits, 7).tolist() == [2, 5, 0, 3, 6, 1, 4]
     assert oracle.hot_lists(hits, 3).tolist() == [2, 5, 0]
 
+
+
+def test_split_probes_worked_example_and_invariants():
+    """Partial residency (Section 4.4): a probe row split by hand (lists 3, 8 and 20 resident of 0..24: the row
+    8 5 20 -1 3 30 11 gives 8 20 3 here and 5 11 elsewhere; 30 is no list at all), and on random inputs: the two parts
+    are disjoint, together they are the valid entries of the row, each keeps the given order, the first holds
+    exactly the resident ones (numpy set operations, not the oracle's own loops)."""
+    resident = np.zeros(25, bool)
+    resident[[3, 8, 20]] = True
+    res, mis = oracle.split_probes(np.array([[8, 5, 20, -1, 3, 30, 11]], np.int32), resident)
+    assert res[0].tolist() == [8, 20, 3, -1, -1, -1, -1] and mis[0].tolist() == [5, 11, -1, -1, -1, -1, -1]
+    rng = np.random.default_rng(4)
+    nlist = 60
+    resident = rng.random(nlist) < 0.4
+    probe = np.stack([rng.permutation(nlist + 6)[:25] - 3 for _ in range(40)]).astype(np.int32)    # some outside 0..nlist-1
+    res, mis = oracle.split_probes(probe, resident)
+    for i in range(probe.shape[0]):
+        valid = probe[i][(probe[i] >= 0) & (probe[i] < nlist)]
+        r, m = res[i][res[i] >= 0], mis[i][mis[i] >= 0]
+        assert len(r) + len(m) == len(valid) and not np.intersect1d(r, m).size
+        assert np.array_equal(r, valid[resident[valid]]) and np.array_equal(m, valid[~resident[valid]])
+        assert (res[i][len(r):] == -1).all() and (mis[i][len(m):] == -1).all()
