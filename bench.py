@@ -38,13 +38,45 @@ def operand_name(cfg, ix):
     if cfg.dtype == "bf16":
         return "f16" if ix.row_tables else "bf16"   # binary16 row table asked for at load, else bfloat16 rows x (hi, lo) query
     return "f16"
-# HBM bytes per list-scan launch (read + written) from the rocprofv3 FETCH_SIZE / WRITE_SIZE counter runs
-# summarised under profiles/ (counters cannot be read from inside this process); other workloads: null
-MEASURED_TRAFFIC = {"C3": 8.94e9 + 0.04e9}
+def traffic_from_profiles(cfg, row_tables):
+    """HBM bytes per list-scan launch (read + written) as the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised under
+    profiles/ measured them for this workload (counters cannot be read from inside this process): the number after
+    `hbm_bytes_per_scan_launch:` in profiles/k_scan_<storage>_<workload>[_row_tables].txt, or None when there is no
+    such summary (other batch sizes than the workload's own are not looked up at all)."""
+    name = f"k_scan_{cfg.dtype}_{cfg.name}{'_row_tables' if row_tables and cfg.dtype != 'f16' else ''}.txt"
+    path = os.path.join(ROOT, "profiles", name)
+    if not os.path.exists(path):
+        return None, None
+    for line in open(path):
+        if line.strip().startswith("hbm_bytes_per_scan_launch:"):
+            return float(line.split(":", 1)[1].split()[0]), "profiles/" + name
+    return None, None
 
 
-def cpu_baseline(cfg, idx, q, target_s=30.0):
-    """The oracle as it stands, on the host cores, on a sample sized for about target_s seconds."""
+def cpu_info():
+    model, phys = "unknown", set()
+    try:
+        pid = cid = None
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name") and model == "unknown":
+                model = line.split(":", 1)[1].strip()
+            elif line.startswith("physical id"):
+                pid = line.split(":", 1)[1].strip()
+            elif line.startswith("core id"):
+                cid = line.split(":", 1)[1].strip()
+            elif not line.strip():
+                if pid is not None and cid is not None:
+                    phys.add((pid, cid))
+                pid = cid = None
+    except OSError:
+        pass
+    return model, len(phys) or None, os.cpu_count()
+
+
+def cpu_baseline(cfg, idx, q, gpu_ids, gpu_scores, target_s=20.0):
+    """The oracle as it stands, on the host cores, on a sample of the batch sized for about target_s seconds; next to
+    it the same on one thread (a smaller sample), how the timed GPU result compares with the oracle's on that sample,
+    and the recall of the search against the oracle's exhaustive search on a few queries."""
     import numpy as np
     import oracle
     import synth
@@ -66,13 +98,42 @@ def cpu_baseline(cfg, idx, q, target_s=30.0):
     if n1 > 0:
         sel = order[n0:n0 + n1]
         t0 = time.time()
-        oracle.ivf_search(np.ascontiguousarray(qh[sel]), cent, off, vec, cfg.dtype, ids, cfg.nprobe, cfg.k, m)
+        _, ids_o, sc_o = oracle.ivf_search(np.ascontiguousarray(qh[sel]), cent, off, vec, cfg.dtype, ids, cfg.nprobe, cfg.k, m)
         total_t, total_n = time.time() - t0, n1
     else:
+        sel = order[:n0]
+        _, ids_o, sc_o = oracle.ivf_search(np.ascontiguousarray(qh[sel]), cent, off, vec, cfg.dtype, ids, cfg.nprobe, cfg.k, m)
         total_t, total_n = t_pilot, n0
-    return {"value": total_n / total_t, "unit": "queries/s", "cores": threads, "kind": "oracle",
+    rate = total_n / total_t
+    # one thread: about 5 s worth of the same queries
+    n_one = int(max(1, min(len(sel), 5.0 * rate / max(threads, 1))))
+    oracle.set_threads(1)
+    t0 = time.time()
+    oracle.ivf_search(np.ascontiguousarray(qh[sel[:n_one]]), cent, off, vec, cfg.dtype, ids, cfg.nprobe, cfg.k, m)
+    t_one = time.time() - t0
+    oracle.set_threads(threads)
+    # the GPU's result for the sampled queries against the oracle's (whole search, the oracle's own probe lists)
+    g_i, g_s = gpu_ids[sel], gpu_scores[sel].astype(np.float64)
+    finite = np.isfinite(sc_o) & (np.abs(sc_o) > 0)
+    rel = np.abs(g_s - sc_o)[finite] / np.abs(sc_o[finite])
+    overlap = float(np.mean([np.isin(g_i[i], ids_o[i]).mean() for i in range(len(sel))]))
+    # recall of the approximate search (both sides) against the exhaustive search, on a few queries
+    nb = int(min(16, len(sel)))
+    t0 = time.time()
+    ids_b, _ = oracle.bruteforce(np.ascontiguousarray(qh[sel[:nb]]), vec, cfg.dtype, ids, cfg.k, m)
+    t_b = time.time() - t0
+    rec_gpu = float(np.mean([np.isin(ids_b[i], g_i[i]).mean() for i in range(nb)]))
+    rec_or = float(np.mean([np.isin(ids_b[i], ids_o[i]).mean() for i in range(nb)]))
+    model, phys, logical = cpu_info()
+    return {"value": rate, "unit": "queries/s", "cores": threads, "kind": "oracle",
             "sample": f"{total_n} randomly chosen queries of the batch (full index, nprobe={cfg.nprobe}, "
-                      f"k={cfg.k}), {total_t:.1f} s after a {n0}-query pilot"}
+                      f"k={cfg.k}), {total_t:.1f} s after a {n0}-query pilot",
+            "cpu_model": model, "physical_cores": phys, "logical_cpus": logical,
+            "one_thread": {"value": n_one / t_one, "unit": "queries/s", "sample": f"the first {n_one} of those queries, {t_one:.1f} s"},
+            "gpu_vs_oracle_on_sample": {"queries": int(len(sel)), "rows_with_identical_ids": float((g_i == ids_o).all(1).mean()),
+                                        "id_set_overlap": overlap, "max_rel_score_err": float(rel.max()) if rel.size else 0.0},
+            "recall_at_k_vs_exhaustive": {"queries": nb, "k": cfg.k, "gpu": rec_gpu, "oracle": rec_or,
+                                          "exhaustive_search_s": round(t_b, 1)}}
 
 
 def bench_width_split(args, cfg, hr, ix, idx, rounds, metric):
@@ -266,6 +327,9 @@ def main():
                          "time against the HBM peak; prints its own JSON line")
     ap.add_argument("--row-tables", action="store_true",
                     help="load float32 / bfloat16 lists with HR_LOAD_ROW_TABLES (binary16 row tables: as many bytes again)")
+    ap.add_argument("--flush-mb", type=int, default=0,
+                    help="write this many MB of scratch between the timed calls (512 evicts the last-level cache, for batches "
+                         "small enough to stay in it); each call is then timed by its own pair of events")
     ap.add_argument("--noise", type=float, default=0.0, help="spread of vectors and queries around their centroid instead of the workload's own")
     ap.add_argument("--drift", type=float, default=0.0, help="step of a query from round to round instead of the workload's own")
     args = ap.parse_args()
@@ -326,11 +390,22 @@ def main():
         step(i)
     torch.cuda.synchronize()
     hr.hr_ivf_profile_begin(ix.handle, args.steps)
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
+    if args.flush_mb > 0:
+        scratch = torch.empty(args.flush_mb << 20, dtype=torch.uint8, device="cuda")
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+        for i in range(args.steps):
+            scratch.fill_(i & 255)
+            evs[i][0].record()
+            step(i)
+            evs[i][1].record()
+        torch.cuda.synchronize()
+        dt = sum(a.elapsed_time(b) for a, b in evs) * 1e-3
+    else:
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            step(i)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
     n_timed, scan_ms = hr.hr_ivf_profile_end(ix.handle)
     if args.graph:
         # (the library records its events when it enqueues the kernel; a replayed graph enqueues
@@ -354,6 +429,8 @@ def main():
     scan_flops = 2.0 * cfg.d * pair_rows
     achieved = scan_bytes / (scan_ms * 1e-3) / 1e9 if scan_ms > 0 else 0.0
 
+    own_shape = args.nq == 0 and args.nprobe == 0 and args.noise == 0 and args.drift == 0
+    traffic, traffic_src = traffic_from_profiles(cfg, args.row_tables) if own_shape else (None, None)
     out = {
         "metric": "queries/sec batched IVF top-k search", "value": nq / (ms_per_step * 1e-3),
         "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -362,18 +439,20 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}: N={cfg.N}, d={cfg.d}, nlist={cfg.nlist}, nq={nq}, "
                                f"nprobe={cfg.nprobe}, k={cfg.k}, {cfg.dtype} storage, {cfg.metric}",
-                   "row_tables": bool(args.row_tables and cfg.dtype != "f16"), "rounds": cfg.rounds, "launch": "hip graph replay" if args.graph else "eager", "scan_items": st["items"], "seg_rows": st["seg_rows"],
+                   "row_tables": bool(args.row_tables and cfg.dtype != "f16"), "rounds": cfg.rounds, "launch": "hip graph replay" if args.graph else "eager", "cache_flushed_between_calls_mb": args.flush_mb, "scan_items": st["items"], "seg_rows": st["seg_rows"],
                    "pairs": st["pairs"]},
         "roofline": {"bound": "hbm", "kernel": "k_scan (list scan)", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": MEASURED_TRAFFIC.get(cfg.name), "scan_ms_avg": scan_ms, "launches_timed": n_timed,
+                     "traffic": traffic, "traffic_source": traffic_src, "scan_ms_avg": scan_ms, "launches_timed": n_timed,
                      "algorithmic_bytes_per_launch": scan_bytes,
                      "mfma_tflops": scan_flops / (scan_ms * 1e-3) / 1e12 if scan_ms > 0 else 0.0,
                      "mfma_frac": (scan_flops / (scan_ms * 1e-3) / 1e12 / mfma_peak(cfg, ix)) if scan_ms > 0 else 0.0,
                      "mfma_peak_tflops": mfma_peak(cfg, ix)},
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, idx, rounds[0])
+        # (the result of the last timed step, for the comparison with the oracle on the sampled queries)
+        last = (args.steps - 1) % len(rounds)
+        out["cpu_baseline"] = cpu_baseline(cfg, idx, rounds[last], ids.cpu().numpy(), scores.cpu().numpy())
     ix.close()
     print(json.dumps(out))
 

@@ -43,6 +43,7 @@ def _load():
         c = ctypes
         p = c.c_void_p
         lib.oracle_num_threads.restype = c.c_int
+        lib.oracle_set_threads.argtypes = [c.c_int]
         lib.oracle_coarse.argtypes = [p, c.c_int64, p, c.c_int64, c.c_int, c.c_int, c.c_int, p, p]
         lib.oracle_scan.argtypes = [p, c.c_int64, c.c_int, p, c.c_int64, p, c.c_int, p, p,
                                     c.c_int, c.c_int, c.c_int, p, p]
@@ -57,6 +58,11 @@ def _load():
 
 def num_threads():
     return int(_load().oracle_num_threads())
+
+
+def set_threads(n):
+    """Threads the query loops use from now on (timing on one core); results do not depend on it."""
+    _load().oracle_set_threads(int(n))
 
 
 def _ptr(a):

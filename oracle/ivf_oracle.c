@@ -129,6 +129,16 @@ static void topk_emit(const topk_t *t, int64_t *out_ids, double *out_scores)
     }
 }
 
+/* number of threads the query loops use from now on (for timing the oracle on one core); no arithmetic changes */
+void oracle_set_threads(int n)
+{
+#ifdef _OPENMP
+    if (n > 0) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
 int oracle_num_threads(void)
 {
 #ifdef _OPENMP

@@ -86,7 +86,7 @@ size_t scan_lds_bytes(int dtype, int d, int cap, int shape, int nbuf)
         buf = (size_t)((chunks + threads - 1) / threads) * threads * 16;
     }
     const size_t cw = (size_t)cols_per_set(dtype) * shape_sets(shape);
-    return nbuf * buf + cw * cap * sizeof(Cand) + (size_t)nbuf * kBlockRows * sizeof(float) + 16;
+    return nbuf * buf + cw * cap * sizeof(Cand) + (size_t)nbuf * kBlockRows * sizeof(float) + 32;
 }
 }  // namespace hr
 
@@ -197,7 +197,7 @@ struct Plan {
     size_t o_thr;                   // 2*nq ints set to "-inf"
     size_t o_qop_c, o_qnorm_c, o_qop_s, o_qnorm_s;
     size_t o_probe;
-    size_t o_pair_entry, o_bucket_off, o_bucket_q, o_item_base, o_slot_base, o_item_tab, o_xq;
+    size_t o_pair_entry, o_bucket_off, o_bucket_q, o_item_base, o_slot_base, o_xq;
     size_t o_ckeys;                 // coarse step: [cchunk, nlist] keys of one chunk of queries
     int64_t cchunk;                 // queries per coarse chunk
     size_t o_slot_cnt, o_slot_ent;
@@ -263,8 +263,7 @@ static Plan make_plan(const hr_ivf_index* ix, int64_t nq, int nprobe, int k, con
     p.o_bucket_q = take((size_t)pairs * 4);
     p.o_item_base = take((size_t)(nlist + 1) * 4);
     p.o_slot_base = take((size_t)(nlist + 1) * 4);
-    p.o_item_tab = take((size_t)p.item_cap * sizeof(int4));
-    p.o_xq = take((size_t)p.item_cap * 8 * 4);
+    p.o_xq = take((size_t)p.item_cap * 8 * 2 * sizeof(int4));
     p.o_ckeys = take((size_t)p.cchunk * nlist * 4);
     const size_t slots = (size_t)p.slot_cap;
     p.o_slot_cnt = take(slots * 4);
@@ -573,9 +572,8 @@ static int enqueue_scan(const hr_ivf_index* ix, const Plan& p, char* ws, int64_t
     b.slot_base = (int*)(ws + p.o_slot_base);
     b.slot_cap = p.slot_cap;
     b.item_target = p.item_target;
-    b.item_tab = (int4*)(ws + p.o_item_tab);
     b.dyn = zero + ix->nlist;
-    b.xq = (int*)(ws + p.o_xq);
+    b.xq_rec = (int4*)(ws + p.o_xq);
     b.xq_count = zero + ix->nlist + DYN_COUNT + 8;
     b.round_cnt = zero + p.zoff_round;
     b.round_cur = zero + p.zoff_round + 8 * 64;
@@ -611,9 +609,8 @@ static int enqueue_scan(const hr_ivf_index* ix, const Plan& p, char* ws, int64_t
     a.list_off = ix->d_list_off;
     a.bucket_off = b.bucket_off;
     a.bucket_q = b.bucket_q;
-    a.item_tab = b.item_tab;
     a.dyn = b.dyn;
-    a.xq = b.xq;
+    a.xq_rec = b.xq_rec;
     a.xq_count = b.xq_count;
     a.xq_head = zero + ix->nlist + DYN_COUNT + 16;
     a.xq_stride = p.item_cap;

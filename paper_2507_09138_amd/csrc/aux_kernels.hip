@@ -484,9 +484,12 @@ __global__ __launch_bounds__(256) void k_item_expand(BucketArgs a)
     long long base = a.item_base[l];
     const long long sbase = a.slot_base[l];
     const int R = a.dyn[DYN_ROUNDS];
+    const int row_first = a.list_off[l], boff = a.bucket_off[l];
     for (int s = lane; s < nseg; s += 64) {
         const int x = queue_of(l, s), slot = x * kRounds + round_of(l, s, nseg, R);
         const int pos = a.round_cnt[slot] + atomicAdd(&a.round_cur[slot], nqt);
+        const int row0 = row_first + s * seg;
+        const int nrows = min(len - s * seg, seg);
         for (int t = 0; t < nqt; t++) {
             long long idx = base + (long long)s * nqt + t;
             // first result slot of the item: entries t*cw .. of segment s (the last tile of a bucket has fewer
@@ -494,8 +497,9 @@ __global__ __launch_bounds__(256) void k_item_expand(BucketArgs a)
             const long long first = sbase + (long long)s * w + (long long)t * a.cw;
             // (the guards cannot fail: the host sizes the tables from the same bounds)
             if (idx < a.item_cap && pos + t < a.item_cap && first + min(a.cw, w - t * a.cw) <= a.slot_cap) {
-                a.item_tab[idx] = make_int4(l, s, t, (int)first);
-                a.xq[(size_t)x * a.item_cap + pos + t] = (int)idx;
+                int4* rec = a.xq_rec + ((size_t)x * a.item_cap + pos + t) * 2;
+                rec[0] = make_int4(row0, nrows, boff, w);
+                rec[1] = make_int4(t, (int)first, l, s);
             }
         }
     }

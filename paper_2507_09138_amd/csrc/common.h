@@ -94,9 +94,10 @@ struct ScanArgs {
     const int* list_off;        // [nlist+1] row offsets
     const int* bucket_off;      // [nlist+1]
     const int* bucket_q;        // [pairs] query index per bucket entry
-    const int4* item_tab;       // [items] (list, segment, query tile, first result slot of the item)
     const int* dyn;             // device scalars: [0] = items, [1] = rows per segment
-    const int* xq;              // [8][xq_stride] item numbers queued per XCD
+    const int4* xq_rec;         // [8][xq_stride][2] the items queued per XCD, each a record of two int4:
+                                // (first row, rows, first entry of the list's bucket, width of the bucket),
+                                // (query tile, first result slot of the item, list, segment)
     const int* xq_count;        // [8] queue lengths
     int* xq_head;               // [8] next position to pop (zeroed before launch)
     int xq_stride;
@@ -183,9 +184,8 @@ struct BucketArgs {
     int* bucket_q;              // [nq*nprobe]
     int* item_base;             // [nlist+1]
     int* slot_base;             // [nlist+1] first result slot of every list
-    int4* item_tab;             // [item_cap]
     int* dyn;                   // device scalars
-    int* xq;                    // [8][item_cap] per-XCD queues of item numbers
+    int4* xq_rec;               // [8][item_cap][2] per-XCD queues of item records (see ScanArgs)
     int* xq_count;              // [8] queue lengths
     int* round_cnt;             // [8][64] items per queue and round, then where each round starts (zeroed before launch)
     int* round_cur;             // [8][64] items placed so far per queue and round (zeroed before launch)

@@ -399,7 +399,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
     const int part = (NC == 8) ? ((lane >> 3) & 1) : 0;   // 0 = hi, 1 = lo operand column
     const bool owner = (NC == 16) || part == 0;    // lane whose accumulator holds the full dot
     Cand* mysel = sel + (wave * WC) * a.cap;
-    const int seg_rows = a.dense ? a.dense_seg_rows : a.dyn[DYN_SEG_ROWS];
+    const int seg_rows = a.dense_seg_rows;                   // (dense mode only: the items of the lists carry their rows)
     const int myx = blockIdx.x & 7;                // workgroups are dealt round-robin to the 8 XCDs
     int drained = 0;                               // thread 0: queues found empty
 
@@ -436,39 +436,44 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
                 if (i < a.dense_items) item = i;
             } else {
                 // own XCD's queue first (its items share list segments through this XCD's L2),
-                // then the others' leftovers
+                // then the others' leftovers.  A queue entry is the whole record of the item.
                 for (int t = 0; t < 8 && item < 0; t++) {
                     int x = (myx + t) & 7;
                     if (drained & (1 << x)) continue;
                     int pos = atomicAdd(&a.xq_head[x], 1);
-                    if (pos < a.xq_count[x]) item = a.xq[(size_t)x * a.xq_stride + pos];
-                    else drained |= 1 << x;
+                    if (pos < a.xq_count[x]) {
+                        const int4* rec = a.xq_rec + ((size_t)x * a.xq_stride + pos) * 2;
+                        const int4 r0 = rec[0], r1 = rec[1];
+                        s_item[1] = r0.x; s_item[2] = r0.y; s_item[3] = r0.z; s_item[4] = r0.w;
+                        s_item[5] = r1.x; s_item[6] = r1.y;
+                        item = 0;
+                    } else {
+                        drained |= 1 << x;
+                    }
                 }
             }
-            *s_item = item;
+            s_item[0] = item;
         }
         __syncthreads();
-        const int item = __builtin_amdgcn_readfirstlane(*s_item);
+        const int item = __builtin_amdgcn_readfirstlane(s_item[0]);
         if (item < 0) break;
 
         // ---- decode the work item
-        int list, seg, qt, row0, row_end, w, boff, slot0 = 0;
+        int qt, row0, row_end, w, boff, slot0 = 0;
         if (a.dense) {
-            seg = item / a.dense_nqt;
+            const int seg = item / a.dense_nqt;
             qt = item - seg * a.dense_nqt;
-            list = 0;
             row0 = seg * seg_rows;
             row_end = min(a.dense_nrows, row0 + seg_rows);
             w = a.nq;
             boff = 0;
         } else {
-            int4 it = a.item_tab[item];
-            list = it.x; seg = it.y; qt = it.z; slot0 = it.w;
-            int l0 = a.list_off[list], l1 = a.list_off[list + 1];
-            row0 = l0 + seg * seg_rows;
-            row_end = min(l1, row0 + seg_rows);
-            boff = a.bucket_off[list];
-            w = a.bucket_off[list + 1] - boff;
+            row0 = __builtin_amdgcn_readfirstlane(s_item[1]);
+            row_end = row0 + __builtin_amdgcn_readfirstlane(s_item[2]);
+            boff = __builtin_amdgcn_readfirstlane(s_item[3]);
+            w = __builtin_amdgcn_readfirstlane(s_item[4]);
+            qt = __builtin_amdgcn_readfirstlane(s_item[5]);
+            slot0 = __builtin_amdgcn_readfirstlane(s_item[6]);
         }
         const int nrows = row_end - row0;
         const int nblk = (nrows + kBlockRows - 1) / kBlockRows;
@@ -868,28 +873,42 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
                 }
                 int added = 0;
                 if (GS) {
-                    // one column at a time, its entries spread over the lanes
-#pragma unroll 1
-                    for (int cl = 0; cl < WC; cl++) {
-                        const float cwd = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wd), cl));
-                        const int cn = __builtin_amdgcn_readlane(have ? n : 0, cl);
-                        if (cn == 0 || !(cwd > 0.f)) continue;
-                        const float cbase = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, base), cl));
-                        const uint32_t cnow = __builtin_amdgcn_readlane(now, cl);
-                        const int qc = __builtin_amdgcn_readlane(qcol, cl);
-                        const float inv = 1.0f / cwd;
+                    // the entries of all columns of this wave side by side over the lanes (entry e of the
+                    // wave = entry e - start[c] of column c): one load and one addition per entry, all
+                    // of a pass in flight together
+                    const int cnt = (have && wd > 0.f) ? n : 0;
+                    const int incl = wave_prefix_sum(cnt);
+                    const int total = __builtin_amdgcn_readlane(incl, 63);
+                    unsigned long long gained = 0;                   // columns whose histogram got an addition
+                    for (int e0 = 0; e0 < total; e0 += 64) {
+                        const int e = e0 + lane;
+                        const bool live = e < total;
+                        int c = 0;                                   // column of entry e: columns that end at or before e
+#pragma unroll
+                        for (int cl = 0; cl < WC; cl++) c += (__builtin_amdgcn_readlane(incl, cl) <= e) ? 1 : 0;
+                        c = live ? c : 0;
+                        const int start = __shfl(incl - cnt, c);
+                        const float cbase = __shfl(base, c), cwd = __shfl(wd, c);
+                        const uint32_t cnow = (uint32_t)__shfl((int)now, c);
+                        const int qc = __shfl(qcol, c);
                         bool did = false;
-                        for (int i = lane; i < cn; i += 64) {
-                            const uint32_t ek = gsel[cl * a.cap + i].key;
-                            if (ek < cnow) continue;
-                            const float key = dec_key(ek);
-                            int b = (int)fminf(fmaxf((key - cbase) * inv, 0.f), (float)(kHistBins - 1));
-                            if (hist_edge(cbase, cwd, b) > key) b--;
-                            else if (b < kHistBins - 1 && hist_edge(cbase, cwd, b + 1) <= key) b++;
-                            if (b >= 0) did |= atomicAdd(&a.hist[(size_t)qc * kHistBins + b], 1) >= 0;
+                        if (live) {
+                            const uint32_t ek = gsel[c * a.cap + (e - start)].key;
+                            if (ek >= cnow) {
+                                const float key = dec_key(ek);
+                                int b = (int)fminf(fmaxf((key - cbase) * (1.0f / cwd), 0.f), (float)(kHistBins - 1));
+                                if (hist_edge(cbase, cwd, b) > key) b--;
+                                else if (b < kHistBins - 1 && hist_edge(cbase, cwd, b + 1) <= key) b++;
+                                // (the returned value is used so that the additions have been performed
+                                // before the counts are read back below)
+                                if (b >= 0) did = atomicAdd(&a.hist[(size_t)qc * kHistBins + b], 1) >= 0;
+                            }
                         }
-                        if (__builtin_amdgcn_ballot_w64(did) != 0 && lane == cl) added = 1;
+#pragma unroll
+                        for (int cl = 0; cl < WC; cl++)
+                            if (__builtin_amdgcn_ballot_w64(did && c == cl) != 0) gained |= 1ull << cl;
                     }
+                    if (lane < WC && ((gained >> lane) & 1)) added = 1;
                 } else if (have && wd > 0.f) {
                     const Cand* cb = mysel + lane * a.cap;
                     const float inv = 1.0f / wd;
