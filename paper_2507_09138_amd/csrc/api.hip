@@ -504,10 +504,17 @@ static int scan_grid(const hr_ivf_index* ix, size_t lds, int shape)
     return ix->num_cus * occ;
 }
 
-static int enqueue_clear(const Plan& p, char* ws, int64_t nq, hipStream_t s)
+// query operands for the coarse step (coarse) and / or the list scan (scan), and, in the same launch, what the
+// call needs cleared in its workspace
+static int enqueue_prep(const hr_ivf_index* ix, const Plan& p, char* ws, const float* queries, int64_t nq, bool coarse,
+                        bool scan, hipStream_t s)
 {
-    HR_HIP(launch_fill_i32((int*)(ws + p.o_zero), (int64_t)p.n_zero, 0, s));
-    HR_HIP(launch_fill_i32((int*)(ws + p.o_thr), nq * 2, (int)kKeyNegInf, s));
+    const int od = operand_dtype(ix);
+    const bool f32 = od == HR_F32;             // the scan multiplies the operand of the coarse step
+    HR_HIP(launch_prep_queries(queries, nq, ix->d, scan ? od : (int)HR_F32, (coarse || (scan && f32)) ? ws + p.o_qop_c : nullptr,
+                               coarse ? (float*)(ws + p.o_qnorm_c) : nullptr, (scan && !f32) ? ws + p.o_qop_s : nullptr,
+                               scan ? (float*)(ws + p.o_qnorm_s) : nullptr, (int*)(ws + p.o_zero), (int64_t)p.n_zero,
+                               (int*)(ws + p.o_thr), nq * 2, (int)kKeyNegInf, s));
     return HR_OK;
 }
 
@@ -657,9 +664,7 @@ int hr_ivf_search(const hr_ivf_index* ix, const float* queries, int64_t nq, int3
     if (int rc = check_ws(p, workspace, workspace_bytes)) return rc;
     char* ws = (char*)workspace;
     hipStream_t s = (hipStream_t)stream;
-    if (int rc = enqueue_clear(p, ws, nq, s)) return rc;
-    HR_HIP(launch_prep_queries(queries, nq, ix->d, operand_dtype(ix), ws + p.o_qop_c, (float*)(ws + p.o_qnorm_c),
-                               operand_dtype(ix) == HR_F32 ? nullptr : ws + p.o_qop_s, (float*)(ws + p.o_qnorm_s), s));
+    if (int rc = enqueue_prep(ix, p, ws, queries, nq, true, true, s)) return rc;
     int32_t* probe = (int32_t*)(ws + p.o_probe);
     if (int rc = enqueue_coarse(ix, p, ws, nq, nprobe, metric, probe, nullptr, s)) return rc;
     return enqueue_scan(ix, p, ws, nq, probe, nprobe, k, metric, out_ids, out_scores, s);
@@ -685,9 +690,7 @@ int hr_ivf_search_static(const hr_ivf_index* ix, const float* queries, int64_t n
                                       "use hr_ivf_search with a workspace", (long long)nq, nprobe, k, p.total, (size_t)HR_STATIC_SCRATCH_BYTES);
     char* ws = (char*)ix->scratch;
     hipStream_t s = (hipStream_t)stream;
-    if (int rc = enqueue_clear(p, ws, nq, s)) return rc;
-    HR_HIP(launch_prep_queries(queries, nq, ix->d, operand_dtype(ix), ws + p.o_qop_c, (float*)(ws + p.o_qnorm_c),
-                               operand_dtype(ix) == HR_F32 ? nullptr : ws + p.o_qop_s, (float*)(ws + p.o_qnorm_s), s));
+    if (int rc = enqueue_prep(ix, p, ws, queries, nq, true, true, s)) return rc;
     int32_t* probe = (int32_t*)(ws + p.o_probe);
     if (int rc = enqueue_coarse(ix, p, ws, nq, nprobe, metric, probe, nullptr, s)) return rc;
     return enqueue_scan(ix, p, ws, nq, probe, nprobe, k, metric, out_ids, out_scores, s);
@@ -705,9 +708,7 @@ int hr_ivf_coarse(const hr_ivf_index* ix, const float* queries, int64_t nq, int3
     if (int rc = check_ws(p, workspace, workspace_bytes)) return rc;
     char* ws = (char*)workspace;
     hipStream_t s = (hipStream_t)stream;
-    if (int rc = enqueue_clear(p, ws, nq, s)) return rc;
-    HR_HIP(launch_prep_queries(queries, nq, ix->d, HR_F32, ws + p.o_qop_c, (float*)(ws + p.o_qnorm_c),
-                               nullptr, nullptr, s));
+    if (int rc = enqueue_prep(ix, p, ws, queries, nq, true, false, s)) return rc;
     return enqueue_coarse(ix, p, ws, nq, nprobe, metric, out_probe_ids, out_probe_scores, s);
 }
 
@@ -725,10 +726,7 @@ int hr_ivf_scan(const hr_ivf_index* ix, const float* queries, int64_t nq, const 
     if (int rc = check_ws(p, workspace, workspace_bytes)) return rc;
     char* ws = (char*)workspace;
     hipStream_t s = (hipStream_t)stream;
-    if (int rc = enqueue_clear(p, ws, nq, s)) return rc;
-    const bool f32 = operand_dtype(ix) == HR_F32;
-    HR_HIP(launch_prep_queries(queries, nq, ix->d, operand_dtype(ix), f32 ? ws + p.o_qop_c : nullptr, nullptr,
-                               f32 ? nullptr : ws + p.o_qop_s, (float*)(ws + p.o_qnorm_s), s));
+    if (int rc = enqueue_prep(ix, p, ws, queries, nq, false, true, s)) return rc;
     return enqueue_scan(ix, p, ws, nq, probe_ids, nprobe, k, metric, out_ids, out_scores, s);
 }
 
@@ -746,10 +744,7 @@ static int scan_step(const hr_ivf_index* ix, const float* queries, int64_t nq, c
     if (int rc = check_ws(p, workspace, workspace_bytes)) return rc;
     char* ws = (char*)workspace;
     hipStream_t s = (hipStream_t)stream;
-    if (int rc = enqueue_clear(p, ws, nq, s)) return rc;
-    const bool f32 = operand_dtype(ix) == HR_F32;
-    HR_HIP(launch_prep_queries(queries, nq, ix->d, operand_dtype(ix), f32 ? ws + p.o_qop_c : nullptr, nullptr,
-                               f32 ? nullptr : ws + p.o_qop_s, (float*)(ws + p.o_qnorm_s), s));
+    if (int rc = enqueue_prep(ix, p, ws, queries, nq, false, true, s)) return rc;
     return enqueue_scan(ix, p, ws, nq, probe_ids, nprobe, k, metric, io_ids, io_scores, s, true, io_rows);
 }
 

@@ -225,9 +225,14 @@ hipError_t launch_row_norms(const void* rows, int dtype, int64_t nrows, int d, f
 // lo row per query.  binary16 storage: the query rounded to binary16.  bfloat16 storage:
 // bfloat16 hi and lo rows.  The squared norms are those of the operand actually multiplied,
 // so that the expanded L2 form cancels consistently.  One wave per query.
+// The same launch clears what a call needs cleared in its workspace (counters, histograms: zero; the per-query
+// lower bounds: the key of -inf): one small launch less in front of every search.
 __global__ __launch_bounds__(256) void k_prep_queries(const float* q, int64_t nq, int d, int dtype,
-                                                      _Float16* qc, float* qnorm_c, void* qs, float* qnorm_s)
+                                                      _Float16* qc, float* qnorm_c, void* qs, float* qnorm_s,
+                                                      int* zero, int64_t n_zero, int* neg, int64_t n_neg, int neg_value)
 {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_zero; i += (int64_t)gridDim.x * blockDim.x) zero[i] = 0;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_neg; i += (int64_t)gridDim.x * blockDim.x) neg[i] = neg_value;
     int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= nq) return;
     int lane = threadIdx.x & 63;
@@ -265,11 +270,12 @@ __global__ __launch_bounds__(256) void k_prep_queries(const float* q, int64_t nq
 }
 
 hipError_t launch_prep_queries(const float* q, int64_t nq, int d, int dtype, void* qop_coarse,
-                               float* qnorm_coarse, void* qop_scan, float* qnorm_scan, hipStream_t s)
+                               float* qnorm_coarse, void* qop_scan, float* qnorm_scan,
+                               int* zero, int64_t n_zero, int* neg, int64_t n_neg, int neg_value, hipStream_t s)
 {
     if (nq <= 0) return hipSuccess;
     hipLaunchKernelGGL(k_prep_queries, dim3((unsigned)((nq + 3) / 4)), dim3(256), 0, s, q, nq, d, dtype,
-                       (_Float16*)qop_coarse, qnorm_coarse, qop_scan, qnorm_scan);
+                       (_Float16*)qop_coarse, qnorm_coarse, qop_scan, qnorm_scan, zero, n_zero, neg, n_neg, neg_value);
     return hipGetLastError();
 }
 
@@ -320,8 +326,33 @@ __device__ __forceinline__ long long block_sum_1024(long long v, long long* s_wa
     return t;
 }
 
-// One workgroup: bucket offsets, rows per segment for this batch, first work item of every
-// list.
+// Work items and their order of execution.  Items are numbered list-major (segment-major,
+// query tile minor inside a list).  The order of execution is given by eight queues, one per
+// XCD: all query tiles of one (list, segment) go to the same queue, next to each other, so the
+// workgroups that re-read that segment run on one XCD at about the same time and share it
+// through that XCD's L2.  Inside a queue the segments are ordered in rounds.  The longest list
+// has eight segments per round, in order: its segments are spread over the whole run, and the
+// later ones start from the lower bounds that the earlier ones have published.  The segments
+// of a shorter list are spread evenly over the same rounds from a start that depends on the
+// list (a list of one segment lands in a round of its own choosing).  So every stretch of a
+// queue holds the same mix of items that many queries share (long lists of popular clusters:
+// bound by the matrix pipes) and items of a few queries (bound by the row stream from HBM), and
+// the two kinds run side by side on the compute units of an XCD for the whole run; with all
+// short lists in the first round the device streams rows with idle matrix pipes first and
+// multiplies with an idle HBM afterwards.  (Within a round the order is that of arrival;
+// results do not depend on the order.)
+// (kRounds, the most rounds a queue has, is declared with the device scalars in common.h)
+
+// segment s of the nseg segments of list l: queue and round (R rounds in use)
+__device__ __forceinline__ int queue_of(int l, int s) { return (l + s) & 7; }
+__device__ __forceinline__ int round_of(int l, int s, int nseg, int R)
+{
+    const unsigned u = ((unsigned)l * 2654435761u) >> 16;            // start of the list inside its first stretch, in 65536ths
+    return (int)((((long long)s << 16) + u) * R / ((long long)nseg << 16));
+}
+
+// One workgroup: bucket offsets, rows per segment for this batch, first work item and first
+// result slot of every list, and where every round of every queue starts.
 __global__ __launch_bounds__(1024) void k_bucket_scan(BucketArgs a)
 {
     __shared__ int s_wave[17];
@@ -404,10 +435,10 @@ __global__ __launch_bounds__(1024) void k_bucket_scan(BucketArgs a)
         if (t == 0) {
             a.slot_base[a.nlist] = total;
             a.dyn[DYN_SLOTS] = total;
-            // rounds of the queues: the longest list has eight segments per round
-            a.dyn[DYN_ROUNDS] = max(1, min(kRounds, (s_maxseg + 7) / 8));
         }
     }
+    // rounds of the queues: the longest list has eight segments per round
+    if (t == 0) a.dyn[DYN_ROUNDS] = max(1, min(kRounds, (s_maxseg + 7) / 8));
 }
 
 __global__ void k_bucket_scatter(BucketArgs a)
@@ -420,31 +451,7 @@ __global__ void k_bucket_scatter(BucketArgs a)
     a.bucket_q[a.bucket_off[l] + e] = (int)(i / a.nprobe);
 }
 
-// Work items and their order of execution.  Items are numbered list-major (segment-major,
-// query tile minor inside a list).  The order of execution is given by eight queues, one per
-// XCD: all query tiles of one (list, segment) go to the same queue, next to each other, so the
-// workgroups that re-read that segment run on one XCD at about the same time and share it
-// through that XCD's L2.  Inside a queue the segments are ordered in rounds.  The longest list
-// has eight segments per round, in order: its segments are spread over the whole run, and the
-// later ones start from the lower bounds that the earlier ones have published.  The segments
-// of a shorter list are spread evenly over the same rounds from a start that depends on the
-// list (a list of one segment lands in a round of its own choosing).  So every stretch of a
-// queue holds the same mix of items that many queries share (long lists of popular clusters:
-// bound by the matrix pipes) and items of a few queries (bound by the row stream from HBM), and
-// the two kinds run side by side on the compute units of an XCD for the whole run; with all
-// short lists in the first round the device streams rows with idle matrix pipes first and
-// multiplies with an idle HBM afterwards.  (Within a round the order is that of arrival;
-// results do not depend on the order.)
-// (kRounds, the most rounds a queue has, is declared with the device scalars in common.h)
-
-// segment s of the nseg segments of list l: queue and round (R rounds in use)
-__device__ __forceinline__ int queue_of(int l, int s) { return (l + s) & 7; }
-__device__ __forceinline__ int round_of(int l, int s, int nseg, int R)
-{
-    const unsigned u = ((unsigned)l * 2654435761u) >> 16;            // start of the list inside its first stretch, in 65536ths
-    return (int)((((long long)s << 16) + u) * R / ((long long)nseg << 16));
-}
-
+// items per queue and round (one wave per list, its segments over the lanes)
 __global__ __launch_bounds__(256) void k_round_count(BucketArgs a)
 {
     int l = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -460,18 +467,19 @@ __global__ __launch_bounds__(256) void k_round_count(BucketArgs a)
     for (int s = lane; s < nseg; s += 64) atomicAdd(&a.round_cnt[queue_of(l, s) * kRounds + round_of(l, s, nseg, R)], nqt);
 }
 
-// 8 x kRounds counts -> where every round starts in its queue, and the queue lengths
-__global__ __launch_bounds__(64) void k_round_scan(BucketArgs a)
-{
-    const int x = threadIdx.x;
-    if (x >= 8) return;
-    int run = 0;
-    for (int r = 0; r < kRounds; r++) { int c = a.round_cnt[x * kRounds + r]; a.round_cnt[x * kRounds + r] = run; run += c; }
-    a.xq_count[x] = min(run, a.item_cap);
-}
-
+// (every workgroup turns the 8 x kRounds counts into where every round starts in its queue, for itself; the
+// first one also writes the queue lengths)
 __global__ __launch_bounds__(256) void k_item_expand(BucketArgs a)
 {
+    __shared__ int s_start[8 * kRounds];
+    for (int i = threadIdx.x; i < 8 * kRounds; i += 256) s_start[i] = a.round_cnt[i];
+    __syncthreads();
+    if (threadIdx.x < 8) {
+        int run = 0;
+        for (int r = 0; r < kRounds; r++) { const int c = s_start[threadIdx.x * kRounds + r]; s_start[threadIdx.x * kRounds + r] = run; run += c; }
+        if (blockIdx.x == 0) a.xq_count[threadIdx.x] = min(run, a.item_cap);
+    }
+    __syncthreads();
     int l = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (l >= a.nlist) return;
     int lane = threadIdx.x & 63;
@@ -487,7 +495,7 @@ __global__ __launch_bounds__(256) void k_item_expand(BucketArgs a)
     const int row_first = a.list_off[l], boff = a.bucket_off[l];
     for (int s = lane; s < nseg; s += 64) {
         const int x = queue_of(l, s), slot = x * kRounds + round_of(l, s, nseg, R);
-        const int pos = a.round_cnt[slot] + atomicAdd(&a.round_cur[slot], nqt);
+        const int pos = s_start[slot] + atomicAdd(&a.round_cur[slot], nqt);
         const int row0 = row_first + s * seg;
         const int nrows = min(len - s * seg, seg);
         for (int t = 0; t < nqt; t++) {
@@ -513,7 +521,6 @@ hipError_t launch_bucketing(const BucketArgs& a, hipStream_t s)
     hipLaunchKernelGGL(k_bucket_scan, dim3(1), dim3(1024), 0, s, a);
     hipLaunchKernelGGL(k_bucket_scatter, dim3(gp), dim3(256), 0, s, a);
     hipLaunchKernelGGL(k_round_count, dim3((unsigned)((a.nlist + 3) / 4)), dim3(256), 0, s, a);
-    hipLaunchKernelGGL(k_round_scan, dim3(1), dim3(64), 0, s, a);
     hipLaunchKernelGGL(k_item_expand, dim3((unsigned)((a.nlist + 3) / 4)), dim3(256), 0, s, a);
     return hipGetLastError();
 }

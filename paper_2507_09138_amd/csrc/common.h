@@ -155,7 +155,8 @@ hipError_t launch_topk_rows(const float* keys, const float* qnorm, int32_t* out_
 hipError_t launch_seed(int dtype, int d, const SeedArgs& a, hipStream_t s);
 hipError_t launch_row_norms(const void* rows, int dtype, int64_t nrows, int d, float* out, hipStream_t s);
 hipError_t launch_prep_queries(const float* q, int64_t nq, int d, int dtype, void* qop_coarse,
-                               float* qnorm_coarse, void* qop_scan, float* qnorm_scan, hipStream_t s);
+                               float* qnorm_coarse, void* qop_scan, float* qnorm_scan,
+                               int* zero, int64_t n_zero, int* neg, int64_t n_neg, int neg_value, hipStream_t s);
 hipError_t launch_fill_i32(int* p, int64_t n, int v, hipStream_t s);
 hipError_t launch_hot_lists(const unsigned long long* hits, int nlist, int gc, int32_t* out, hipStream_t s);
 hipError_t launch_read_hits(unsigned long long* hits, int64_t n, int64_t* out, int reset, hipStream_t s);
