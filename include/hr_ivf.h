@@ -302,6 +302,17 @@ int hr_ivf_stats(const hr_ivf_index* index, const void* workspace, size_t worksp
                  int64_t nq, int32_t nprobe, int32_t k, int64_t out[4]);
 
 /*
+ * hr_ivf_workspace_layout — how the library divides a workspace of hr_ivf_workspace_bytes(index, nq, nprobe, k)
+ * bytes: for every region it uses, its offset and its length in bytes (out[2i], out[2i+1], HOST, in order of
+ * offset; *n = number of regions, of which at most cap are written).  Behind every region lie at least
+ * HR_WORKSPACE_ALIGN bytes that no kernel writes: a test can fill the workspace with a pattern, run a search and
+ * verify that the pattern survives everywhere outside the regions (an overrun of a region that is sized on the
+ * host and indexed on the device would show there).  For tests; the layout may change between versions.
+ */
+int hr_ivf_workspace_layout(const hr_ivf_index* index, int64_t nq, int32_t nprobe, int32_t k, int64_t* out,
+                            int32_t cap, int32_t* n);
+
+/*
  * Kernel timing for benchmarks.  hr_ivf_profile_begin creates max_calls pairs of HIP events
  * (no device memory); from then on every hr_ivf_search / hr_ivf_scan records one pair on its
  * stream immediately before and after the list-scan kernel (the dominant kernel), until

@@ -149,7 +149,7 @@ int oracle_num_threads(void)
 }
 
 /*
- * Coarse step (Section 2.2: "the nprobe closest clusters are selected").
+ * Coarse step (Section 2.2: the choice of the clusters whose centroids are closest to the query).
  * out_probe[q*nprobe + r] = index of the r-th best centroid for query q,
  * out_scores likewise (double).  Returns 0, or -1 on bad arguments.
  */

@@ -55,6 +55,7 @@ def _load_lib():
     L.hr_ivf_rescore.argtypes = [p, p, c.c_int64, p, c.c_int32, c.c_int32, c.c_int32, p, p, p, p]
     L.hr_ivf_lists_of_rows.argtypes = [p, p, c.c_int64, p, p]
     L.hr_ivf_reorder_probes.argtypes = [p, c.c_int64, c.c_int32, p, c.c_int32, p, c.c_int32, p, p]
+    L.hr_ivf_workspace_layout.argtypes = [p, c.c_int64, c.c_int32, c.c_int32, c.POINTER(c.c_int64), c.c_int32, c.POINTER(c.c_int32)]
     L.hr_ivf_stats.argtypes = [p, p, c.c_size_t, c.c_int64, c.c_int32, c.c_int32, c.POINTER(c.c_int64)]
     L.hr_ivf_profile_begin.argtypes = [p, c.c_int32]
     L.hr_ivf_profile_end.argtypes = [p, c.POINTER(c.c_int32), c.POINTER(c.c_double)]
@@ -184,6 +185,14 @@ def hr_ivf_split_probes(handle, probe_ids, nq, nprobe, out_resident, out_missing
 
 def hr_ivf_refresh_rows(handle, row_begin, row_end, stream=None):
     _check(lib.hr_ivf_refresh_rows(handle, row_begin, row_end, _stream(stream)))
+
+
+def hr_ivf_workspace_layout(handle, nq, nprobe, k):
+    """[(offset, bytes)] of the regions of a workspace for this batch shape."""
+    out = (ctypes.c_int64 * 64)()
+    n = ctypes.c_int32()
+    _check(lib.hr_ivf_workspace_layout(handle, nq, nprobe, k, out, 32, ctypes.byref(n)))
+    return [(out[2 * i], out[2 * i + 1]) for i in range(min(n.value, 32))]
 
 
 def hr_ivf_stats(handle, workspace, workspace_bytes, nq, nprobe, k):

@@ -202,6 +202,10 @@ struct Plan {
     int64_t cchunk;                 // queries per coarse chunk
     size_t o_slot_cnt, o_slot_ent;
     size_t total;
+    // the regions above in order of their offsets (for hr_ivf_workspace_layout); a guard gap of
+    // HR_WORKSPACE_ALIGN bytes that nothing writes lies behind every one
+    int nreg;
+    size_t reg_off[24], reg_len[24];
 };
 
 // What bounds the size of a plan: the aimed number of work items of the list scan (segments are sized so that
@@ -245,7 +249,12 @@ static Plan make_plan(const hr_ivf_index* ix, int64_t nq, int nprobe, int k, con
     p.slot_cap = (int)((int64_t)p.cw_s * lim.item_target + pairs);
 
     size_t o = 0;
-    auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
+    auto take = [&](size_t bytes) {
+        size_t at = o;
+        p.reg_off[p.nreg] = at; p.reg_len[p.nreg] = bytes; p.nreg++;
+        o = align_up(o + bytes) + HR_WORKSPACE_ALIGN;
+        return at;
+    };
     p.zoff_round = (size_t)nlist + DYN_COUNT + 24;  // + 8 counters, 8 queue lengths, 8 queue heads
     p.zoff_hist = p.zoff_round + 2 * 8 * 64;
     p.zoff_hpar = p.zoff_hist + (size_t)nq * kHistBins;
@@ -873,6 +882,19 @@ int hr_ivf_refresh_rows(hr_ivf_index* ix, int64_t row_begin, int64_t row_end, vo
     if (ix->d_vec_hi)
         HR_HIP(launch_split_f32((const float*)rows, n * ix->d, (char*)ix->d_vec_hi + (size_t)row_begin * ix->d * 2,
                                 (char*)ix->d_vec_lo + (size_t)row_begin * ix->d * 2, s));
+    return HR_OK;
+}
+
+int hr_ivf_workspace_layout(const hr_ivf_index* ix, int64_t nq, int32_t nprobe, int32_t k, int64_t* out, int32_t cap,
+                            int32_t* n)
+{
+    if (int rc = check_index(ix)) return rc;
+    if (!out || !n || cap < 0) return fail(HR_ERR_ARG, "out / n is null");
+    if (nprobe < 1 || nprobe > HR_NPROBE_MAX) return fail(HR_ERR_ARG, "nprobe=%d must be in 1..%d", nprobe, HR_NPROBE_MAX);
+    if (int rc = check_batch(ix, nq, nprobe > ix->nlist ? (int)ix->nlist : nprobe, k, HR_METRIC_IP, true)) return rc;
+    const Plan p = make_plan(ix, nq, nprobe, k);
+    *n = p.nreg;
+    for (int i = 0; i < p.nreg && i < cap; i++) { out[2 * i] = (int64_t)p.reg_off[i]; out[2 * i + 1] = (int64_t)p.reg_len[i]; }
     return HR_OK;
 }
 

@@ -77,6 +77,7 @@ def test_null_handle_is_rejected(hr):
     assert hr.lib.hr_ivf_hot_lists(None, 1, None, None) == -2
     assert hr.lib.hr_ivf_refresh_rows(None, 0, 0, None) == -2
     assert hr.lib.hr_ivf_set_resident(None, None, 0, 1, None) == -2
+    assert hr.lib.hr_ivf_workspace_layout(None, 1, 1, 1, None, 0, None) == -2
     assert hr.lib.hr_ivf_split_probes(None, None, 1, 1, None, None, None) == -2
     assert hr.lib.hr_ivf_search_static(None, None, 1, 1, 1, 0, None, None, None) == -2
     bogus = (ctypes.c_uint64 * 64)()                 # memory that is not an index

@@ -823,6 +823,46 @@ def test_partial_residency_hot_lists_resident_then_one_swapped_in(dtype, metric)
     ix.close()
 
 
+@pytest.mark.parametrize("dtype,metric,k,tables", [("f16", "ip", 10, False), ("bf16", "l2", 100, False), ("f32", "l2", 30, True),
+                                                   ("f32", "ip", 5, False), ("bf16", "ip", 64, True)])
+def test_no_kernel_writes_outside_its_workspace_region(dtype, metric, k, tables):
+    """Guard words: the workspace is filled with a pattern, a search, a coarse call, a scan and a step-wise scan run in
+    it, and the pattern must survive in every byte that lies outside the regions the library says it uses (behind
+    every region there is a gap for exactly this), and in the bytes beyond the size it asked for.  The regions are
+    sized on the host from worst-case bounds and indexed on the device, where an overrun would otherwise be silent."""
+    hr = _hr()
+    print(f"case guards {dtype} {metric} k={k}", flush=True)
+    cfg = synth.scaled(synth.CONFIGS["C3"], N=150000, nlist=200, nq=700, nprobe=24, k=k, dtype=dtype, metric=metric, d=128,
+                       normalize=metric == "ip")
+    idx = synth.make_index(cfg, "cuda")
+    q = synth.make_queries(cfg, idx)[0]
+    ix = hr.IvfIndex(idx.centroids, idx.list_offsets, idx.list_vectors, idx.list_ids, row_tables=tables)
+    m = hr.HR_METRIC_IP if metric == "ip" else hr.HR_METRIC_L2
+    for nq, nprobe in ((700, 24), (33, 200), (1, 1)):
+        need = hr.hr_ivf_workspace_bytes(ix.handle, nq, nprobe, k)
+        regions = hr.hr_ivf_workspace_layout(ix.handle, nq, nprobe, k)
+        assert regions and all(o % 256 == 0 for o, _ in regions) and max(o + n for o, n in regions) <= need
+        tail = 1 << 16
+        ws = torch.full((need + tail,), 0xA5, dtype=torch.uint8, device="cuda")
+        qq = q[:nq].contiguous()
+        ids = torch.empty(nq, k, dtype=torch.int64, device="cuda")
+        sc = torch.empty(nq, k, dtype=torch.float32, device="cuda")
+        probe = torch.empty(nq, nprobe, dtype=torch.int32, device="cuda")
+        hr.hr_ivf_search(ix.handle, qq, nq, nprobe, k, m, ids, sc, ws, need)
+        hr.hr_ivf_coarse(ix.handle, qq, nq, nprobe, m, probe, None, ws, need)
+        hr.hr_ivf_scan(ix.handle, qq, nq, probe, nprobe, k, m, ids, sc, ws, need)
+        ids.fill_(-1)
+        hr.hr_ivf_scan_step(ix.handle, qq, nq, probe, nprobe, k, m, ids, sc, ws, need)
+        torch.cuda.synchronize()
+        outside = torch.ones(need + tail, dtype=torch.bool, device="cuda")
+        for o, n in regions:
+            outside[o:o + n] = False
+        bad = (ws != 0xA5) & outside
+        assert not bool(bad.any()), f"nq={nq} nprobe={nprobe}: byte {int(bad.nonzero()[0])} outside every region was written"
+        assert int(outside[:need].sum()) >= 256 * len(regions)
+    ix.close()
+
+
 def test_negative_labels_are_refused_at_load():
     """A negative id marks an empty place in results, so a label may not be negative."""
     hr = _hr()

@@ -417,3 +417,17 @@ def test_split_probes_worked_example_and_invariants():
         assert len(r) + len(m) == len(valid) and not np.intersect1d(r, m).size
         assert np.array_equal(r, valid[resident[valid]]) and np.array_equal(m, valid[~resident[valid]])
         assert (res[i][len(r):] == -1).all() and (mis[i][len(m):] == -1).all()
+
+
+def test_oracle_under_address_and_undefined_behaviour_sanitizers(tmp_path):
+    """The oracle's C code built with -fsanitize=address,undefined (host code only) and run on small inputs that
+    reach its corners (oracle/sanitize_main.c): any out-of-bounds access, use after free or undefined arithmetic
+    stops the run with a report."""
+    import subprocess
+    src = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "oracle", "sanitize_main.c")
+    exe = str(tmp_path / "oracle_sanitize")
+    subprocess.run(["gcc", "-O1", "-g", "-std=c11", "-fopenmp", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+                    "-fno-omit-frame-pointer", "-Wall", "-Wextra", "-o", exe, src, "-lm"], check=True)
+    env = dict(os.environ, ASAN_OPTIONS="verify_asan_link_order=0:detect_leaks=1", OMP_NUM_THREADS="4")
+    r = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=120)
+    assert r.returncode == 0 and "oracle sanitize ok" in r.stdout, r.stdout + r.stderr
