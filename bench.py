@@ -38,6 +38,8 @@ def operand_name(cfg, ix):
     if cfg.dtype == "bf16":
         return "f16" if ix.row_tables else "bf16"   # binary16 row table asked for at load, else bfloat16 rows x (hi, lo) query
     return "f16"
+
+
 def traffic_from_profiles(cfg, row_tables):
     """HBM bytes per list-scan launch (read + written) as the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised under
     profiles/ measured them for this workload (counters cannot be read from inside this process): the number after
@@ -440,7 +442,7 @@ def main():
         "config": {"workload": f"{cfg.name}: N={cfg.N}, d={cfg.d}, nlist={cfg.nlist}, nq={nq}, "
                                f"nprobe={cfg.nprobe}, k={cfg.k}, {cfg.dtype} storage, {cfg.metric}",
                    "row_tables": bool(args.row_tables and cfg.dtype != "f16"), "rounds": cfg.rounds, "launch": "hip graph replay" if args.graph else "eager", "cache_flushed_between_calls_mb": args.flush_mb, "scan_items": st["items"], "seg_rows": st["seg_rows"],
-                   "pairs": st["pairs"]},
+                   "pairs": st["pairs"], "workspace_mb": round(ws.numel() / 2**20, 1)},
         "roofline": {"bound": "hbm", "kernel": "k_scan (list scan)", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic, "traffic_source": traffic_src, "scan_ms_avg": scan_ms, "launches_timed": n_timed,

@@ -994,12 +994,16 @@ inline hipError_t launch_scan_dtype(int d, const ScanArgs& a, int shape, int gri
 }
 
 // ------------------------------------------------------------------------------------------
-// Threshold seeding.  One wave per query scores the first rows of the query's best-ranked
+// Threshold seeding.  One workgroup per query scores the first rows of the query's best-ranked
 // list (with the very MFMA sequence of k_scan, so the keys are the ones the scan will compute
 // for these rows) and publishes the k-th best of them as the query's starting lower bound.
 // On clustered data that bound already excludes nearly every row of the other probed lists,
 // which then cost the scan one compare per score instead of a candidate insertion.  Any k
 // real candidates give a valid bound, so the result of the search does not depend on this.
+// The kernel is a chain of round trips to memory (probe row, list offsets, rows), so what
+// matters is how few there are one after the other: each wave takes every fourth 16-row
+// block and asks for the whole block at once (the query operand waits in LDS meanwhile,
+// not in registers), wave 0 then picks the k-th key.
 constexpr int kSeedRowsMax = 192;
 
 template <int DT, int KSTEPS>
@@ -1009,11 +1013,13 @@ __global__ __launch_bounds__(256) void k_seed(SeedArgs a)
     constexpr int NC = T::nc;
     constexpr int d = KSTEPS * 32;
     constexpr int rowb = d * T::esize;
-    __shared__ uint32_t s_keys[4][kSeedRowsMax];
+    constexpr int QP = (NC == 8) ? 2 : 1;               // operand rows per query (bfloat16: hi and lo)
+    __shared__ uint32_t s_keys[kSeedRowsMax];
+    __shared__ u32x4 s_q[QP * KSTEPS * 4];
     const int lane = lane_id(), wave = threadIdx.x >> 6;
-    const int64_t q = (int64_t)blockIdx.x * 4 + wave;
-    if (q >= a.nq) return;
-    // the best-ranked list of the query whose vectors are in place (among the first 64 places of its row)
+    const int64_t q = blockIdx.x;
+    // the best-ranked list of the query whose vectors are in place (among the first 64 places of its row);
+    // every wave finds it for itself (same loads, same answer: what follows is uniform over the workgroup)
     int l = -1;
     {
         const int c = lane < a.nprobe ? a.probe[q * a.nprobe + lane] : -1;
@@ -1024,52 +1030,63 @@ __global__ __launch_bounds__(256) void k_seed(SeedArgs a)
     const int row0 = a.list_off[l];
     const int nrows = min(a.list_off[l + 1] - row0, a.seed_rows);
     if (nrows < a.k) return;
+    for (int i = threadIdx.x; i < QP * KSTEPS * 4; i += 256)
+        s_q[i] = ((const u32x4*)((const char*)a.qop + (size_t)q * QP * (size_t)(d * 2)))[i];
     const int g = lane >> 4;
     const int part = (NC == 8) ? ((lane >> 3) & 1) : 0;
     const bool bcol = (lane & (NC - 1)) == 0;          // MFMA column 0 (and its lo twin)
-    u32x4 bfrag[KSTEPS];
-    {
-        const size_t qrow = (NC == 8) ? ((size_t)q * 2 + part) : (size_t)q;
-        const char* qp = (const char*)a.qop + qrow * (size_t)(d * 2) + g * 16;
-#pragma unroll
-        for (int t = 0; t < KSTEPS; t++) bfrag[t] = bcol ? *(const u32x4*)(qp + t * 64) : u32x4{0, 0, 0, 0};
-    }
-    uint32_t* keys = s_keys[wave];
+    const u32x4* qfrag = s_q + part * (KSTEPS * 4) + g;
+    __syncthreads();
     const int nblk = (nrows + 15) / 16;
-    for (int blk = 0; blk < nblk; blk++) {
+    for (int blk = wave; blk < nblk; blk += 4) {
         const int r = row0 + blk * 16 + (lane & 15);
         const bool rv = r < row0 + nrows;
-        const char* rp = (const char*)a.rows + (size_t)r * rowb;
+        const char* rp = (const char*)a.rows + (size_t)(rv ? r : row0) * rowb;
         floatx4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+        if constexpr (DT == HR_F32) {
+            constexpr int H = KSTEPS / 2;               // half a row at a time: 8 registers per k-step
 #pragma unroll
-        for (int t = 0; t < KSTEPS; t++) {
-            if constexpr (DT == HR_F32) {
-                float x[8];
-                u32x4 v0 = rv ? *(const u32x4*)(rp + t * 128 + g * 32) : u32x4{0, 0, 0, 0};
-                u32x4 v1 = rv ? *(const u32x4*)(rp + t * 128 + g * 32 + 16) : u32x4{0, 0, 0, 0};
-                const floatx4 f0 = __builtin_bit_cast(floatx4, v0), f1 = __builtin_bit_cast(floatx4, v1);
+            for (int h = 0; h < 2; h++) {
+                u32x4 v0[H], v1[H];
 #pragma unroll
-                for (int i = 0; i < 4; i++) { x[i] = f0[i]; x[4 + i] = f1[i]; }
-                half8 hi, lo;
-#pragma unroll
-                for (int i = 0; i < 8; i++) {
-                    _Float16 h = (_Float16)x[i];
-                    hi[i] = h;
-                    lo[i] = (_Float16)((x[i] - (float)h) * 2048.0f);
+                for (int t = 0; t < H; t++) {
+                    v0[t] = *(const u32x4*)(rp + (h * H + t) * 128 + g * 32);
+                    v1[t] = *(const u32x4*)(rp + (h * H + t) * 128 + g * 32 + 16);
                 }
-                half8 b = __builtin_bit_cast(half8, bfrag[t]);
-                acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(hi, b, acc0, 0, 0, 0);
-                acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(lo, b, acc1, 0, 0, 0);
-            } else {
-                u32x4 v = rv ? *(const u32x4*)(rp + t * 64 + g * 16) : u32x4{0, 0, 0, 0};
+#pragma unroll
+                for (int t = 0; t < H; t++) {
+                    const floatx4 f0 = __builtin_bit_cast(floatx4, v0[t]), f1 = __builtin_bit_cast(floatx4, v1[t]);
+                    float x[8];
+#pragma unroll
+                    for (int i = 0; i < 4; i++) { x[i] = rv ? f0[i] : 0.f; x[4 + i] = rv ? f1[i] : 0.f; }
+                    half8 hi, lo;
+#pragma unroll
+                    for (int i = 0; i < 8; i++) {
+                        _Float16 hh = (_Float16)x[i];
+                        hi[i] = hh;
+                        lo[i] = (_Float16)((x[i] - (float)hh) * 2048.0f);
+                    }
+                    const half8 b = __builtin_bit_cast(half8, bcol ? qfrag[(h * H + t) * 4] : u32x4{0, 0, 0, 0});
+                    acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(hi, b, acc0, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(lo, b, acc1, 0, 0, 0);
+                }
+            }
+        } else {
+            u32x4 v[KSTEPS];
+#pragma unroll
+            for (int t = 0; t < KSTEPS; t++) v[t] = *(const u32x4*)(rp + t * 64 + g * 16);
+#pragma unroll
+            for (int t = 0; t < KSTEPS; t++) {
+                const u32x4 x = rv ? v[t] : u32x4{0, 0, 0, 0};
+                const u32x4 bq = bcol ? qfrag[t * 4] : u32x4{0, 0, 0, 0};
                 if constexpr (DT == HR_F16) {
-                    half8 b = __builtin_bit_cast(half8, bfrag[t]);
-                    if (t & 1) acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, v), b, acc1, 0, 0, 0);
-                    else       acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, v), b, acc0, 0, 0, 0);
+                    const half8 b = __builtin_bit_cast(half8, bq);
+                    if (t & 1) acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, x), b, acc1, 0, 0, 0);
+                    else       acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, x), b, acc0, 0, 0, 0);
                 } else {
-                    bf16x8 b = __builtin_bit_cast(bf16x8, bfrag[t]);
-                    if (t & 1) acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, v), b, acc1, 0, 0, 0);
-                    else       acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, v), b, acc0, 0, 0, 0);
+                    const bf16x8 b = __builtin_bit_cast(bf16x8, bq);
+                    if (t & 1) acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, x), b, acc1, 0, 0, 0);
+                    else       acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, x), b, acc0, 0, 0, 0);
                 }
             }
         }
@@ -1081,19 +1098,21 @@ __global__ __launch_bounds__(256) void k_seed(SeedArgs a)
                 float t1 = lane_xor8(acc1[r4]);
                 dot = acc0[r4] + (t0 + acc1[r4]) * (1.0f / 2048.0f) + t1 * (1.0f / 4194304.0f);
             } else if constexpr (DT == HR_BF16) {
-                float v = acc0[r4] + acc1[r4];
-                dot = v + lane_xor8(v);
+                float v2 = acc0[r4] + acc1[r4];
+                dot = v2 + lane_xor8(v2);
             } else {
                 dot = acc0[r4] + acc1[r4];
             }
             const int row = row0 + blk * 16 + g * 4 + r4;
             if ((lane & 15) == 0 && row < row0 + nrows) {
                 float key = a.l2 ? (2.0f * dot - a.row_norm[row]) : dot;
-                keys[blk * 16 + g * 4 + r4] = enc_key(key);
+                s_keys[blk * 16 + g * 4 + r4] = enc_key(key);
             }
         }
     }
-    wave_sync();
+    __syncthreads();
+    if (wave != 0) return;
+    const uint32_t* keys = s_keys;
     // k-th largest of the nrows keys (binary radix select, as in wave_select)
     uint32_t e[3];
     unsigned long long alive[3];
@@ -1149,7 +1168,7 @@ template <int DT>
 inline hipError_t launch_seed_dtype(int d, const SeedArgs& a, hipStream_t s)
 {
     if (a.nq <= 0) return hipSuccess;
-    const dim3 grid((unsigned)((a.nq + 3) / 4));
+    const dim3 grid((unsigned)a.nq);
 #define HR_SEED_CASE(KS) case KS * 32: hipLaunchKernelGGL((k_seed<DT, KS>), grid, dim3(256), 0, s, a); return hipGetLastError();
     switch (d) {
         HR_SEED_CASE(2)
