@@ -353,6 +353,10 @@ __device__ __forceinline__ int round_of(int l, int s, int nseg, int R)
 
 // One workgroup: bucket offsets, rows per segment for this batch, first work item and first
 // result slot of every list, and where every round of every queue starts.
+// (PER > 0: every thread owns at most PER lists and reads their widths and lengths once, all loads in flight
+// together, into registers; the passes below then run without touching memory again.  PER == 0: any number of
+// lists per thread, read from memory in every pass.)
+template <int PER>
 __global__ __launch_bounds__(1024) void k_bucket_scan(BucketArgs a)
 {
     __shared__ int s_wave[17];
@@ -362,13 +366,47 @@ __global__ __launch_bounds__(1024) void k_bucket_scan(BucketArgs a)
     if (t == 0) s_maxseg = 0;
     const int per = (a.nlist + 1023) / 1024;
     const int l0 = min(a.nlist, t * per), l1 = min(a.nlist, l0 + per);
+    constexpr int NR = PER > 0 ? PER : 1;
+    constexpr int UN = NR;                              // loops over a thread's lists: unrolled when they sit in registers
+    int wv[NR], lv[NR];
+    if constexpr (PER > 0) {
+#pragma unroll
+        for (int i = 0; i < PER; i++) {
+            const int l = min(l0 + i, a.nlist - 1);
+            wv[i] = a.list_w[l];
+            lv[i] = a.list_off[l + 1] - a.list_off[l];
+        }
+    }
+    auto width = [&](int l) __attribute__((always_inline)) -> int {
+        if constexpr (PER > 0) {
+            int r = 0;
+#pragma unroll
+            for (int i = 0; i < PER; i++) r = (l - l0 == i) ? wv[i] : r;
+            return r;
+        } else {
+            return a.list_w[l];
+        }
+    };
+    auto length = [&](int l) __attribute__((always_inline)) -> int {
+        if constexpr (PER > 0) {
+            int r = 0;
+#pragma unroll
+            for (int i = 0; i < PER; i++) r = (l - l0 == i) ? lv[i] : r;
+            return r;
+        } else {
+            return a.list_off[l + 1] - a.list_off[l];
+        }
+    };
 
     // pass 1: bucket offsets, cost = sum rows * query tiles, rows streamed, pairs
     int w_sum = 0;
     long long cost = 0, rows = 0;
-    for (int l = l0; l < l1; l++) {
-        int w = a.list_w[l];
-        long long len = a.list_off[l + 1] - a.list_off[l];
+#pragma unroll UN
+    for (int i = 0; i < (PER > 0 ? PER : per); i++) {
+        const int l = l0 + i;
+        if (l >= l1) break;
+        int w = width(l);
+        long long len = length(l);
         if (a.hits != nullptr && w > 0) atomicAdd(&a.hits[l], (unsigned long long)w);     // access frequency of the list
         w_sum += w;
         cost += len * ((w + a.cw - 1) / a.cw);
@@ -377,7 +415,12 @@ __global__ __launch_bounds__(1024) void k_bucket_scan(BucketArgs a)
     int total;
     {
         int run = block_scan_1024(w_sum, s_wave, total);
-        for (int l = l0; l < l1; l++) { a.bucket_off[l] = run; run += a.list_w[l]; }
+#pragma unroll UN
+        for (int i = 0; i < (PER > 0 ? PER : per); i++) {
+            const int l = l0 + i;
+            if (l >= l1) break;
+            a.bucket_off[l] = run; run += width(l);
+        }
         if (t == 0) { a.bucket_off[a.nlist] = total; a.dyn[DYN_PAIRS] = total; }
     }
     const long long c = block_sum_1024(cost, s_lwave);
@@ -400,21 +443,27 @@ __global__ __launch_bounds__(1024) void k_bucket_scan(BucketArgs a)
 
     // pass 2: work items per list = segments * query tiles; result slots per list = segments * bucket width
     // (one slot per (segment, query of the bucket): slot of entry e of segment s = slot_base[l] + s * w + e)
-    auto list_items = [&](int l, int& nseg, int& nqt) {
-        const int w = a.list_w[l];
-        const int len = a.list_off[l + 1] - a.list_off[l];
+    auto list_items = [&](int l, int& nseg, int& nqt) __attribute__((always_inline)) {
+        const int w = width(l);
+        const int len = length(l);
         nseg = (w > 0 && len > 0) ? (len + seg - 1) / seg : 0;
         nqt = (w + a.cw - 1) / a.cw;
     };
     int items = 0, slots = 0, maxseg = 0;
-    for (int l = l0; l < l1; l++) {
+#pragma unroll UN
+    for (int i = 0; i < (PER > 0 ? PER : per); i++) {
+        const int l = l0 + i;
+        if (l >= l1) break;
         int nseg, nqt; list_items(l, nseg, nqt);
-        items += nseg * nqt; slots += nseg * a.list_w[l]; maxseg = max(maxseg, nseg);
+        items += nseg * nqt; slots += nseg * width(l); maxseg = max(maxseg, nseg);
     }
     if (maxseg > 0) atomicMax(&s_maxseg, maxseg);
     {
         int run = block_scan_1024(items, s_wave, total);
-        for (int l = l0; l < l1; l++) {
+#pragma unroll UN
+        for (int i = 0; i < (PER > 0 ? PER : per); i++) {
+            const int l = l0 + i;
+            if (l >= l1) break;
             a.item_base[l] = run;
             int nseg, nqt; list_items(l, nseg, nqt);
             run += nseg * nqt;
@@ -427,10 +476,13 @@ __global__ __launch_bounds__(1024) void k_bucket_scan(BucketArgs a)
     }
     {
         int run = block_scan_1024(slots, s_wave, total);
-        for (int l = l0; l < l1; l++) {
+#pragma unroll UN
+        for (int i = 0; i < (PER > 0 ? PER : per); i++) {
+            const int l = l0 + i;
+            if (l >= l1) break;
             a.slot_base[l] = run;
             int nseg, nqt; list_items(l, nseg, nqt);
-            run += nseg * a.list_w[l];
+            run += nseg * width(l);
         }
         if (t == 0) {
             a.slot_base[a.nlist] = total;
@@ -518,7 +570,10 @@ hipError_t launch_bucketing(const BucketArgs& a, hipStream_t s)
     int64_t pairs = (int64_t)a.nq * a.nprobe;
     unsigned gp = (unsigned)((pairs + 255) / 256);
     hipLaunchKernelGGL(k_bucket_count, dim3(gp), dim3(256), 0, s, a);
-    hipLaunchKernelGGL(k_bucket_scan, dim3(1), dim3(1024), 0, s, a);
+    const int per = (a.nlist + 1023) / 1024;
+    if (per <= 4) hipLaunchKernelGGL(k_bucket_scan<4>, dim3(1), dim3(1024), 0, s, a);
+    else if (per <= 16) hipLaunchKernelGGL(k_bucket_scan<16>, dim3(1), dim3(1024), 0, s, a);
+    else hipLaunchKernelGGL(k_bucket_scan<0>, dim3(1), dim3(1024), 0, s, a);
     hipLaunchKernelGGL(k_bucket_scatter, dim3(gp), dim3(256), 0, s, a);
     hipLaunchKernelGGL(k_round_count, dim3((unsigned)((a.nlist + 3) / 4)), dim3(256), 0, s, a);
     hipLaunchKernelGGL(k_item_expand, dim3((unsigned)((a.nlist + 3) / 4)), dim3(256), 0, s, a);
@@ -566,6 +621,8 @@ __global__ __launch_bounds__(256) void k_merge(MergeArgs a)
     __shared__ int64_t s_tie[4][HR_K_MAX];
     __shared__ int s_pref[4][HR_NPROBE_MAX + 1];
     __shared__ int s_cnt[4];
+    __shared__ int s_first[4][64];
+    __shared__ size_t s_slot[4][64];
     __shared__ int64_t s_ext_id[4][HR_K_MAX];
     __shared__ float s_ext_score[4][HR_K_MAX];
     __shared__ int s_ext_row[4][HR_K_MAX];
@@ -578,6 +635,8 @@ __global__ __launch_bounds__(256) void k_merge(MergeArgs a)
     Cand* buf = s_buf[wave];
     int64_t* tie = s_tie[wave];
     int* pref = s_pref[wave];
+    int* first = s_first[wave];
+    size_t* slot_of = s_slot[wave];
     const int k = a.k;
     const int seg_rows = a.dyn[DYN_SEG_ROWS];
 
@@ -652,12 +711,27 @@ __global__ __launch_bounds__(256) void k_merge(MergeArgs a)
             }
             c = a.slot_cnt[slot];
         }
-        int maxc = c;
+        // the entries of these 64 slots, 64 at a time whichever slot they sit in (a loop over the fullest slot's
+        // entries would be one round trip to memory per entry: the slot of a query's own cluster holds up to k)
+        int inc = c;
 #pragma unroll
-        for (int o = 32; o > 0; o >>= 1) maxc = max(maxc, __shfl_xor(maxc, o));
-        for (int j = 0; j < maxc; j++) {
-            if (j < c) {
-                Cand cd = a.slot_ent[slot * a.slot_stride + j];
+        for (int o = 1; o < 64; o <<= 1) {
+            int v = __shfl_up(inc, o);
+            if (lane >= o) inc += v;
+        }
+        const int tot = __shfl(inc, 63);
+        first[lane] = inc - c;
+        slot_of[lane] = slot;
+        wave_sync();
+        for (int e0 = 0; e0 < tot; e0 += 64) {
+            const int e = e0 + lane;
+            if (e < tot) {
+                int lo = 0, hi = 64;                  // largest lane o with first[o] <= e: the slot that holds entry e
+                while (hi - lo > 1) {
+                    int mid = (lo + hi) >> 1;
+                    if (first[mid] <= e) lo = mid; else hi = mid;
+                }
+                Cand cd = a.slot_ent[slot_of[lo] * a.slot_stride + (e - first[lo])];
                 bool take = cd.key >= thr;
                 // a row the carried result already holds (it came from a cache of earlier results
                 // and its list is scanned now) is not taken a second time
@@ -677,6 +751,7 @@ __global__ __launch_bounds__(256) void k_merge(MergeArgs a)
                 wave_sync();
             }
         }
+        wave_sync();
     }
     wave_sync();
     int n = __builtin_amdgcn_readfirstlane(s_cnt[wave]);

@@ -187,6 +187,18 @@ def test_nprobe_max_many_lists():
     compare_all(idx, q, nprobe=128, k=20, metric="ip")
 
 
+@pytest.mark.parametrize("nlist", [5000, 20000])
+def test_many_short_lists(nlist):
+    """More lists than the grouping kernel's one workgroup has threads: 5 and 20 lists per thread (the second
+    beyond what a thread keeps in registers), many of them empty or shorter than k."""
+    print(f"case {nlist} lists of 2.5 rows on average", flush=True)
+    idx = _random_index(nlist * 5 // 2, 64, nlist, "f16", seed=41)
+    g = torch.Generator(device="cpu").manual_seed(11)
+    q = torch.randn(70, 64, generator=g).cuda()
+    compare_all(idx, q, nprobe=200, k=10, metric="ip")
+    compare_all(idx, q, nprobe=17, k=3, metric="l2")
+
+
 def test_nprobe_512_paper_range():
     """The paper probes 128 to 512 clusters with k = 1 (Section 6.1): nprobe 512 over 700 lists."""
     print("case nprobe=512 over 700 lists, k=1", flush=True)
