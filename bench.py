@@ -429,6 +429,11 @@ def main():
     assert rows_streamed == st["rows_streamed"], (rows_streamed, st)
     scan_bytes = rows_streamed * cfg.d * ESIZE[cfg.dtype]
     scan_flops = 2.0 * cfg.d * pair_rows
+    # flops the matrix pipes execute for them: a wave's MFMA covers 16 columns = 16 queries (binary16 operands) or 8
+    # queries in hi and lo parts (bfloat16 rows as stored; float32 rows, which also come as two planes), whether or
+    # not all of them belong to the bucket (the 16-row padding of a segment's last block is not counted)
+    gran, mult = (16, 1) if operand_name(cfg, ix) == "f16" else ((8, 2) if cfg.dtype == "bf16" else (8, 4))
+    executed_rows = int((((w + gran - 1) // gran) * gran * lens).sum()) * mult
     achieved = scan_bytes / (scan_ms * 1e-3) / 1e9 if scan_ms > 0 else 0.0
 
     own_shape = args.nq == 0 and args.nprobe == 0 and args.noise == 0 and args.drift == 0
@@ -449,8 +454,21 @@ def main():
                      "algorithmic_bytes_per_launch": scan_bytes,
                      "mfma_tflops": scan_flops / (scan_ms * 1e-3) / 1e12 if scan_ms > 0 else 0.0,
                      "mfma_frac": (scan_flops / (scan_ms * 1e-3) / 1e12 / mfma_peak(cfg, ix)) if scan_ms > 0 else 0.0,
-                     "mfma_peak_tflops": mfma_peak(cfg, ix)},
+                     "mfma_peak_tflops": mfma_peak(cfg, ix),
+                     "mfma_flops_executed_over_algorithmic": executed_rows / max(pair_rows, 1)},
     }
+    if len(rounds) > 1:
+        # every round of the workload timed as a call of its own (three passes over the rounds, after the timed region)
+        per = [[] for _ in rounds]
+        for _ in range(3):
+            for r in range(len(rounds)):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                (eager_step if args.graph else step)(r)
+                e1.record()
+                torch.cuda.synchronize()
+                per[r].append(e0.elapsed_time(e1))
+        out["config"]["per_round_ms"] = [round(min(x), 4) for x in per]
     if not args.no_cpu_baseline:
         # (the result of the last timed step, for the comparison with the oracle on the sampled queries)
         last = (args.steps - 1) % len(rounds)
