@@ -1,6 +1,7 @@
 // Small kernels around the list scan: query operand preparation, row norms, grouping of
 // (query, list) probes by list, and the per-query merge of the scan's partial results.
 #include <algorithm>
+#include <type_traits>
 
 #include "scan_kernel.h"
 
@@ -905,7 +906,13 @@ __global__ __launch_bounds__(256) void k_topk_rows(TopkArgs a)
         }
         wave_sync();
         if (cnt >= k && cnt <= kCollect) {
-            if (cnt > k) wave_select<kCollect / 64>(ent, cnt, k, nullptr);      // (equal keys: lower index first)
+            // (equal keys: lower index first; the select walks as many 64-entry chunks as were collected, not
+            // as many as the buffer holds)
+            if (cnt > k) {
+                if (cnt <= 256) wave_select<4>(ent, cnt, k, nullptr);
+                else if (cnt <= 512) wave_select<8>(ent, cnt, k, nullptr);
+                else wave_select<kCollect / 64>(ent, cnt, k, nullptr);
+            }
             done = true;
         }
     }
@@ -985,26 +992,32 @@ __global__ __launch_bounds__(256) void k_topk_rows(TopkArgs a)
     }
     wave_sync();
     // order: key descending, index ascending (rank of every entry = entries ahead of it)
-    constexpr int PER = HR_NPROBE_MAX / 64;         // entries per lane
-    Cand e[PER];
-    int pos[PER];
-#pragma unroll
-    for (int m = 0; m < PER; m++) { e[m] = lane + 64 * m < k ? ent[lane + 64 * m] : Cand{0u, 0u}; pos[m] = 0; }
-    for (int i = 0; i < k; i++) {
-        const Cand o = ent[i];
-#pragma unroll
-        for (int m = 0; m < PER; m++) pos[m] += (o.key > e[m].key || (o.key == e[m].key && o.row < e[m].row)) ? 1 : 0;
-    }
     const float qn = (a.l2 && a.qnorm) ? a.qnorm[q] : 0.f;
+    auto emit = [&](auto per) __attribute__((always_inline)) {
+        constexpr int PER = decltype(per)::value;       // entries per lane
+        Cand e[PER];
+        int pos[PER];
 #pragma unroll
-    for (int m = 0; m < PER; m++) {
-        if (lane + 64 * m < k) {
-            const float key = dec_key(e[m].key);
-            const size_t o = (size_t)q * a.k + pos[m];
-            a.out_ids[o] = (int32_t)e[m].row;
-            if (a.out_scores) a.out_scores[o] = a.l2 ? fmaxf(qn - key, 0.f) : key;
+        for (int m = 0; m < PER; m++) { e[m] = lane + 64 * m < k ? ent[lane + 64 * m] : Cand{0u, 0u}; pos[m] = 0; }
+        for (int i = 0; i < k; i++) {
+            const Cand o = ent[i];
+#pragma unroll
+            for (int m = 0; m < PER; m++) pos[m] += (o.key > e[m].key || (o.key == e[m].key && o.row < e[m].row)) ? 1 : 0;
         }
-    }
+#pragma unroll
+        for (int m = 0; m < PER; m++) {
+            if (lane + 64 * m < k) {
+                const float key = dec_key(e[m].key);
+                const size_t o = (size_t)q * a.k + pos[m];
+                a.out_ids[o] = (int32_t)e[m].row;
+                if (a.out_scores) a.out_scores[o] = a.l2 ? fmaxf(qn - key, 0.f) : key;
+            }
+        }
+    };
+    if (k <= 64) emit(std::integral_constant<int, 1>{});
+    else if (k <= 128) emit(std::integral_constant<int, 2>{});
+    else if (k <= 256) emit(std::integral_constant<int, 4>{});
+    else emit(std::integral_constant<int, HR_NPROBE_MAX / 64>{});
     for (int idx = k + lane; idx < a.k; idx += 64) {       // fewer than k rows: pad
         const size_t o = (size_t)q * a.k + idx;
         a.out_ids[o] = -1;
