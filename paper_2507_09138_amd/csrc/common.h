@@ -34,6 +34,7 @@ __host__ __device__ constexpr int shape_sets(int shape) { return shape_waves(sha
 __host__ __device__ constexpr int scan_group(int dtype, int ksteps, int nw)
 {
     if (ksteps < 8) return ksteps < 4 ? ksteps : 4;
+    if (nw == 8 && dtype == HR_F32 && ksteps >= 24) return 2;       // (leaves registers for a second row block in flight)
     if (nw == 8) return ((dtype == HR_F32 || dtype == HR_F16X2) && ksteps >= 32) ? 2 : 4;   // (256 registers per lane)
     return 8;
 }
