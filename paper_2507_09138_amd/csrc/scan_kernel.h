@@ -356,6 +356,70 @@ __device__ __forceinline__ void mfma_block(const char* const (&ap)[4], const u32
     }
 }
 
+// Two blocks that lie ready in LDS, multiplied back to back as one chain of 2 * KSTEPS k-steps: the first
+// fragments of the second block are fetched while the last MFMAs of the first are issued (a block started on
+// its own begins with a round trip to LDS during which the wave has nothing to issue), and `between` (the
+// filter of the first block) runs after the first MFMAs of the second block have been handed to the matrix pipe.
+template <int DT, int KSTEPS, int NCS, int NA, typename S, typename F>
+__device__ __forceinline__ void mfma_pair(const char* const (&ap0)[4], const char* const (&ap1)[4], const u32x4 (&bfrag)[NCS][KSTEPS],
+                                          floatx4 (&acc0)[NCS][kAcc], floatx4 (&acc1)[NCS][kAcc], F&& between)
+{
+    constexpr int G = S::grp;
+    constexpr int NG = KSTEPS / G;
+    constexpr int AM = (NA == 1 ? kAcc : 2) - 1;
+    constexpr int P = StoreTraits<DT>::planes;
+    static_assert(KSTEPS % G == 0, "k-steps must split into whole groups");
+    static_assert(NG % 2 == 0, "the fragment buffers alternate: an even number of groups per block");
+#pragma unroll
+    for (int s = 0; s < NA; s++)
+#pragma unroll
+        for (int i = 0; i < kAcc; i++) { acc0[s][i] = floatx4{0.f, 0.f, 0.f, 0.f}; acc1[s][i] = floatx4{0.f, 0.f, 0.f, 0.f}; }
+    u32x4 af[2][P][G];
+    // (every index below is a compile-time constant: the loop over the groups is unrolled by the type system,
+    // so that the operand and accumulator arrays stay in registers)
+    auto fetch = [&](auto gc) __attribute__((always_inline)) {       // group gg of the 2 * NG groups of the pair
+        constexpr int gg = decltype(gc)::value;
+        constexpr int g0 = (gg < NG ? gg : gg - NG) * G;
+#pragma unroll
+        for (int i = 0; i < G; i++)
+#pragma unroll
+            for (int pl = 0; pl < P; pl++) {
+                if constexpr (gg < NG) af[gg & 1][pl][i] = *(const u32x4*)(ap0[(g0 + i) & 3] + pl * S::plane_bytes + ((g0 + i) >> 2) * 256);
+                else                   af[gg & 1][pl][i] = *(const u32x4*)(ap1[(g0 + i) & 3] + pl * S::plane_bytes + ((g0 + i) >> 2) * 256);
+            }
+    };
+    auto group = [&](auto gc, floatx4 (&acc)[NCS][kAcc]) __attribute__((always_inline)) {
+        constexpr int gg = decltype(gc)::value;
+#pragma unroll
+        for (int i = 0; i < G; i++) {
+            const int t = (gg < NG ? gg : gg - NG) * G + i;
+#pragma unroll
+            for (int s = 0; s < NA; s++) {
+                if constexpr (StoreTraits<DT>::planes == 2) {
+                    half8 b = __builtin_bit_cast(half8, bfrag[s][t]);
+                    acc[s][0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, af[gg & 1][0][i]), b, acc[s][0], 0, 0, 0);
+                    acc[s][1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, af[gg & 1][1][i]), b, acc[s][1], 0, 0, 0);
+                } else if constexpr (DT == HR_F16) {
+                    half8 b = __builtin_bit_cast(half8, bfrag[s][t]);
+                    acc[s][t & AM] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, af[gg & 1][0][i]), b, acc[s][t & AM], 0, 0, 0);
+                } else {
+                    bf16x8 b = __builtin_bit_cast(bf16x8, bfrag[s][t]);
+                    acc[s][t & AM] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af[gg & 1][0][i]), b, acc[s][t & AM], 0, 0, 0);
+                }
+            }
+        }
+    };
+    fetch(std::integral_constant<int, 0>{});
+    static_for<2 * NG>([&](auto gc) __attribute__((always_inline)) {
+        constexpr int gg = decltype(gc)::value;
+        if constexpr (gg + 1 < 2 * NG) fetch(std::integral_constant<int, gg + 1>{});
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (gg < NG) group(gc, acc0); else group(gc, acc1);
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (gg == NG) between();
+    });
+}
+
 // prune with as few register slots per lane as the buffer capacity needs
 __device__ __forceinline__ uint32_t select_k(Cand* buf, int n, int k, int cap, const int64_t* ids)
 {
@@ -700,8 +764,8 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
         };
 
         int bi = 0;                                              // blk % NB
-        floatx4 accs[1][NCS][kAcc];
-        floatx4 nrms[1] = {floatx4{0.f, 0.f, 0.f, 0.f}};
+        floatx4 accs[2][NCS][kAcc];
+        floatx4 nrms[2] = {floatx4{0.f, 0.f, 0.f, 0.f}, floatx4{0.f, 0.f, 0.f, 0.f}};
         // direct staging: (1) this wave's part of block blk has landed, (2) barrier: so has
         // everybody's, and nobody reads block blk-1 any more, (3) request block blk+D into the
         // buffer that one leaves, (4) multiply, (5) select
@@ -753,17 +817,37 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
                 fill_direct(blk + D + 1, fb + 1);
             };
             if (early) requests();
-#pragma unroll
-            for (int h = 0; h < 2; h++) {
-                if (nact > 0 && blk + h < nblk) {
-                    const char* cur = stage + (bi + h) * S::buf_bytes;
-                    if (a.l2) nrms[0] = *(const floatx4*)(nstage + (bi + h) * kBlockRows + g * 4);
-                    const char* const ap[4] = {cur + abase[0], cur + abase[1], cur + abase[2], cur + abase[3]};
-                    if (NCS == 2 && nact == 2) mfma_block<DT, KSTEPS, NCS, NCS, S>(ap, bfrag, accs[0]);
-                    else                       mfma_block<DT, KSTEPS, NCS, 1, S>(ap, bfrag, accs[0]);
-                    select_block(accs[0], nrms[0], row0 + (blk + h) * kBlockRows + g * 4);
+            if (NCS == 1 && S::grp * 2 <= KSTEPS && (KSTEPS / S::grp) % 2 == 0 && nact > 0 && blk + 1 < nblk) {
+                // both blocks of the pair as one chain (see mfma_pair); the late requests go out with the
+                // filter of the first block
+                const char* c0 = stage + bi * S::buf_bytes;
+                const char* c1 = c0 + S::buf_bytes;
+                if (a.l2) {
+                    nrms[0] = *(const floatx4*)(nstage + bi * kBlockRows + g * 4);
+                    nrms[1] = *(const floatx4*)(nstage + (bi + 1) * kBlockRows + g * 4);
                 }
-                if (h == 0 && !early) requests();
+                const char* const ap0[4] = {c0 + abase[0], c0 + abase[1], c0 + abase[2], c0 + abase[3]};
+                const char* const ap1[4] = {c1 + abase[0], c1 + abase[1], c1 + abase[2], c1 + abase[3]};
+                if constexpr (NCS == 1 && (KSTEPS / S::grp) % 2 == 0 && S::grp * 2 <= KSTEPS) {
+                    mfma_pair<DT, KSTEPS, NCS, 1, S>(ap0, ap1, bfrag, accs[0], accs[1], [&]() __attribute__((always_inline)) {
+                        if (!early) requests();
+                        select_block(accs[0], nrms[0], row0 + blk * kBlockRows + g * 4);
+                    });
+                }
+                select_block(accs[1], nrms[1], row0 + (blk + 1) * kBlockRows + g * 4);
+            } else {
+#pragma unroll
+                for (int h = 0; h < 2; h++) {
+                    if (nact > 0 && blk + h < nblk) {
+                        const char* cur = stage + (bi + h) * S::buf_bytes;
+                        if (a.l2) nrms[0] = *(const floatx4*)(nstage + (bi + h) * kBlockRows + g * 4);
+                        const char* const ap[4] = {cur + abase[0], cur + abase[1], cur + abase[2], cur + abase[3]};
+                        if (NCS == 2 && nact == 2) mfma_block<DT, KSTEPS, NCS, NCS, S>(ap, bfrag, accs[0]);
+                        else                       mfma_block<DT, KSTEPS, NCS, 1, S>(ap, bfrag, accs[0]);
+                        select_block(accs[0], nrms[0], row0 + (blk + h) * kBlockRows + g * 4);
+                    }
+                    if (h == 0 && !early) requests();
+                }
             }
             bi = bi + 2 == NB ? 0 : bi + 2;
         };
