@@ -85,6 +85,12 @@ __device__ __forceinline__ void lds_dma16(const void* base, uint32_t byte_off, u
 {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" :: "s"(lds), "v"(byte_off), "s"(base) : "memory");
 }
+// the same marked non-temporal: rows that nobody else will ask for (a list scanned by one work item) should not
+// push the rows that several work items share out of the L2
+__device__ __forceinline__ void lds_dma16_nt(const void* base, uint32_t byte_off, uint32_t lds)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 nt" :: "s"(lds), "v"(byte_off), "s"(base) : "memory");
+}
 __device__ __forceinline__ void lds_dma4(const void* base, uint32_t byte_off, uint32_t lds)
 {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" :: "s"(lds), "v"(byte_off), "s"(base) : "memory");
@@ -264,12 +270,21 @@ __host__ __device__ constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4)
 // ring registers free of the zero-fill writes that would otherwise have to wait for the
 // loads still in flight.
 template <typename S>
-__device__ __forceinline__ void load_block(const char* src, int valid_chunks, u32x4 (&regs)[S::nld])
+__device__ __forceinline__ void load_block(const char* src, int valid_chunks, u32x4 (&regs)[S::nld], bool once)
 {
+    // (once: nobody else reads these rows: non-temporal loads, so that they do not displace shared rows in the L2)
+    if (once) {
 #pragma unroll
-    for (int m = 0; m < S::nld; m++) {
-        int c = min((int)threadIdx.x + S::threads * m, valid_chunks - 1);
-        regs[m] = *(const u32x4*)(src + (size_t)c * 16);
+        for (int m = 0; m < S::nld; m++) {
+            int c = min((int)threadIdx.x + S::threads * m, valid_chunks - 1);
+            regs[m] = __builtin_nontemporal_load((const u32x4*)(src + (size_t)c * 16));
+        }
+    } else {
+#pragma unroll
+        for (int m = 0; m < S::nld; m++) {
+            int c = min((int)threadIdx.x + S::threads * m, valid_chunks - 1);
+            regs[m] = *(const u32x4*)(src + (size_t)c * 16);
+        }
     }
 }
 
@@ -551,6 +566,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
         //
         // direct: block blk -> buffer buf, straight from HBM; the squared norms of its rows go
         // to a place of this wave's own (each wave fetches its own copy: 64 bytes)
+        const bool stream_once = !a.dense && w <= S::cw;   // the only work item that reads these rows
         auto fill_direct = [&](int blk, int buf) __attribute__((always_inline)) {
             const int bl = min(blk, nblk - 1);
             const int valid = min(nrows - bl * kBlockRows, kBlockRows);
@@ -559,8 +575,13 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
                 const char* bsrc = (pl == 0 ? src : src_lo) + (size_t)bl * kBlockRows * S::rowb;
                 const uint32_t dst = lds_addr(stage) + buf * S::buf_bytes + pl * S::plane_bytes + wave * 1024;
                 if (valid == kBlockRows) {
+                    if (stream_once) {
 #pragma unroll
-                    for (int m = 0; m < NLD; m++) lds_dma16(bsrc, goff[m], dst + m * S::nfw * 1024);
+                        for (int m = 0; m < NLD; m++) lds_dma16_nt(bsrc, goff[m], dst + m * S::nfw * 1024);
+                    } else {
+#pragma unroll
+                        for (int m = 0; m < NLD; m++) lds_dma16(bsrc, goff[m], dst + m * S::nfw * 1024);
+                    }
                 } else {
                     // ragged last block: rows past the end repeat the last valid one (their scores
                     // are masked out of the selection)
@@ -593,7 +614,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
         if constexpr (S::direct) {
             for (int i = 0; i < D; i++) fill_direct(i, i);
         } else {
-            load_block<S>(block_src(0), block_chunks(0), ring[0]);
+            load_block<S>(block_src(0), block_chunks(0), ring[0], stream_once);
             nring[0] = load_norm(0);
         }
 
@@ -644,7 +665,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
             nstage[threadIdx.x & (kBlockRows - 1)] = nring[0];      // (same value from several threads)
             static_for<PF>([&](auto pc) __attribute__((always_inline)) {
                 constexpr int slot = (decltype(pc)::value + 1) % PF;
-                load_block<S>(block_src(decltype(pc)::value + 1), block_chunks(decltype(pc)::value + 1), ring[slot]);
+                load_block<S>(block_src(decltype(pc)::value + 1), block_chunks(decltype(pc)::value + 1), ring[slot], stream_once);
                 nring[slot] = load_norm(decltype(pc)::value + 1);
             });
         } else {
@@ -861,7 +882,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_scan(ScanArgs a)
             constexpr int pn = (p + 1) % PF;
             stage_block<DT, S>(stage + (bi ^ 1) * S::buf_bytes, ring[pn]);
             nstage[(bi ^ 1) * kBlockRows + (threadIdx.x & (kBlockRows - 1))] = nring[pn];
-            load_block<S>(block_src(blk + 1 + PF), block_chunks(blk + 1 + PF), ring[pn]);
+            load_block<S>(block_src(blk + 1 + PF), block_chunks(blk + 1 + PF), ring[pn], stream_once);
             nring[pn] = load_norm(blk + 1 + PF);
             if (live && nact > 0) {
                 const char* cur = stage + bi * S::buf_bytes;
